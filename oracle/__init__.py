@@ -1,0 +1,187 @@
+"""ctypes access to the fp64 CPU oracle (oracle/chebykan_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg.  The GPU library never imports or links this.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "chebykan_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib: Optional[ctypes.CDLL] = None
+
+MAX_DEGREE = 64
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (-O2, OpenMP, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-ffp-contract=off", "-o", tmp, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int64)
+        i64 = ctypes.c_int64
+        lib.oracle_cheb_T.argtypes = [ctypes.c_double, ctypes.c_int, dp]
+        lib.oracle_cheb_T.restype = None
+        lib.oracle_cheb_T_trig.argtypes = [ctypes.c_double, ctypes.c_int, dp]
+        lib.oracle_cheb_T_trig.restype = None
+        lib.oracle_cheb_dT.argtypes = [ctypes.c_double, ctypes.c_int, dp]
+        lib.oracle_cheb_dT.restype = None
+        lib.oracle_num_threads.argtypes = []
+        lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_forward.argtypes = [dp, dp, dp, i64, i64, i64, ctypes.c_int]
+        lib.oracle_forward.restype = ctypes.c_int
+        lib.oracle_backward.argtypes = [dp, dp, dp, dp, dp, i64, i64, i64, ctypes.c_int]
+        lib.oracle_backward.restype = ctypes.c_int
+        lib.oracle_forward_at.argtypes = [dp, dp, ip, ip, i64, dp, i64, i64, i64, ctypes.c_int]
+        lib.oracle_forward_at.restype = ctypes.c_int
+        lib.oracle_dx_at.argtypes = [dp, dp, dp, ip, ip, i64, dp, i64, i64, i64, ctypes.c_int]
+        lib.oracle_dx_at.restype = ctypes.c_int
+        lib.oracle_dC_at.argtypes = [dp, dp, ip, ip, ip, i64, dp, i64, i64, i64, ctypes.c_int]
+        lib.oracle_dC_at.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.float64)
+
+
+def _i64(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.int64)
+
+
+def _dp(a: Optional[np.ndarray]):
+    if a is None:
+        return ctypes.POINTER(ctypes.c_double)()
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _ip(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def cheb_T(u: float, degree: int) -> np.ndarray:
+    out = np.zeros(degree + 1)
+    _load().oracle_cheb_T(float(u), int(degree), _dp(out))
+    return out
+
+
+def cheb_T_trig(u: float, degree: int) -> np.ndarray:
+    out = np.zeros(degree + 1)
+    _load().oracle_cheb_T_trig(float(u), int(degree), _dp(out))
+    return out
+
+
+def cheb_dT(u: float, degree: int) -> np.ndarray:
+    out = np.zeros(degree + 1)
+    _load().oracle_cheb_dT(float(u), int(degree), _dp(out))
+    return out
+
+
+def _check_shapes(x, C, dy=None) -> Tuple[int, int, int, int]:
+    B, I = x.shape
+    I2, O, K = C.shape
+    if I2 != I:
+        raise ValueError("C.shape[0] must equal x.shape[1]")
+    if dy is not None and dy.shape != (B, O):
+        raise ValueError("dy must be [batch, out]")
+    if K - 1 > MAX_DEGREE:
+        raise ValueError("degree above oracle maximum")
+    return B, I, O, K - 1
+
+
+def forward(x, C) -> np.ndarray:
+    """y[B,O] in fp64 from x[B,I], C[I,O,d+1] (any float dtype, promoted exactly)."""
+    x, C = _f64(x), _f64(C)
+    B, I, O, d = _check_shapes(x, C)
+    y = np.empty((B, O), dtype=np.float64)
+    rc = _load().oracle_forward(_dp(x), _dp(C), _dp(y), B, I, O, d)
+    assert rc == 0
+    return y
+
+
+def backward(x, C, dy, need_dx: bool = True, need_dC: bool = True):
+    """(dx[B,I], dC[I,O,d+1]) in fp64; an unrequested output is None."""
+    x, C, dy = _f64(x), _f64(C), _f64(dy)
+    B, I, O, d = _check_shapes(x, C, dy)
+    dx = np.empty((B, I), dtype=np.float64) if need_dx else None
+    dC = np.empty((I, O, d + 1), dtype=np.float64) if need_dC else None
+    rc = _load().oracle_backward(_dp(x), _dp(C), _dp(dy), _dp(dx), _dp(dC), B, I, O, d)
+    assert rc == 0
+    return dx, dC
+
+
+def forward_at(x, C, bs, os_) -> np.ndarray:
+    x, C = _f64(x), _f64(C)
+    B, I, O, d = _check_shapes(x, C)
+    bs, os_ = _i64(bs), _i64(os_)
+    assert bs.shape == os_.shape and bs.ndim == 1
+    assert bs.size == 0 or (bs.min() >= 0 and bs.max() < B and os_.min() >= 0 and os_.max() < O)
+    out = np.empty(bs.size, dtype=np.float64)
+    rc = _load().oracle_forward_at(_dp(x), _dp(C), _ip(bs), _ip(os_), bs.size, _dp(out), B, I, O, d)
+    assert rc == 0
+    return out
+
+
+def dx_at(x, C, dy, bs, is_) -> np.ndarray:
+    x, C, dy = _f64(x), _f64(C), _f64(dy)
+    B, I, O, d = _check_shapes(x, C, dy)
+    bs, is_ = _i64(bs), _i64(is_)
+    assert bs.shape == is_.shape and bs.ndim == 1
+    assert bs.size == 0 or (bs.min() >= 0 and bs.max() < B and is_.min() >= 0 and is_.max() < I)
+    out = np.empty(bs.size, dtype=np.float64)
+    rc = _load().oracle_dx_at(_dp(x), _dp(C), _dp(dy), _ip(bs), _ip(is_), bs.size, _dp(out), B, I, O, d)
+    assert rc == 0
+    return out
+
+
+def dC_at(x, dy, degree: int, is_, os_, ks) -> np.ndarray:
+    x, dy = _f64(x), _f64(dy)
+    B, I = x.shape
+    O = dy.shape[1]
+    assert dy.shape[0] == B
+    is_, os_, ks = _i64(is_), _i64(os_), _i64(ks)
+    assert is_.shape == os_.shape == ks.shape and is_.ndim == 1
+    assert is_.size == 0 or (is_.min() >= 0 and is_.max() < I and os_.min() >= 0 and os_.max() < O
+                             and ks.min() >= 0 and ks.max() <= degree)
+    out = np.empty(is_.size, dtype=np.float64)
+    rc = _load().oracle_dC_at(_dp(x), _dp(dy), _ip(is_), _ip(os_), _ip(ks), is_.size, _dp(out),
+                              B, I, O, int(degree))
+    assert rc == 0
+    return out
+
+
+def rel_err(got, want) -> float:
+    """max |got - want| / RMS(want): the error measure the parity bar is stated in."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    if want.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(want * want)))
+    diff = float(np.max(np.abs(got - want)))
+    if rms == 0.0:
+        return 0.0 if diff == 0.0 else float("inf")
+    return diff / rms
