@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused Chebyshev-KAN forward + backward pass on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input:
+forward through every layer of the workload's stack, then backward (dx and dC)
+through every layer in reverse, all enqueued through the C ABI on one stream.
+
+Prints ONE JSON line.  `value` is rows per second of the whole job, inputs
+resident in HBM.  `roofline` describes the dominant kernel call, timed with
+events on the launch stream in a second pass over the same steps (so the event
+records do not perturb `value`).  `cpu_baseline` is the fp64 CPU oracle timed on
+this machine's host cores on a bounded row sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F32_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--rotate", type=int, default=4,
+                    help="number of distinct (x, dy) input sets cycled through, so inputs are not cache-resident")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--family", type=int, default=0, help="kernel family override (0 auto)")
+    return ap.parse_args()
+
+
+class Stack:
+    """Device buffers and the launch sequence of one workload."""
+
+    def __init__(self, w, rotate, torch, binding, wl):
+        self.w, self.torch, self.binding = w, torch, binding
+        B = w.batch
+        self.B = B
+        self.layers = w.layers
+        self.d = w.degree
+        x0, Cs, dy_last = wl.workload_inputs(w)
+        self.x0_sets = [torch.from_numpy(x0).cuda()]
+        self.dy_sets = [torch.from_numpy(dy_last).cuda()]
+        for r in range(1, rotate):
+            self.x0_sets.append(torch.from_numpy(
+                wl.make_x(B, w.widths[0], wl.tensor_seed(w.index, 0, "x") + 100000 * r, w.x_mean, w.x_std)).cuda())
+            self.dy_sets.append(torch.from_numpy(
+                wl.make_dy(B, w.widths[-1], wl.tensor_seed(w.index, len(self.layers) - 1, "dy") + 100000 * r)).cuda())
+        self.C = [torch.from_numpy(c).cuda() for c in Cs]
+        self.y = [torch.empty((B, o), device="cuda") for (_, o) in self.layers]
+        self.dx = [torch.empty((B, i), device="cuda") for (i, _) in self.layers]
+        self.dC = [torch.empty_like(c) for c in self.C]
+        self.ws = [binding.alloc_workspace(B, i, o, self.d) for (i, o) in self.layers]
+        self.stream = torch.cuda.Stream()
+
+    def calls(self, step):
+        """The ABI calls of one step, in order: (tag, layer, thunk)."""
+        b, n = self.binding, len(self.layers)
+        x0 = self.x0_sets[step % len(self.x0_sets)]
+        dyl = self.dy_sets[step % len(self.dy_sets)]
+        s = self.stream
+        out = []
+        for l in range(n):
+            xin = x0 if l == 0 else self.y[l - 1]
+            out.append(("fwd", l, lambda l=l, xin=xin: b.chebykan_forward(xin, self.C[l], self.y[l], self.ws[l], s)))
+        for l in reversed(range(n)):
+            xin = x0 if l == 0 else self.y[l - 1]
+            dy = dyl if l == n - 1 else self.dx[l + 1]
+            out.append(("dx", l, lambda l=l, xin=xin, dy=dy:
+                        b.chebykan_backward(xin, self.C[l], dy, self.dx[l], None, self.ws[l], s)))
+            out.append(("dC", l, lambda l=l, xin=xin, dy=dy:
+                        b.chebykan_backward(xin, self.C[l], dy, None, self.dC[l], self.ws[l], s)))
+        return out
+
+    def step_fused_calls(self, step):
+        """One step as a user would issue it: one forward and one backward call per layer."""
+        b, n = self.binding, len(self.layers)
+        x0 = self.x0_sets[step % len(self.x0_sets)]
+        dyl = self.dy_sets[step % len(self.dy_sets)]
+        s = self.stream
+        for l in range(n):
+            xin = x0 if l == 0 else self.y[l - 1]
+            b.chebykan_forward(xin, self.C[l], self.y[l], self.ws[l], s)
+        for l in reversed(range(n)):
+            xin = x0 if l == 0 else self.y[l - 1]
+            dy = dyl if l == n - 1 else self.dx[l + 1]
+            b.chebykan_backward(xin, self.C[l], dy, self.dx[l], self.dC[l], self.ws[l], s)
+
+
+def call_work(tag, B, I, O, d):
+    """Algorithmic flops and HBM bytes of one call (fp32)."""
+    K = d + 1
+    if tag == "fwd":
+        return 2 * B * I * O * K, 4 * (B * I + I * O * K + B * O)
+    if tag == "dx":
+        return 2 * B * I * O * d, 4 * (B * I + I * O * K + B * O + B * I)
+    return 2 * B * I * O * K, 4 * (B * I + B * O + I * O * K)
+
+
+def cpu_baseline(w, wl, target_seconds):
+    """Time the fp64 oracle on the host cores over a bounded row sample of the workload."""
+    import oracle
+    flops_per_row = sum(wl.layer_flops(1, i, o, w.degree) for (i, o) in w.layers)
+    # plain loops reach roughly 0.5 GFLOP/s per thread; aim for target_seconds
+    threads = oracle.num_threads()
+    rows = int(min(w.batch, max(64, target_seconds * 0.5e9 * threads / flops_per_row)))
+    x0, Cs, dy_last = wl.workload_inputs(w, batch=rows)
+    t0 = time.perf_counter()
+    xs = [x0.astype(np.float64)]
+    for C in Cs:
+        xs.append(oracle.forward(xs[-1], C))
+    dy = dy_last.astype(np.float64)
+    for l in reversed(range(len(Cs))):
+        dx, dC = oracle.backward(xs[l], Cs[l], dy)
+        dy = dx
+    dt = time.perf_counter() - t0
+    return {"value": rows / dt, "unit": "samples/s", "cores": threads, "kind": "oracle",
+            "sample": "%d of %d rows of workload %s, full stack fwd+bwd in fp64, %.2f s" % (rows, w.batch, w.name, dt)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus %d refused)" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2511_14852_amd import binding, workloads as wl
+
+    if not torch.cuda.is_available():
+        raise RuntimeError("bench.py needs a GPU; there is no CPU fallback")
+    binding.load()
+    binding.chebykan_set_kernel_family(args.family)
+    w = wl.WORKLOADS[args.workload]
+    st = Stack(w, max(1, args.rotate), torch, binding, wl)
+    B = w.batch
+
+    # ---- throughput: W warm-up steps, then exactly K timed steps
+    for k in range(args.warmup):
+        st.step_fused_calls(k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        st.step_fused_calls(k)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    # ---- per-call durations: the same steps again with events on the launch stream
+    n_calls = len(st.calls(0))
+    ksteps = min(args.steps, 50)
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_calls)]
+           for _ in range(ksteps)]
+    for k in range(ksteps):
+        for c, (tag, l, thunk) in enumerate(st.calls(k)):
+            evs[k][c][0].record(st.stream)
+            thunk()
+            evs[k][c][1].record(st.stream)
+    torch.cuda.synchronize()
+    per_call = []
+    for c, (tag, l, _) in enumerate(st.calls(0)):
+        ms = float(np.mean([evs[k][c][0].elapsed_time(evs[k][c][1]) for k in range(ksteps)]))
+        I, O = w.layers[l]
+        fl, by = call_work(tag, B, I, O, w.degree)
+        per_call.append({"call": tag, "layer": l, "in": I, "out": O, "us": round(ms * 1e3, 2),
+                         "tflops": round(fl / (ms * 1e-3) / 1e12, 3), "gbs": round(by / (ms * 1e-3) / 1e9, 1),
+                         "mfma_frac": round(fl / (ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS, 4),
+                         "hbm_frac": round(by / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)})
+    dom = max(per_call, key=lambda r: r["us"])
+    I, O = dom["in"], dom["out"]
+    fl, by = call_work(dom["call"], B, I, O, w.degree)
+    t_mfma, t_hbm = fl / (PEAK_MFMA_F32_TFLOPS * 1e12), by / (PEAK_HBM_GBS * 1e9)
+    if t_mfma >= t_hbm:
+        roof = {"bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(dom["tflops"] / PEAK_MFMA_F32_TFLOPS, 4)}
+    else:
+        roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(dom["gbs"] / PEAK_HBM_GBS, 4)}
+    roof["traffic"] = None
+    roof["kernel"] = "%s layer %d (%d->%d)" % (dom["call"], dom["layer"], I, O)
+    roof["us"] = dom["us"]
+
+    total_flops = sum(wl.layer_flops(B, i, o, w.degree) for (i, o) in w.layers)
+    total_bytes = sum(wl.layer_bytes(B, i, o, w.degree) for (i, o) in w.layers)
+    line = {
+        "metric": "Cheby-KAN fwd+bwd samples/s", "value": B / (ms_per_step * 1e-3), "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %s, batch %d, widths %s, degree %d" % (
+            w.name, w.note, B, "->".join(map(str, w.widths)), w.degree), "input_sets_rotated": len(st.x0_sets)},
+        "tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
+        "algorithmic_gbs": total_bytes / (ms_per_step * 1e-3) / 1e9,
+        "mfma_frac": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS,
+        "hbm_frac": total_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "roofline": roof,
+        "calls": per_call,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, wl, args.cpu_seconds)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

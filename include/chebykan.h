@@ -1,0 +1,113 @@
+/*
+ * chebykan.h - C ABI of the fused Chebyshev-KAN layer for AMD MI355X (gfx950).
+ *
+ * One layer maps x[batch,in] to y[batch,out] through per-edge Chebyshev
+ * expansions of tanh(x) (paper Sec. 2.2: Eq. 2 for the basis, Eq. 3 and the
+ * Fig. 3 caption for the contraction; Alg. 1 for forward, Alg. 2 for backward):
+ *
+ *   u[b,i]    = tanh(x[b,i])
+ *   T_0 = 1, T_1 = u, T_{k+1} = 2 u T_k - T_{k-1}
+ *   y[b,o]    = sum_i sum_{k=0..degree} C[i,o,k] * T_k(u[b,i])
+ *   dC[i,o,k] = sum_b T_k(u[b,i]) * dy[b,o]
+ *   dx[b,i]   = (1 - u^2) * sum_o dy[b,o] * sum_{k=1..degree} C[i,o,k] * T_k'(u)
+ *
+ * There is no bias term.  dx is the gradient with respect to the raw input, so
+ * it carries the tanh derivative.  The basis and its derivative are evaluated
+ * exactly (three-term recurrences), not by table interpolation.
+ *
+ * Conventions common to every entry point
+ *  - All tensor pointers are DEVICE pointers owned by the caller, fp32,
+ *    row-major and contiguous, at least 4-byte aligned (16-byte alignment of
+ *    the base pointers enables the vectorised paths):
+ *        x  [batch, in]      C  [in, out, degree+1]   (the paper's original
+ *        y  [batch, out]     dC [in, out, degree+1]    coefficient layout,
+ *        dy [batch, out]     dx [batch, in]            Sec. 4.5.1)
+ *  - Outputs are OVERWRITTEN (never accumulated into); inputs are not modified;
+ *    outputs must not alias inputs.
+ *  - `workspace` is device memory owned by the caller, at least
+ *    chebykan_workspace_bytes(...) bytes, 256-byte aligned; it may be NULL when
+ *    that size is 0.  Its contents are scratch: undefined before and after.
+ *  - `stream` is a hipStream_t passed as an opaque pointer (NULL = the null
+ *    stream).  All work is enqueued on it; the call returns without
+ *    synchronising.  The library allocates nothing and frees nothing.
+ *  - Results are bitwise reproducible from run to run for fixed shapes: every
+ *    reduction has a fixed order and no floating-point atomics are used.
+ *  - batch == 0 is a successful no-op for forward and dx; dC is then zeroed.
+ *  - Errors are reported by return code only.  On any error nothing has been
+ *    enqueued.
+ */
+#ifndef CHEBYKAN_H
+#define CHEBYKAN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CHEBYKAN_MAX_DEGREE 32
+
+typedef enum chebykan_status {
+    CHEBYKAN_OK = 0,
+    CHEBYKAN_ERR_NULL = -1,      /* a required pointer is NULL                         */
+    CHEBYKAN_ERR_SHAPE = -2,     /* batch < 0, in/out <= 0, degree < 0 or > MAX_DEGREE,
+                                    or a tensor would exceed 2^31-1 rows*cols limits   */
+    CHEBYKAN_ERR_WORKSPACE = -3, /* workspace NULL or smaller than required            */
+    CHEBYKAN_ERR_DEVICE = -4,    /* current device is not a gfx950 part                */
+    CHEBYKAN_ERR_LAUNCH = -5     /* HIP reported an error when launching               */
+} chebykan_status;
+
+typedef void *chebykan_stream_t; /* a hipStream_t */
+
+/* pass selector for chebykan_workspace_bytes */
+#define CHEBYKAN_PASS_FORWARD 0
+#define CHEBYKAN_PASS_BACKWARD 1
+
+/*
+ * Bytes of workspace the given call needs (0 is possible).  Host-only, no GPU
+ * access.  Returns 0 for invalid shapes (the compute call will report them).
+ * Backward needs room for the per-slice partial coefficient gradients of the
+ * deterministic two-stage reduction (the idea of the paper's Sec. 4.4 applied
+ * to the batch axis).
+ */
+size_t chebykan_workspace_bytes(int64_t batch, int in, int out, int degree, int pass);
+
+/*
+ * Forward pass (paper Alg. 1 as a function; Eq. 2-3): writes y[batch,out].
+ */
+chebykan_status chebykan_forward(const float *x, const float *C, float *y,
+                                 int64_t batch, int in, int out, int degree,
+                                 void *workspace, size_t workspace_bytes,
+                                 chebykan_stream_t stream);
+
+/*
+ * Backward pass (paper Alg. 2 as a function): writes dx[batch,in] and
+ * dC[in,out,degree+1].  Either output pointer may be NULL to skip it (not both
+ * required).  Nothing is kept from the forward call: u, T_k and T_k' are
+ * regenerated from x.
+ */
+chebykan_status chebykan_backward(const float *x, const float *C, const float *dy,
+                                  float *dx, float *dC,
+                                  int64_t batch, int in, int out, int degree,
+                                  void *workspace, size_t workspace_bytes,
+                                  chebykan_stream_t stream);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *chebykan_status_string(chebykan_status status);
+
+/*
+ * Kernel-family override for tests and tuning: 0 = automatic choice (default),
+ * 1 = force the generic any-degree kernels, 2 = force the MFMA kernels where
+ * the shape supports them.  Process-wide, not thread-safe; returns the previous
+ * value.  Not part of the paper's method.
+ */
+int chebykan_set_kernel_family(int family);
+
+/* Library/ABI version: major*1000 + minor. */
+int chebykan_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHEBYKAN_H */

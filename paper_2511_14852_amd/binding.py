@@ -1,0 +1,168 @@
+"""ctypes binding of libchebykan.so: argument marshalling only.
+
+Every step of the layer runs inside the HIP library; PyTorch appears here only
+as the owner of device memory and streams.  There is no CPU fallback: if the
+library is missing or no gfx950 device is current, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+from . import build as _build
+
+CHEBYKAN_OK = 0
+CHEBYKAN_ERR_NULL = -1
+CHEBYKAN_ERR_SHAPE = -2
+CHEBYKAN_ERR_WORKSPACE = -3
+CHEBYKAN_ERR_DEVICE = -4
+CHEBYKAN_ERR_LAUNCH = -5
+CHEBYKAN_PASS_FORWARD = 0
+CHEBYKAN_PASS_BACKWARD = 1
+CHEBYKAN_MAX_DEGREE = 32
+
+EXPORTS = (
+    "chebykan_workspace_bytes", "chebykan_forward", "chebykan_backward",
+    "chebykan_status_string", "chebykan_set_kernel_family", "chebykan_version",
+)
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+class ChebykanError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__("%s failed: %s (status %d)" % (where, chebykan_status_string(status), status))
+
+
+def library_path() -> str:
+    return _build.LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Load the built library; build it first only if no built library exists."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB_PATH):
+            _build.build_library()
+        lib = ctypes.CDLL(_build.LIB_PATH)
+        vp, i64, ci, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+        lib.chebykan_workspace_bytes.argtypes = [i64, ci, ci, ci, ci]
+        lib.chebykan_workspace_bytes.restype = sz
+        lib.chebykan_forward.argtypes = [vp, vp, vp, i64, ci, ci, ci, vp, sz, vp]
+        lib.chebykan_forward.restype = ci
+        lib.chebykan_backward.argtypes = [vp, vp, vp, vp, vp, i64, ci, ci, ci, vp, sz, vp]
+        lib.chebykan_backward.restype = ci
+        lib.chebykan_status_string.argtypes = [ci]
+        lib.chebykan_status_string.restype = ctypes.c_char_p
+        lib.chebykan_set_kernel_family.argtypes = [ci]
+        lib.chebykan_set_kernel_family.restype = ci
+        lib.chebykan_version.argtypes = []
+        lib.chebykan_version.restype = ci
+        _lib = lib
+    return _lib
+
+
+# ---------------------------------------------------------------- raw calls
+# Pointers are plain integers (device addresses) or None; status is returned.
+
+def raw_forward(x_ptr, C_ptr, y_ptr, batch, n_in, n_out, degree, ws_ptr=None, ws_bytes=0, stream=None) -> int:
+    return int(load().chebykan_forward(x_ptr, C_ptr, y_ptr, batch, n_in, n_out, degree, ws_ptr, ws_bytes, stream))
+
+
+def raw_backward(x_ptr, C_ptr, dy_ptr, dx_ptr, dC_ptr, batch, n_in, n_out, degree, ws_ptr=None, ws_bytes=0,
+                 stream=None) -> int:
+    return int(load().chebykan_backward(x_ptr, C_ptr, dy_ptr, dx_ptr, dC_ptr, batch, n_in, n_out, degree,
+                                        ws_ptr, ws_bytes, stream))
+
+
+def chebykan_status_string(status: int) -> str:
+    return load().chebykan_status_string(int(status)).decode()
+
+
+def chebykan_workspace_bytes(batch: int, n_in: int, n_out: int, degree: int, which_pass: int) -> int:
+    return int(load().chebykan_workspace_bytes(batch, n_in, n_out, degree, which_pass))
+
+
+def chebykan_set_kernel_family(family: int) -> int:
+    return int(load().chebykan_set_kernel_family(int(family)))
+
+
+def chebykan_version() -> int:
+    return int(load().chebykan_version())
+
+
+# ------------------------------------------------------------ tensor calls
+
+def _check(t, name, shape=None):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != torch.float32 or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous fp32 tensor on the GPU" % name)
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s has shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
+
+
+def _stream_ptr(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _ws(workspace, need):
+    if need == 0:
+        return None, 0
+    if workspace is None:
+        raise ValueError("this call needs a workspace of %d bytes" % need)
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace must be a contiguous GPU tensor")
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def chebykan_forward(x, C, y, workspace=None, stream=None) -> None:
+    """Enqueue y = layer(x; C) on the stream (torch's current stream by default)."""
+    _check(x, "x")
+    B, I = x.shape
+    _check(C, "C")
+    if C.dim() != 3 or C.shape[0] != I:
+        raise ValueError("C must be [in, out, degree+1]")
+    O, K = int(C.shape[1]), int(C.shape[2])
+    _check(y, "y", (B, O))
+    need = chebykan_workspace_bytes(B, I, O, K - 1, CHEBYKAN_PASS_FORWARD)
+    ws_ptr, ws_bytes = _ws(workspace, need)
+    st = raw_forward(x.data_ptr(), C.data_ptr(), y.data_ptr(), B, I, O, K - 1, ws_ptr, ws_bytes,
+                     _stream_ptr(stream))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_forward")
+
+
+def chebykan_backward(x, C, dy, dx, dC, workspace=None, stream=None) -> None:
+    """Enqueue dx and/or dC (pass None to skip one) on the stream."""
+    _check(x, "x")
+    B, I = x.shape
+    _check(C, "C")
+    if C.dim() != 3 or C.shape[0] != I:
+        raise ValueError("C must be [in, out, degree+1]")
+    O, K = int(C.shape[1]), int(C.shape[2])
+    _check(dy, "dy", (B, O))
+    if dx is not None:
+        _check(dx, "dx", (B, I))
+    if dC is not None:
+        _check(dC, "dC", (I, O, K))
+    need = chebykan_workspace_bytes(B, I, O, K - 1, CHEBYKAN_PASS_BACKWARD)
+    ws_ptr, ws_bytes = _ws(workspace, need)
+    st = raw_backward(x.data_ptr(), C.data_ptr(), dy.data_ptr(),
+                      None if dx is None else dx.data_ptr(), None if dC is None else dC.data_ptr(),
+                      B, I, O, K - 1, ws_ptr, ws_bytes, _stream_ptr(stream))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_backward")
+
+
+def alloc_workspace(batch: int, n_in: int, n_out: int, degree: int, device="cuda"):
+    """A torch byte tensor large enough for both passes of one layer (None if none is needed)."""
+    import torch
+    need = max(chebykan_workspace_bytes(batch, n_in, n_out, degree, CHEBYKAN_PASS_FORWARD),
+               chebykan_workspace_bytes(batch, n_in, n_out, degree, CHEBYKAN_PASS_BACKWARD))
+    if need == 0:
+        return None
+    return torch.empty(need, dtype=torch.uint8, device=device)

@@ -1,0 +1,150 @@
+// C ABI of the library: argument validation, kernel choice, launches.
+// See include/chebykan.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+#include <string.h>
+
+#include "../../include/chebykan.h"
+#include "dispatch.h"
+#include "generic_kernels.h"
+
+namespace chebykan {
+
+static int g_family = 0;  // 0 auto, 1 generic, 2 mfma
+
+// Is the current device a gfx950 part?  Cached per device ordinal.
+static chebykan_status check_device()
+{
+    static int verdict[64];  // 0 unknown, 1 ok, -1 wrong arch
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) {
+        (void)hipGetLastError();
+        return CHEBYKAN_ERR_DEVICE;
+    }
+    if (dev < 64 && verdict[dev] != 0) return verdict[dev] > 0 ? CHEBYKAN_OK : CHEBYKAN_ERR_DEVICE;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return CHEBYKAN_ERR_DEVICE;
+    }
+    const bool ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+    if (dev < 64) verdict[dev] = ok ? 1 : -1;
+    return ok ? CHEBYKAN_OK : CHEBYKAN_ERR_DEVICE;
+}
+
+static bool shape_ok(int64_t batch, int in, int out, int degree)
+{
+    if (batch < 0 || in <= 0 || out <= 0 || degree < 0 || degree > CHEBYKAN_MAX_DEGREE) return false;
+    const int64_t lim = (int64_t)1 << 40;  // element counts stay far inside int64
+    if (batch * in > lim || batch * out > lim) return false;
+    if ((int64_t)in * out * (degree + 1) > ((int64_t)1 << 31) - 1) return false;
+    if (batch > ((int64_t)1 << 31) - 1) return false;
+    return true;
+}
+
+static chebykan_status launch_status()
+{
+    return hipGetLastError() == hipSuccess ? CHEBYKAN_OK : CHEBYKAN_ERR_LAUNCH;
+}
+
+static void generic_forward(const float* x, const float* C, float* y, int64_t B, int I, int O, int d,
+                            hipStream_t s)
+{
+    dim3 block(64, 4), grid((unsigned)((B + 3) / 4), (unsigned)((O + 63) / 64));
+    hipLaunchKernelGGL(generic_forward_kernel, grid, block, 0, s, x, C, y, B, I, O, d);
+}
+
+static void generic_dx(const float* x, const float* C, const float* dy, float* dx, int64_t B, int I, int O,
+                       int d, hipStream_t s)
+{
+    dim3 block(64, 4), grid((unsigned)((B + 3) / 4), (unsigned)((I + 63) / 64));
+    hipLaunchKernelGGL(generic_dx_kernel, grid, block, 0, s, x, C, dy, dx, B, I, O, d);
+}
+
+static void generic_dC(const float* x, const float* dy, float* dC, int64_t B, int I, int O, int d,
+                       hipStream_t s)
+{
+    const int64_t n = (int64_t)I * O * (d + 1);
+    hipLaunchKernelGGL(generic_dC_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, dy, dC, B, I,
+                       O, d);
+}
+
+}  // namespace chebykan
+
+using namespace chebykan;
+
+extern "C" {
+
+int chebykan_version(void) { return 1000; }
+
+int chebykan_set_kernel_family(int family)
+{
+    const int prev = g_family;
+    if (family >= 0 && family <= 2) g_family = family;
+    return prev;
+}
+
+const char* chebykan_status_string(chebykan_status status)
+{
+    switch (status) {
+        case CHEBYKAN_OK: return "ok";
+        case CHEBYKAN_ERR_NULL: return "a required pointer is NULL";
+        case CHEBYKAN_ERR_SHAPE: return "invalid shape or degree";
+        case CHEBYKAN_ERR_WORKSPACE: return "workspace missing or too small";
+        case CHEBYKAN_ERR_DEVICE: return "no gfx950 device is current";
+        case CHEBYKAN_ERR_LAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+size_t chebykan_workspace_bytes(int64_t batch, int in, int out, int degree, int pass)
+{
+    if (!shape_ok(batch, in, out, degree)) return 0;
+    if (pass == CHEBYKAN_PASS_FORWARD) return forward_workspace_bytes(batch, in, out, degree);
+    if (pass == CHEBYKAN_PASS_BACKWARD) return backward_workspace_bytes(batch, in, out, degree);
+    return 0;
+}
+
+chebykan_status chebykan_forward(const float* x, const float* C, float* y, int64_t batch, int in, int out,
+                                 int degree, void* workspace, size_t workspace_bytes,
+                                 chebykan_stream_t stream)
+{
+    if (!x || !C || !y) return CHEBYKAN_ERR_NULL;
+    if (!shape_ok(batch, in, out, degree)) return CHEBYKAN_ERR_SHAPE;
+    const size_t need = forward_workspace_bytes(batch, in, out, degree);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
+    const chebykan_status dev = check_device();
+    if (dev != CHEBYKAN_OK) return dev;
+    if (batch == 0) return CHEBYKAN_OK;
+    hipStream_t s = (hipStream_t)stream;
+    (void)hipGetLastError();
+    if (g_family != 1 && mfma_forward(x, C, y, batch, in, out, degree, workspace, s)) return launch_status();
+    generic_forward(x, C, y, batch, in, out, degree, s);
+    return launch_status();
+}
+
+chebykan_status chebykan_backward(const float* x, const float* C, const float* dy, float* dx, float* dC,
+                                  int64_t batch, int in, int out, int degree, void* workspace,
+                                  size_t workspace_bytes, chebykan_stream_t stream)
+{
+    if (!x || !C || !dy) return CHEBYKAN_ERR_NULL;
+    if (!dx && !dC) return CHEBYKAN_ERR_NULL;
+    if (!shape_ok(batch, in, out, degree)) return CHEBYKAN_ERR_SHAPE;
+    const size_t need = backward_workspace_bytes(batch, in, out, degree);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
+    const chebykan_status dev = check_device();
+    if (dev != CHEBYKAN_OK) return dev;
+    hipStream_t s = (hipStream_t)stream;
+    (void)hipGetLastError();
+    if (dx && batch > 0) {
+        if (!(g_family != 1 && mfma_dx(x, C, dy, dx, batch, in, out, degree, workspace, s)))
+            generic_dx(x, C, dy, dx, batch, in, out, degree, s);
+    }
+    if (dC) {
+        // batch == 0 still defines dC (all zeros): the generic kernel's empty sum gives that.
+        if (!(g_family != 1 && batch > 0 && mfma_dC(x, dy, dC, batch, in, out, degree, workspace, s)))
+            generic_dC(x, dy, dC, batch, in, out, degree, s);
+    }
+    return launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,105 @@
+// Any-degree kernels: one thread per output element, exact recurrences, plain
+// fp32 VALU arithmetic.  They serve degrees and shapes the MFMA kernels are not
+// specialised for and give an on-device cross-check of those kernels.
+//
+// Every reduction runs in a fixed order inside one thread, with the running sum
+// folded into a second accumulator every FOLD terms so that long fp32 sums do
+// not lose accuracy.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "basis.h"
+
+namespace chebykan {
+
+constexpr int GENERIC_FOLD = 16;
+
+// y[b,o] = sum_i sum_k C[i,o,k] T_k(tanh x[b,i])          (paper Eq. 2-3, Alg. 1 inner loop)
+// block = (64 outputs, 4 rows); grid = (ceil(B/4), ceil(O/64)).
+__global__ void __launch_bounds__(256)
+generic_forward_kernel(const float* __restrict__ x, const float* __restrict__ C, float* __restrict__ y,
+                       int64_t B, int I, int O, int degree)
+{
+    const int o = blockIdx.y * 64 + threadIdx.x;
+    const int64_t b = (int64_t)blockIdx.x * 4 + threadIdx.y;
+    if (o >= O || b >= B) return;
+    const int K = degree + 1;
+    const float* xr = x + b * I;
+    float total = 0.0f, part = 0.0f;
+    for (int i = 0; i < I; ++i) {
+        const float u = normalise(xr[i]);
+        const float* c = C + ((int64_t)i * O + o) * K;
+        float t_prev = 1.0f, t_cur = u;
+        float acc = c[0];
+        for (int k = 1; k < K; ++k) {
+            acc = fmaf(c[k], t_cur, acc);
+            const float t_next = fmaf(2.0f * u, t_cur, -t_prev);
+            t_prev = t_cur;
+            t_cur = t_next;
+        }
+        part += acc;
+        if ((i % GENERIC_FOLD) == GENERIC_FOLD - 1) { total += part; part = 0.0f; }
+    }
+    y[b * O + o] = total + part;
+}
+
+// dx[b,i] = (1-u^2) sum_o dy[b,o] sum_{k>=1} C[i,o,k] T_k'(u)   (paper Alg. 2, x_grad)
+// block = (64 inputs, 4 rows); grid = (ceil(B/4), ceil(I/64)).
+__global__ void __launch_bounds__(256)
+generic_dx_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
+                  float* __restrict__ dx, int64_t B, int I, int O, int degree)
+{
+    const int i = blockIdx.y * 64 + threadIdx.x;
+    const int64_t b = (int64_t)blockIdx.x * 4 + threadIdx.y;
+    if (i >= I || b >= B) return;
+    const int K = degree + 1;
+    const float u = normalise(x[b * I + i]);
+    const float two_u = 2.0f * u;
+    const float* g = dy + b * O;
+    float total = 0.0f, part = 0.0f;
+    for (int o = 0; o < O; ++o) {
+        const float* c = C + ((int64_t)i * O + o) * K;
+        float U_prev = 0.0f, U_cur = 1.0f;   // U_{k-2}, U_{k-1}
+        float inner = 0.0f;
+        for (int k = 1; k < K; ++k) {
+            inner = fmaf(c[k], (float)k * U_cur, inner);
+            const float U_next = fmaf(two_u, U_cur, -U_prev);
+            U_prev = U_cur;
+            U_cur = U_next;
+        }
+        part = fmaf(g[o], inner, part);
+        if ((o % GENERIC_FOLD) == GENERIC_FOLD - 1) { total += part; part = 0.0f; }
+    }
+    dx[b * I + i] = tanh_slope(u) * (total + part);
+}
+
+// dC[i,o,k] = sum_b T_k(tanh x[b,i]) dy[b,o]                   (paper Alg. 2, coeff_grad)
+// one thread per coefficient, sequential over the batch in a fixed order.
+__global__ void __launch_bounds__(256)
+generic_dC_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ dC,
+                  int64_t B, int I, int O, int degree)
+{
+    const int K = degree + 1;
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (int64_t)I * O * K) return;
+    const int k = (int)(e % K);
+    const int o = (int)((e / K) % O);
+    const int i = (int)(e / ((int64_t)K * O));
+    float total = 0.0f, mid = 0.0f, part = 0.0f;
+    for (int64_t b = 0; b < B; ++b) {
+        const float u = normalise(x[b * I + i]);
+        float t_prev = 1.0f, t_cur = (k == 0) ? 1.0f : u;
+        for (int n = 1; n < k; ++n) {
+            const float t_next = fmaf(2.0f * u, t_cur, -t_prev);
+            t_prev = t_cur;
+            t_cur = t_next;
+        }
+        part = fmaf(t_cur, dy[b * O + o], part);
+        if ((b % 64) == 63) { mid += part; part = 0.0f; }
+        if ((b % 4096) == 4095) { total += mid; mid = 0.0f; }
+    }
+    dC[e] = total + (mid + part);
+}
+
+}  // namespace chebykan

@@ -1,0 +1,91 @@
+"""Host-side checks of the C-ABI library that need no GPU: the library loads,
+exports every symbol the public header declares, and rejects bad arguments
+before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2511_14852_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    names = []
+    for fn in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if not fn.endswith(".h"):
+            continue
+        text = open(os.path.join(ROOT, "include", fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b(chebykan_[a-z_0-9]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    declared = _declared_functions()
+    assert set(binding.EXPORTS) == set(declared)
+    for name in declared:
+        assert hasattr(lib, name), name
+        assert ctypes.cast(getattr(lib, name), ctypes.c_void_p).value
+
+
+def test_version_and_status_strings():
+    assert binding.chebykan_version() >= 1000
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -5):
+        s = binding.chebykan_status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert "unknown" in binding.chebykan_status_string(-99)
+
+
+def test_argument_validation_happens_before_any_device_use():
+    P = 4096  # any non-null value: never dereferenced on these paths
+    assert binding.raw_forward(None, P, P, 4, 4, 4, 2) == binding.CHEBYKAN_ERR_NULL
+    assert binding.raw_forward(P, None, P, 4, 4, 4, 2) == binding.CHEBYKAN_ERR_NULL
+    assert binding.raw_forward(P, P, None, 4, 4, 4, 2) == binding.CHEBYKAN_ERR_NULL
+    assert binding.raw_forward(P, P, P, -1, 4, 4, 2) == binding.CHEBYKAN_ERR_SHAPE
+    assert binding.raw_forward(P, P, P, 4, 0, 4, 2) == binding.CHEBYKAN_ERR_SHAPE
+    assert binding.raw_forward(P, P, P, 4, 4, 0, 2) == binding.CHEBYKAN_ERR_SHAPE
+    assert binding.raw_forward(P, P, P, 4, 4, 4, -1) == binding.CHEBYKAN_ERR_SHAPE
+    assert binding.raw_forward(P, P, P, 4, 4, 4, binding.CHEBYKAN_MAX_DEGREE + 1) == binding.CHEBYKAN_ERR_SHAPE
+    assert binding.raw_forward(P, P, P, 4, 70000, 70000, 8) == binding.CHEBYKAN_ERR_SHAPE
+    assert binding.raw_backward(P, P, None, P, P, 4, 4, 4, 2) == binding.CHEBYKAN_ERR_NULL
+    assert binding.raw_backward(P, P, P, None, None, 4, 4, 4, 2) == binding.CHEBYKAN_ERR_NULL
+    assert binding.raw_backward(P, P, P, P, P, 4, 4, -3, 2) == binding.CHEBYKAN_ERR_SHAPE
+
+
+def test_workspace_query_is_host_only_and_checked():
+    P = 4096
+    assert binding.chebykan_workspace_bytes(-1, 4, 4, 2, 0) == 0
+    assert binding.chebykan_workspace_bytes(4, 4, 4, 2, 7) == 0
+    for (B, I, O, d) in [(256, 64, 64, 4), (65536, 64, 64, 6), (16384, 1024, 1024, 8), (65536, 64, 1, 6)]:
+        for which in (0, 1):
+            n = binding.chebykan_workspace_bytes(B, I, O, d, which)
+            assert 0 <= n < (2 << 30)
+            if n > 0:
+                if which == 0:
+                    assert binding.raw_forward(P, P, P, B, I, O, d, None, 0) == binding.CHEBYKAN_ERR_WORKSPACE
+                    assert binding.raw_forward(P, P, P, B, I, O, d, P, n - 1) == binding.CHEBYKAN_ERR_WORKSPACE
+                else:
+                    assert binding.raw_backward(P, P, P, P, P, B, I, O, d, None, 0) == binding.CHEBYKAN_ERR_WORKSPACE
+                    assert binding.raw_backward(P, P, P, P, P, B, I, O, d, P, n - 1) == binding.CHEBYKAN_ERR_WORKSPACE
+
+
+def test_kernel_family_switch_round_trips():
+    prev = binding.chebykan_set_kernel_family(1)
+    assert binding.chebykan_set_kernel_family(prev) == 1
+    assert binding.chebykan_set_kernel_family(99) == prev   # invalid value ignored
+    assert binding.chebykan_set_kernel_family(prev) == prev
+
+
+def test_no_device_is_reported_not_faked():
+    """Without a gfx950 device the library must refuse, not fall back to the CPU."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    P = 4096
+    assert binding.raw_forward(P, P, P, 4, 4, 4, 2) == binding.CHEBYKAN_ERR_DEVICE

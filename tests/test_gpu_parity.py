@@ -1,0 +1,228 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle.
+
+Bar: max |gpu - oracle| / RMS(oracle) <= 1e-5 for each of y, dx, dC (exact
+basis, fp32 arithmetic).  Small shapes are compared element by element; the
+full-size workloads are compared on sampled outputs that the oracle computes
+one by one, layer by layer on the GPU's own fp32 layer inputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_14852_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def gpu_layer(x, C, dy=None, family=0, need_dx=True, need_dC=True):
+    """Run forward (+ backward when dy is given) on the GPU; returns numpy arrays."""
+    B, I = x.shape
+    _, O, K = C.shape
+    d = K - 1
+    prev = binding.chebykan_set_kernel_family(family)
+    try:
+        xd, Cd = _dev(x), _dev(C)
+        ws = binding.alloc_workspace(B, I, O, d)
+        y = torch.full((B, O), float("nan"), device="cuda")
+        binding.chebykan_forward(xd, Cd, y, ws)
+        out = [y.cpu().numpy()]
+        if dy is not None:
+            dyd = _dev(dy)
+            dx = torch.full((B, I), float("nan"), device="cuda") if need_dx else None
+            dC = torch.full((I, O, K), float("nan"), device="cuda") if need_dC else None
+            binding.chebykan_backward(xd, Cd, dyd, dx, dC, ws)
+            out += [None if dx is None else dx.cpu().numpy(), None if dC is None else dC.cpu().numpy()]
+        torch.cuda.synchronize()
+    finally:
+        binding.chebykan_set_kernel_family(prev)
+    return out
+
+
+def _inputs(B, I, O, d, seed, x_mean=0.0, x_std=1.0):
+    x = wl.make_x(B, I, seed, x_mean, x_std)
+    C = wl.make_coeff(I, O, d, seed + 1)
+    dy = wl.make_dy(B, O, seed + 2)
+    return x, C, dy
+
+
+def _check_full(x, C, dy, family, label):
+    y, dx, dC = gpu_layer(x, C, dy, family)
+    y_ref = oracle.forward(x, C)
+    dx_ref, dC_ref = oracle.backward(x, C, dy)
+    errs = {"y": oracle.rel_err(y, y_ref), "dx": oracle.rel_err(dx, dx_ref), "dC": oracle.rel_err(dC, dC_ref)}
+    print("%s family=%d errs=%s" % (label, family, {k: "%.2e" % v for k, v in errs.items()}), flush=True)
+    for k, v in errs.items():
+        assert np.isfinite(v) and v <= TOL, (label, family, k, v)
+
+
+# shapes spanning several tiles with ragged tails in every dimension; the
+# degrees with specialised kernels and several without
+SMALL_SHAPES = [
+    (256, 64, 64, 4),      # the small configuration as is
+    (300, 70, 150, 8),
+    (513, 33, 129, 3),
+    (260, 257, 65, 5),
+    (1000, 8, 64, 6),
+    (777, 64, 1, 6),
+    (129, 130, 257, 6),
+    (64, 40, 256, 8),
+    (37, 5, 3, 2),
+    (130, 20, 70, 7),
+    (3, 1, 1, 1),
+    (50, 17, 9, 0),
+    (64, 24, 40, 15),
+    (32, 16, 48, 24),
+    (1, 64, 64, 4),
+]
+
+
+@pytest.mark.parametrize("shape", SMALL_SHAPES, ids=lambda s: "B%d_I%d_O%d_d%d" % s)
+@pytest.mark.parametrize("family", [0, 1], ids=["auto", "generic"])
+def test_small_shapes_elementwise(shape, family):
+    B, I, O, d = shape
+    x, C, dy = _inputs(B, I, O, d, seed=1000 + B + I + O + d)
+    _check_full(x, C, dy, family, "small %s" % (shape,))
+
+
+def test_audio_like_input_distribution_with_saturation():
+    """x ~ N(-2, 1.5^2) plus a few saturating values (|x| > 9 gives u = +-1 in fp32)."""
+    B, I, O, d = 400, 96, 80, 5
+    x, C, dy = _inputs(B, I, O, d, seed=77, x_mean=-2.0, x_std=1.5)
+    x[0, :8] = [12.0, -12.0, 30.0, -30.0, 9.5, -9.5, 0.0, -0.0]
+    _check_full(x, C, dy, 0, "audio-like")
+
+
+def test_degenerate_inputs():
+    B, I, O, d = 130, 12, 20, 4
+    x, C, dy = _inputs(B, I, O, d, seed=5)
+    Cz = np.zeros_like(C)
+    y, dx, dC = gpu_layer(x, Cz, dy)
+    assert np.all(y == 0.0) and np.all(dx == 0.0)
+    assert oracle.rel_err(dC, oracle.backward(x, Cz, dy, need_dx=False)[1]) <= TOL
+    dyh = np.zeros_like(dy)
+    dyh[7, 3] = 1.0
+    y, dx, dC = gpu_layer(x, C, dyh)
+    assert np.all(dx[np.arange(B) != 7] == 0.0)
+    assert np.all(dC[:, np.arange(O) != 3, :] == 0.0)
+    dx_ref, dC_ref = oracle.backward(x, C, dyh)
+    assert np.max(np.abs(dx - dx_ref)) <= 1e-5 * max(1.0, np.max(np.abs(dx_ref)))
+    assert np.max(np.abs(dC - dC_ref)) <= 1e-5
+
+
+def test_skipping_one_gradient_gives_the_same_other():
+    B, I, O, d = 200, 48, 72, 6
+    x, C, dy = _inputs(B, I, O, d, seed=9)
+    _, dx_a, dC_a = gpu_layer(x, C, dy)
+    _, dx_b, none_c = gpu_layer(x, C, dy, need_dC=False)
+    _, none_x, dC_b = gpu_layer(x, C, dy, need_dx=False)
+    assert none_c is None and none_x is None
+    assert np.array_equal(dx_a, dx_b) and np.array_equal(dC_a, dC_b)
+
+
+def test_bitwise_reproducible():
+    B, I, O, d = 2048, 64, 64, 6
+    x, C, dy = _inputs(B, I, O, d, seed=13)
+    a = gpu_layer(x, C, dy)
+    b = gpu_layer(x, C, dy)
+    for p, q in zip(a, b):
+        assert np.array_equal(p, q)
+
+
+def test_empty_batch_and_error_codes_on_device():
+    I, O, d = 8, 4, 3
+    C = _dev(wl.make_coeff(I, O, d, 1))
+    x = torch.empty((0, I), device="cuda")
+    y = torch.empty((0, O), device="cuda")
+    binding.chebykan_forward(x, C, y, binding.alloc_workspace(0, I, O, d))
+    dC = torch.full((I, O, d + 1), float("nan"), device="cuda")
+    binding.chebykan_backward(x, C, y, torch.empty((0, I), device="cuda"), dC, binding.alloc_workspace(0, I, O, d))
+    torch.cuda.synchronize()
+    assert torch.all(dC == 0).item()
+    with pytest.raises(binding.ChebykanError) as e:
+        st = binding.raw_forward(None, C.data_ptr(), C.data_ptr(), 4, I, O, d)
+        raise binding.ChebykanError(st, "chebykan_forward")
+    assert e.value.status == binding.CHEBYKAN_ERR_NULL
+
+
+def test_outputs_outside_the_tensor_are_untouched():
+    """Outputs live inside larger poisoned buffers; the guard bands must survive."""
+    B, I, O, d = 131, 67, 35, 5
+    x, C, dy = _inputs(B, I, O, d, seed=21)
+    xd, Cd, dyd = _dev(x), _dev(C), _dev(dy)
+    pad = 1024
+    sentinel = 12345.5
+
+    def guarded(n):
+        buf = torch.full((n + 2 * pad,), sentinel, device="cuda")
+        return buf, buf[pad:pad + n]
+
+    ybuf, yv = guarded(B * O)
+    dxbuf, dxv = guarded(B * I)
+    dCbuf, dCv = guarded(I * O * (d + 1))
+    ws = binding.alloc_workspace(B, I, O, d)
+    binding.chebykan_forward(xd, Cd, yv.view(B, O), ws)
+    binding.chebykan_backward(xd, Cd, dyd, dxv.view(B, I), dCv.view(I, O, d + 1), ws)
+    torch.cuda.synchronize()
+    for buf, n in ((ybuf, B * O), (dxbuf, B * I), (dCbuf, I * O * (d + 1))):
+        assert torch.all(buf[:pad] == sentinel).item() and torch.all(buf[pad + n:] == sentinel).item()
+        assert not torch.any(buf[pad:pad + n] == sentinel).item()
+    assert oracle.rel_err(yv.view(B, O).cpu().numpy(), oracle.forward(x, C)) <= TOL
+
+
+def test_non_default_stream():
+    B, I, O, d = 300, 64, 64, 4
+    x, C, dy = _inputs(B, I, O, d, seed=31)
+    xd, Cd = _dev(x), _dev(C)
+    y = torch.empty((B, O), device="cuda")
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        binding.chebykan_forward(xd, Cd, y, binding.alloc_workspace(B, I, O, d), stream=s)
+    s.synchronize()
+    assert oracle.rel_err(y.cpu().numpy(), oracle.forward(x, C)) <= TOL
+
+
+# ------------------------------------------------------- full-size workloads
+
+def _sampled_layer_check(x, C, dy, y, dx, dC, rng, label, n=1500):
+    B, I = x.shape
+    _, O, K = C.shape
+    bs, os_ = rng.integers(0, B, n), rng.integers(0, O, n)
+    is_, ks = rng.integers(0, I, n), rng.integers(0, K, n)
+    x64, C64, dy64 = x.astype(np.float64), C.astype(np.float64), dy.astype(np.float64)
+    e_y = oracle.rel_err(y[bs, os_], oracle.forward_at(x64, C64, bs, os_))
+    e_dx = oracle.rel_err(dx[bs, is_], oracle.dx_at(x64, C64, dy64, bs, is_))
+    nc = min(n, 400)
+    e_dC = oracle.rel_err(dC[is_[:nc], os_[:nc], ks[:nc]],
+                          oracle.dC_at(x64, dy64, K - 1, is_[:nc], os_[:nc], ks[:nc]))
+    print("%s y=%.2e dx=%.2e dC=%.2e" % (label, e_y, e_dx, e_dC), flush=True)
+    assert np.isfinite(y).all() and np.isfinite(dx).all() and np.isfinite(dC).all()
+    assert e_y <= TOL and e_dx <= TOL and e_dC <= TOL, (label, e_y, e_dx, e_dC)
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
+def test_full_size_workload_sampled(name):
+    """Whole stack at its real size, in the launch configuration the benchmark times.
+    Each layer is checked on the GPU's own fp32 inputs (x_l = y_{l-1}, dy_l = dx_{l+1})."""
+    w = wl.WORKLOADS[name]
+    x0, Cs, dy_last = wl.workload_inputs(w)
+    rng = np.random.default_rng(99 + w.index)
+    xs = [x0]
+    for C in Cs:
+        (y,) = gpu_layer(xs[-1], C)
+        xs.append(y)
+    dys = [None] * len(Cs)
+    dys[-1] = dy_last
+    for l in reversed(range(len(Cs))):
+        y, dx, dC = gpu_layer(xs[l], Cs[l], dys[l])
+        assert np.array_equal(y, xs[l + 1])          # forward is reproducible
+        _sampled_layer_check(xs[l], Cs[l], dys[l], y, dx, dC, rng, "%s layer %d %s" % (name, l, w.layers[l]))
+        if l > 0:
+            dys[l - 1] = dx
