@@ -33,6 +33,8 @@
  *  - Results are bitwise reproducible from run to run for fixed shapes: every
  *    reduction has a fixed order and no floating-point atomics are used.
  *  - batch == 0 is a successful no-op for forward and dx; dC is then zeroed.
+ *    Pointers to tensors that have no elements (x, y, dy, dx at batch == 0)
+ *    may be NULL.
  *  - Errors are reported by return code only.  On any error nothing has been
  *    enqueued.
  */

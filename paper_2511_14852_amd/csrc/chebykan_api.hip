@@ -108,7 +108,7 @@ chebykan_status chebykan_forward(const float* x, const float* C, float* y, int64
                                  int degree, void* workspace, size_t workspace_bytes,
                                  chebykan_stream_t stream)
 {
-    if (!x || !C || !y) return CHEBYKAN_ERR_NULL;
+    if (!C || (batch != 0 && (!x || !y))) return CHEBYKAN_ERR_NULL;  // empty tensors may be NULL
     if (!shape_ok(batch, in, out, degree)) return CHEBYKAN_ERR_SHAPE;
     const size_t need = forward_workspace_bytes(batch, in, out, degree);
     if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
@@ -126,8 +126,8 @@ chebykan_status chebykan_backward(const float* x, const float* C, const float* d
                                   int64_t batch, int in, int out, int degree, void* workspace,
                                   size_t workspace_bytes, chebykan_stream_t stream)
 {
-    if (!x || !C || !dy) return CHEBYKAN_ERR_NULL;
-    if (!dx && !dC) return CHEBYKAN_ERR_NULL;
+    if (!C || (batch != 0 && (!x || !dy))) return CHEBYKAN_ERR_NULL;  // empty tensors may be NULL
+    if (!dx && !dC && batch != 0) return CHEBYKAN_ERR_NULL;
     if (!shape_ok(batch, in, out, degree)) return CHEBYKAN_ERR_SHAPE;
     const size_t need = backward_workspace_bytes(batch, in, out, degree);
     if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;

@@ -1,0 +1,595 @@
+// fp32 MFMA kernels of the Chebyshev-KAN layer for gfx950 (wave64).
+//
+// The layer is three dense contractions around an on-the-fly basis
+// Phi[b,(i,k)] = T_k(tanh x[b,i])  (never written to HBM):
+//
+//   forward   y  = Phi * W              M = b, N = o,      contraction over (i,k)
+//   dC        dC = Phi^T * dy           M = (i,k), N = o,  contraction over b
+//   dx        G  = dy * W^T             M = b, N = (i,k),  contraction over o
+//             dx[b,i] = (1-u^2) sum_k G[b,(i,k)] T_k'(u)
+//
+// with W[(i,k),o] = C[i,o,k] (paper Eq. 2-3, Alg. 1-2).  Each workgroup of 256
+// threads (4 waves, 2 x 2) owns a 128-row output tile, stages both operands of
+// one contraction chunk in LDS (double buffered, one barrier per chunk) and
+// feeds v_mfma_f32_32x32x2_f32.  Coefficients are read in their original
+// [in][out][degree+1] layout: for one input feature a run of outputs is one
+// contiguous slab, so global loads are unit-stride without any repacking pass;
+// the k/o transposition happens in the LDS addressing.
+//
+// Accuracy: accumulators are folded into a second set about every 512
+// contraction terms, so that long fp32 sums keep a relative error near 1e-6.
+//
+// MFMA operand layout used throughout (32x32x2, lane l, half h = l/32):
+//   A: lane supplies A[row = l%32][k = h];  B: lane supplies B[k = h][col = l%32];
+//   D: register r holds D[row = 8*(r/4) + 4*h + r%4][col = l%32].
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "basis.h"
+
+namespace chebykan {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int MFMA_THREADS = 256;
+constexpr int FOLD_TERMS = 512;  // contraction terms between accumulator folds
+
+__device__ __forceinline__ floatx16 mfma32(float a, float b, floatx16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ floatx16 zero16()
+{
+    floatx16 z;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) z[r] = 0.0f;
+    return z;
+}
+
+// row inside a 32x32 MFMA output block held by register r of a lane in half h
+__device__ __forceinline__ int mfma_row(int r, int h) { return 8 * (r >> 2) + 4 * h + (r & 3); }
+
+// ============================================================== forward
+template <int D_, int BN_, int BI_, int VEC_>
+struct FwdCfg {
+    static constexpr int D = D_, K = D_ + 1, KP = K | 1;      // KP: odd per-output stride in LDS
+    static constexpr int BM = 128, BN = BN_, BI = BI_, VEC = VEC_;
+    static constexpr int WN = BN / 2, TM = 2, TN = WN / 32;
+    static constexpr int CH = BI * K;                          // contraction terms per chunk
+    static constexpr int SA = CH | 1;                          // odd row stride of the Phi tile
+    static constexpr int SS = BN * KP;                         // stride between feature slabs
+    static constexpr int A_FLOATS = (BM * SA + 3) & ~3;
+    static constexpr int B_FLOATS = (BI * SS + 3) & ~3;
+    static constexpr int STAGE = A_FLOATS + B_FLOATS;
+    static constexpr int LDS_BYTES = 2 * STAGE * 4;
+    static constexpr int NSTEP = (BI / 2) * K;
+    static constexpr int FOLD = (FOLD_TERMS / CH) > 0 ? (FOLD_TERMS / CH) : 1;
+    static constexpr int XPT = BI / 2;                         // x values per thread per chunk
+    static constexpr int NE = BI * BN * K;                     // coefficient floats per chunk
+    static constexpr int CPT = (NE / VEC + MFMA_THREADS - 1) / MFMA_THREADS;  // loads per thread
+    static_assert(BI % 2 == 0 && BN % 64 == 0, "tile shape");
+    static_assert((BN * K) % VEC == 0, "vector width");
+};
+
+// y[b,o] = sum_i sum_k C[i,o,k] T_k(tanh x[b,i])      (paper Eq. 2-3; Alg. 1 as a function)
+// grid.x = ceil(B/128) * ceil(O/BN), output-tile index fastest.
+template <class Cfg>
+__global__ void __launch_bounds__(MFMA_THREADS, 2)
+fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float* __restrict__ y,
+                int B, int I, int O, int n_tiles_o)
+{
+    constexpr int D = Cfg::D, K = Cfg::K, KP = Cfg::KP, BN = Cfg::BN, BI = Cfg::BI, VEC = Cfg::VEC;
+    constexpr int SA = Cfg::SA, SS = Cfg::SS, TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
+    extern __shared__ __align__(16) float lds[];
+
+    const int t = threadIdx.x;
+    const int tile_o = blockIdx.x % n_tiles_o;
+    const int tile_b = blockIdx.x / n_tiles_o;
+    const int b0 = tile_b * Cfg::BM;
+    const int o0 = tile_o * BN;
+    const int o_valid_floats = (O - o0 < BN ? O - o0 : BN) * K;   // valid floats of one slab
+
+    // --- producer roles
+    const int xr_row = t >> 1;                     // row of the tile this thread generates basis for
+    const int xr_f0 = (t & 1) * Cfg::XPT;          // first feature (inside the chunk)
+    const bool row_ok = (b0 + xr_row) < B;
+    const float* xrow = x + (int64_t)(b0 + xr_row) * I;
+
+    float xreg[Cfg::XPT];
+    float creg[Cfg::CPT * VEC];
+
+    auto load_chunk = [&](int i0) {
+#pragma unroll
+        for (int j = 0; j < Cfg::XPT; ++j) {
+            const int i = i0 + xr_f0 + j;
+            xreg[j] = (row_ok && i < I) ? xrow[i] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < Cfg::CPT; ++j) {
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            const int il = e / (BN * K);
+            const int rem = e % (BN * K);
+            const bool ok = (e < Cfg::NE) && (i0 + il < I) && (rem < o_valid_floats);
+            const float* src = C + ((int64_t)(i0 + il) * O + o0) * K + rem;
+            if constexpr (VEC == 4) {
+                floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (ok) v = *reinterpret_cast<const floatx4*>(src);
+                creg[j * 4 + 0] = v[0]; creg[j * 4 + 1] = v[1]; creg[j * 4 + 2] = v[2]; creg[j * 4 + 3] = v[3];
+            } else {
+                creg[j] = ok ? *src : 0.0f;
+            }
+        }
+    };
+
+    auto store_chunk = [&](float* sA, float* sB) {
+#pragma unroll
+        for (int j = 0; j < Cfg::XPT; ++j) {
+            float T[D + 1];
+            cheb_T<D>(normalise(xreg[j]), T);
+            float* dst = sA + xr_row * SA + (xr_f0 + j) * K;
+#pragma unroll
+            for (int k = 0; k < K; ++k) dst[k] = T[k];
+        }
+#pragma unroll
+        for (int j = 0; j < Cfg::CPT; ++j) {
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            if (e < Cfg::NE) {
+                const int il = e / (BN * K);
+                const int rem = e % (BN * K);
+                if constexpr (VEC == 4 && KP == K) {
+                    floatx4 v = {creg[j * 4 + 0], creg[j * 4 + 1], creg[j * 4 + 2], creg[j * 4 + 3]};
+                    *reinterpret_cast<floatx4*>(sB + il * SS + rem) = v;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) {
+                        const int n = (rem + q) / K, k = (rem + q) % K;
+                        sB[il * SS + n * KP + k] = creg[j * VEC + q];
+                    }
+                }
+            }
+        }
+    };
+
+    // --- consumer roles
+    const int lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int aBase = (wm * 64 + l32) * SA + h * (BI / 2) * K;
+    const int bBase = h * (BI / 2) * SS + (wn * WN + l32) * KP;
+
+    floatx16 acc[TM][TN], total[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) { acc[i][j] = zero16(); total[i][j] = zero16(); }
+
+    const int n_chunks = (I + BI - 1) / BI;
+    load_chunk(0);
+    for (int c = 0; c < n_chunks; ++c) {
+        float* sA = lds + (c & 1) * Cfg::STAGE;
+        float* sB = sA + Cfg::A_FLOATS;
+        store_chunk(sA, sB);
+        if (c + 1 < n_chunks) load_chunk((c + 1) * BI);
+        __syncthreads();
+        const float* pA = sA + aBase;
+        const float* pB = sB + bBase;
+#pragma unroll
+        for (int s = 0; s < Cfg::NSTEP; ++s) {
+            const int ih = s / K, k = s % K;
+            float a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = pA[i * 32 * SA + s];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = pB[ih * SS + j * 32 * KP + k];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
+        }
+        if ((c + 1) % Cfg::FOLD == 0) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) { total[i][j] += acc[i][j]; acc[i][j] = zero16(); }
+        }
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const floatx16 v = total[i][j] + acc[i][j];
+            const int col = o0 + wn * WN + j * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = b0 + wm * 64 + i * 32 + mfma_row(r, h);
+                if (row < B && col < O) y[(int64_t)row * O + col] = v[r];
+            }
+        }
+}
+
+// =================================================== coefficient gradient
+template <int D_, int BN_, int VEC_>
+struct DcCfg {
+    static constexpr int D = D_, K = D_ + 1, BN = BN_, VEC = VEC_;
+    static constexpr int BIC = 128 / K;                 // input features per tile
+    static constexpr int BMR = BIC * K;                 // real rows (i,k) of the 128-row tile
+    static constexpr int BB = 32;                       // batch rows per chunk
+    static constexpr int SMA = 128 + (BMR % 32);        // Phi^T tile row stride (see store below)
+    static constexpr int SNB = BN;
+    static constexpr int WN = BN / 2, TM = 2, TN = WN / 32;
+    static constexpr int A_FLOATS = BB * SMA;
+    static constexpr int B_FLOATS = BB * SNB;
+    static constexpr int STAGE = (A_FLOATS + B_FLOATS + 3) & ~3;
+    static constexpr int LDS_BYTES = 2 * STAGE * 4;
+    static constexpr int NSTEP = BB / 2;
+    static constexpr int FOLD = FOLD_TERMS / BB;
+    static constexpr int NEA = BB * BIC;
+    static constexpr int XPT = (NEA + MFMA_THREADS - 1) / MFMA_THREADS;
+    static constexpr int NEB = BB * BN;
+    static constexpr int GPT = NEB / VEC / MFMA_THREADS;
+    static_assert(NEB % (VEC * MFMA_THREADS) == 0, "dy tile must split evenly");
+    static_assert(A_FLOATS % 4 == 0, "dy tile must stay 16-byte aligned");
+};
+
+// partial[s][(i,k)][o] = sum over the rows of batch slice s of T_k(tanh x[b,i]) dy[b,o]
+// (paper Alg. 2, coeff_grad; the batch axis is split into slices whose partial sums a
+// second kernel adds in a fixed order - the two-stage reduction of Sec. 4.4 in place
+// of atomics).  grid = (tiles_ik * tiles_o, n_slices).
+template <class Cfg>
+__global__ void __launch_bounds__(MFMA_THREADS, 2)
+dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ partial,
+               int B, int I, int O, int n_tiles_o, int rows_per_slice)
+{
+    constexpr int D = Cfg::D, K = Cfg::K, BN = Cfg::BN, VEC = Cfg::VEC, BB = Cfg::BB, BIC = Cfg::BIC;
+    constexpr int SMA = Cfg::SMA, SNB = Cfg::SNB, TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
+    extern __shared__ __align__(16) float lds[];
+
+    const int t = threadIdx.x;
+    const int tile_o = blockIdx.x % n_tiles_o;
+    const int tile_i = blockIdx.x / n_tiles_o;
+    const int i0 = tile_i * BIC;
+    const int o0 = tile_o * BN;
+    const int slice = blockIdx.y;
+    const int64_t r_begin = (int64_t)slice * rows_per_slice;
+    int64_t r_end = r_begin + rows_per_slice;
+    if (r_end > B) r_end = B;
+
+    float xreg[Cfg::XPT];
+    float greg[Cfg::GPT * VEC];
+
+    auto load_chunk = [&](int64_t r0) {
+#pragma unroll
+        for (int j = 0; j < Cfg::XPT; ++j) {
+            const int e = t + j * MFMA_THREADS;
+            const int bl = e / BIC, il = e % BIC;
+            const bool ok = (e < Cfg::NEA) && (r0 + bl < r_end) && (i0 + il < I);
+            xreg[j] = ok ? x[(r0 + bl) * I + i0 + il] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < Cfg::GPT; ++j) {
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            const int bl = e / BN, n = e % BN;
+            // rows past the slice and columns past O are zero: they then add nothing
+            const bool ok = (r0 + bl < r_end) && (o0 + n < O);
+            const float* src = dy + (r0 + bl) * O + o0 + n;
+            if constexpr (VEC == 4) {
+                floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (ok) v = *reinterpret_cast<const floatx4*>(src);
+                greg[j * 4 + 0] = v[0]; greg[j * 4 + 1] = v[1]; greg[j * 4 + 2] = v[2]; greg[j * 4 + 3] = v[3];
+            } else {
+                greg[j] = ok ? *src : 0.0f;
+            }
+        }
+    };
+
+    auto store_chunk = [&](float* sA, float* sB) {
+#pragma unroll
+        for (int j = 0; j < Cfg::XPT; ++j) {
+            const int e = t + j * MFMA_THREADS;
+            if (e < Cfg::NEA) {
+                const int bl = e / BIC, il = e % BIC;
+                float T[D + 1];
+                cheb_T<D>(normalise(xreg[j]), T);
+                // SMA = BMR (mod 32): consecutive e land K words apart across row ends too
+                float* dst = sA + bl * SMA + il * K;
+#pragma unroll
+                for (int k = 0; k < K; ++k) dst[k] = T[k];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < Cfg::GPT; ++j) {
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            const int bl = e / BN, n = e % BN;
+            if constexpr (VEC == 4) {
+                floatx4 v = {greg[j * 4 + 0], greg[j * 4 + 1], greg[j * 4 + 2], greg[j * 4 + 3]};
+                *reinterpret_cast<floatx4*>(sB + bl * SNB + n) = v;
+            } else {
+                sB[bl * SNB + n] = greg[j];
+            }
+        }
+    };
+
+    const int lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int aBase = h * (BB / 2) * SMA + wm * 64 + l32;
+    const int bBase = h * (BB / 2) * SNB + wn * WN + l32;
+
+    floatx16 acc[TM][TN], total[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) { acc[i][j] = zero16(); total[i][j] = zero16(); }
+
+    const int n_chunks = r_end > r_begin ? (int)((r_end - r_begin + BB - 1) / BB) : 0;
+    if (n_chunks > 0) load_chunk(r_begin);
+    for (int c = 0; c < n_chunks; ++c) {
+        float* sA = lds + (c & 1) * Cfg::STAGE;
+        float* sB = sA + Cfg::A_FLOATS;
+        store_chunk(sA, sB);
+        if (c + 1 < n_chunks) load_chunk(r_begin + (int64_t)(c + 1) * BB);
+        __syncthreads();
+        const float* pA = sA + aBase;
+        const float* pB = sB + bBase;
+#pragma unroll
+        for (int s = 0; s < Cfg::NSTEP; ++s) {
+            float a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = pA[s * SMA + i * 32];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = pB[s * SNB + j * 32];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
+        }
+        if ((c + 1) % Cfg::FOLD == 0) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) { total[i][j] += acc[i][j]; acc[i][j] = zero16(); }
+        }
+    }
+
+    const int64_t IK = (int64_t)I * K;
+    float* out = partial + (int64_t)slice * IK * O;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const floatx16 v = total[i][j] + acc[i][j];
+            const int col = o0 + wn * WN + j * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ml = wm * 64 + i * 32 + mfma_row(r, h);
+                const int64_t mg = (int64_t)i0 * K + ml;
+                if (ml < Cfg::BMR && mg < IK && col < O) out[mg * O + col] = v[r];
+            }
+        }
+}
+
+// dC[i,o,k] = sum_s partial[s][(i,k)][o], slices added in index order; also turns the
+// [(i,k)][o] rows of the partials into the caller's [i][o][k] layout through LDS so that
+// both the reads and the writes are unit-stride.  grid = (ceil(O/256), I).
+template <int D>
+__global__ void __launch_bounds__(256)
+dC_combine_kernel(const float* __restrict__ partial, float* __restrict__ dC, int I, int O, int n_slices)
+{
+    constexpr int K = D + 1, KP = K | 1;
+    extern __shared__ __align__(16) float lds[];   // 256 * KP floats
+    float* tile = lds;
+    const int t = threadIdx.x;
+    const int oc = blockIdx.x * 256;
+    const int i = blockIdx.y;
+    const int o = oc + t;
+    const int64_t IK = (int64_t)I * K;
+    if (o < O) {
+        float v[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) v[k] = 0.0f;
+        for (int s = 0; s < n_slices; ++s) {
+            const float* p = partial + ((int64_t)s * IK + (int64_t)i * K) * O + o;
+#pragma unroll
+            for (int k = 0; k < K; ++k) v[k] += p[(int64_t)k * O];
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k) tile[t * KP + k] = v[k];
+    }
+    __syncthreads();
+    const int n_valid = (O - oc < 256 ? O - oc : 256) * K;
+    float* dst = dC + ((int64_t)i * O + oc) * K;
+    for (int e = t; e < n_valid; e += 256) dst[e] = tile[(e / K) * KP + (e % K)];
+}
+
+// ============================================================ input gradient
+template <int D_, int VEC_>
+struct DxCfg {
+    static constexpr int D = D_, K = D_ + 1, VEC = VEC_;
+    static constexpr int BM = 128;
+    static constexpr int BIX = 128 / D;                 // input features per tile
+    static constexpr int BNR = BIX * D;                 // real columns (i, k=1..D) of the 128-col tile
+    static constexpr int BO = 32;                       // outputs per contraction chunk
+    static constexpr int SAX = BO + 1;                  // odd row stride of the dy tile
+    static constexpr int SSX = BO * K + (D % 32);       // slab stride = D (mod 32): column n hits bank n
+    static constexpr int A_FLOATS = (BM * SAX + 3) & ~3;
+    static constexpr int B_FLOATS = (BIX * SSX + 3) & ~3;
+    static constexpr int STAGE = A_FLOATS + B_FLOATS;
+    static constexpr int SG = 129;                      // row stride of the G tile in the epilogue
+    static constexpr int LDS_FLOATS = (2 * STAGE > BM * SG) ? 2 * STAGE : BM * SG;
+    static constexpr int LDS_BYTES = LDS_FLOATS * 4;
+    static constexpr int NSTEP = BO / 2;
+    static constexpr int FOLD = FOLD_TERMS / BO;
+    static constexpr int NEA = BM * BO;
+    static constexpr int APT = NEA / VEC / MFMA_THREADS;
+    static constexpr int NEB = BIX * BO * K;
+    static constexpr int CPT = (NEB / VEC + MFMA_THREADS - 1) / MFMA_THREADS;
+    static constexpr int EPT = (BM * BIX + MFMA_THREADS - 1) / MFMA_THREADS;
+    static_assert(D >= 1, "degree 0 has no input gradient");
+    static_assert((BO * K) % VEC == 0 && NEA % (VEC * MFMA_THREADS) == 0, "vector width");
+};
+
+// dx[b,i] = (1-u^2) sum_o dy[b,o] sum_{k>=1} C[i,o,k] T_k'(u),  u = tanh x[b,i]
+// (paper Alg. 2, x_grad, with the chain rule through tanh).  The sum over o runs on the
+// matrix cores as G = dy * W^T; the sum over k is the epilogue.  No atomics: one
+// workgroup owns all outputs o for its (b,i) tile.  grid.x = ceil(B/128) * ceil(I/BIX).
+template <class Cfg>
+__global__ void __launch_bounds__(MFMA_THREADS, 2)
+dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
+               float* __restrict__ dx, int B, int I, int O, int n_tiles_i)
+{
+    constexpr int D = Cfg::D, K = Cfg::K, VEC = Cfg::VEC, BIX = Cfg::BIX, BO = Cfg::BO;
+    constexpr int SAX = Cfg::SAX, SSX = Cfg::SSX, SG = Cfg::SG;
+    constexpr int TM = 2, TN = 2;
+    extern __shared__ __align__(16) float lds[];
+
+    const int t = threadIdx.x;
+    const int tile_i = blockIdx.x % n_tiles_i;
+    const int tile_b = blockIdx.x / n_tiles_i;
+    const int b0 = tile_b * Cfg::BM;
+    const int i0 = tile_i * BIX;
+
+    float areg[Cfg::APT * VEC];
+    float creg[Cfg::CPT * VEC];
+
+    auto load_chunk = [&](int oc) {
+        const int o_valid_floats = (O - oc < BO ? O - oc : BO) * K;
+#pragma unroll
+        for (int j = 0; j < Cfg::APT; ++j) {
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            const int m = e / BO, kk = e % BO;
+            const bool ok = (b0 + m < B) && (oc + kk < O);
+            const float* src = dy + (int64_t)(b0 + m) * O + oc + kk;
+            if constexpr (VEC == 4) {
+                floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (ok) v = *reinterpret_cast<const floatx4*>(src);
+                areg[j * 4 + 0] = v[0]; areg[j * 4 + 1] = v[1]; areg[j * 4 + 2] = v[2]; areg[j * 4 + 3] = v[3];
+            } else {
+                areg[j] = ok ? *src : 0.0f;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < Cfg::CPT; ++j) {
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            const int il = e / (BO * K);
+            const int rem = e % (BO * K);
+            const bool ok = (e < Cfg::NEB) && (i0 + il < I) && (rem < o_valid_floats);
+            const float* src = C + ((int64_t)(i0 + il) * O + oc) * K + rem;
+            if constexpr (VEC == 4) {
+                floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (ok) v = *reinterpret_cast<const floatx4*>(src);
+                creg[j * 4 + 0] = v[0]; creg[j * 4 + 1] = v[1]; creg[j * 4 + 2] = v[2]; creg[j * 4 + 3] = v[3];
+            } else {
+                creg[j] = ok ? *src : 0.0f;
+            }
+        }
+    };
+
+    auto store_chunk = [&](float* sA, float* sB) {
+#pragma unroll
+        for (int j = 0; j < Cfg::APT; ++j) {
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            const int m = e / BO, kk = e % BO;
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) sA[m * SAX + kk + q] = areg[j * VEC + q];
+        }
+#pragma unroll
+        for (int j = 0; j < Cfg::CPT; ++j) {
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            if (e < Cfg::NEB) {
+                const int il = e / (BO * K);
+                const int rem = e % (BO * K);
+                if constexpr (VEC == 4 && SSX % 4 == 0) {
+                    floatx4 v = {creg[j * 4 + 0], creg[j * 4 + 1], creg[j * 4 + 2], creg[j * 4 + 3]};
+                    *reinterpret_cast<floatx4*>(sB + il * SSX + rem) = v;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) sB[il * SSX + rem + q] = creg[j * VEC + q];
+                }
+            }
+        }
+    };
+
+    const int lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int aBase = (wm * 64 + l32) * SAX + h * (BO / 2);
+    int bBase[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = wn * 64 + j * 32 + l32;
+        int il = n / D;
+        const int kq = n % D;
+        if (il > BIX - 1) il = BIX - 1;            // padding columns read valid memory, result unused
+        bBase[j] = il * SSX + h * (BO / 2) * K + kq + 1;
+    }
+
+    floatx16 acc[TM][TN], total[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) { acc[i][j] = zero16(); total[i][j] = zero16(); }
+
+    const int n_chunks = (O + BO - 1) / BO;
+    load_chunk(0);
+    for (int c = 0; c < n_chunks; ++c) {
+        float* sA = lds + (c & 1) * Cfg::STAGE;
+        float* sB = sA + Cfg::A_FLOATS;
+        store_chunk(sA, sB);
+        if (c + 1 < n_chunks) load_chunk((c + 1) * BO);
+        __syncthreads();
+        const float* pA = sA + aBase;
+#pragma unroll
+        for (int s = 0; s < Cfg::NSTEP; ++s) {
+            float a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = pA[i * 32 * SAX + s];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = sB[bBase[j] + s * K];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
+        }
+        if ((c + 1) % Cfg::FOLD == 0) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) { total[i][j] += acc[i][j]; acc[i][j] = zero16(); }
+        }
+    }
+
+    // --- epilogue: G tile to LDS, then each thread finishes (row, feature) pairs
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const floatx16 v = total[i][j] + acc[i][j];
+            const int col = wn * 64 + j * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) lds[(wm * 64 + i * 32 + mfma_row(r, h)) * SG + col] = v[r];
+        }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < Cfg::EPT; ++j) {
+        const int e = t + j * MFMA_THREADS;
+        const int m = e / BIX, il = e % BIX;
+        const int b = b0 + m, i = i0 + il;
+        if (e < Cfg::BM * BIX && b < B && i < I) {
+            const float u = normalise(x[(int64_t)b * I + i]);
+            float dT[D];
+            cheb_dT<D>(u, dT);
+            const float* g = lds + m * SG + il * D;
+            float sum = 0.0f;
+#pragma unroll
+            for (int k = 0; k < D; ++k) sum = fmaf(g[k], dT[k], sum);
+            dx[(int64_t)b * I + i] = tanh_slope(u) * sum;
+        }
+    }
+}
+
+}  // namespace chebykan
