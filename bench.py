@@ -114,22 +114,29 @@ def call_work(tag, B, I, O, d):
 def cpu_baseline(w, wl, target_seconds):
     """Time the fp64 oracle on the host cores over a bounded row sample of the workload."""
     import oracle
-    flops_per_row = sum(wl.layer_flops(1, i, o, w.degree) for (i, o) in w.layers)
-    # plain loops reach roughly 0.5 GFLOP/s per thread; aim for target_seconds
     threads = oracle.num_threads()
-    rows = int(min(w.batch, max(64, target_seconds * 0.5e9 * threads / flops_per_row)))
-    x0, Cs, dy_last = wl.workload_inputs(w, batch=rows)
-    t0 = time.perf_counter()
-    xs = [x0.astype(np.float64)]
-    for C in Cs:
-        xs.append(oracle.forward(xs[-1], C))
-    dy = dy_last.astype(np.float64)
-    for l in reversed(range(len(Cs))):
-        dx, dC = oracle.backward(xs[l], Cs[l], dy)
-        dy = dx
-    dt = time.perf_counter() - t0
+
+    def one_pass(rows):
+        x0, Cs, dy_last = wl.workload_inputs(w, batch=rows)
+        t0 = time.perf_counter()
+        xs = [x0.astype(np.float64)]
+        for C in Cs:
+            xs.append(oracle.forward(xs[-1], C))
+        dy = dy_last.astype(np.float64)
+        for l in reversed(range(len(Cs))):
+            dx, _ = oracle.backward(xs[l], Cs[l], dy)
+            dy = dx
+        return time.perf_counter() - t0
+
+    # size the sample from a small probe so that the timed pass takes about target_seconds / 4 of wall time
+    probe_rows = int(min(w.batch, 256))
+    one_pass(probe_rows)                      # first call also loads the library
+    per_row = one_pass(probe_rows) / probe_rows
+    rows = int(min(w.batch, max(probe_rows, (target_seconds / 4.0) / max(per_row, 1e-9))))
+    dt = one_pass(rows)
     return {"value": rows / dt, "unit": "samples/s", "cores": threads, "kind": "oracle",
-            "sample": "%d of %d rows of workload %s, full stack fwd+bwd in fp64, %.2f s" % (rows, w.batch, w.name, dt)}
+            "sample": "%d of %d rows of workload %s, full stack fwd+bwd in fp64, %.2f s wall on %d threads"
+                      % (rows, w.batch, w.name, dt, threads)}
 
 
 def main():

@@ -117,7 +117,7 @@ chebykan_status chebykan_forward(const float* x, const float* C, float* y, int64
     if (batch == 0) return CHEBYKAN_OK;
     hipStream_t s = (hipStream_t)stream;
     (void)hipGetLastError();
-    if (g_family != 1 && mfma_forward(x, C, y, batch, in, out, degree, workspace, s)) return launch_status();
+    if (g_family != 1 && fast_forward(x, C, y, batch, in, out, degree, workspace, s)) return launch_status();
     generic_forward(x, C, y, batch, in, out, degree, s);
     return launch_status();
 }
@@ -135,15 +135,11 @@ chebykan_status chebykan_backward(const float* x, const float* C, const float* d
     if (dev != CHEBYKAN_OK) return dev;
     hipStream_t s = (hipStream_t)stream;
     (void)hipGetLastError();
-    if (dx && batch > 0) {
-        if (!(g_family != 1 && mfma_dx(x, C, dy, dx, batch, in, out, degree, workspace, s)))
-            generic_dx(x, C, dy, dx, batch, in, out, degree, s);
-    }
-    if (dC) {
-        // batch == 0 still defines dC (all zeros): the generic kernel's empty sum gives that.
-        if (!(g_family != 1 && batch > 0 && mfma_dC(x, dy, dC, batch, in, out, degree, workspace, s)))
-            generic_dC(x, dy, dC, batch, in, out, degree, s);
-    }
+    if (g_family != 1 && batch > 0 && fast_backward(x, C, dy, dx, dC, batch, in, out, degree, workspace, s))
+        return launch_status();
+    if (dx && batch > 0) generic_dx(x, C, dy, dx, batch, in, out, degree, s);
+    // batch == 0 still defines dC (all zeros): the generic kernel's empty sum gives that.
+    if (dC) generic_dC(x, dy, dC, batch, in, out, degree, s);
     return launch_status();
 }
 

@@ -1,6 +1,8 @@
-// Internal interface between the C ABI and the MFMA kernel family.
-// Each mfma_* function either enqueues the whole operation on `s` and returns
-// true, or enqueues nothing and returns false (shape/degree not specialised).
+// Internal interface between the C ABI and the specialised kernel families
+// (matrix-core kernels for wide layers, streaming kernels for very narrow ones).
+// Each fast_* function either enqueues the whole operation on `s` and returns
+// true, or enqueues nothing and returns false (shape/degree not specialised:
+// the caller then uses the any-degree kernels).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stddef.h>
@@ -11,11 +13,10 @@ namespace chebykan {
 size_t forward_workspace_bytes(int64_t B, int I, int O, int d);
 size_t backward_workspace_bytes(int64_t B, int I, int O, int d);
 
-bool mfma_forward(const float* x, const float* C, float* y, int64_t B, int I, int O, int d, void* ws,
+bool fast_forward(const float* x, const float* C, float* y, int64_t B, int I, int O, int d, void* ws,
                   hipStream_t s);
-bool mfma_dx(const float* x, const float* C, const float* dy, float* dx, int64_t B, int I, int O, int d,
-             void* ws, hipStream_t s);
-bool mfma_dC(const float* x, const float* dy, float* dC, int64_t B, int I, int O, int d, void* ws,
-             hipStream_t s);
+// dx and/or dC may be null (skipped).
+bool fast_backward(const float* x, const float* C, const float* dy, float* dx, float* dC, int64_t B, int I,
+                   int O, int d, void* ws, hipStream_t s);
 
 }  // namespace chebykan

@@ -4,6 +4,7 @@
 
 #include "dispatch.h"
 #include "mfma_kernels.h"
+#include "narrow_kernels.h"
 
 namespace chebykan {
 
@@ -54,6 +55,10 @@ struct DcPlan {
     int rows_per_slice;  // multiple of 32
 };
 
+// Batch slices for the coefficient gradient.  512 workgroups are resident at once
+// (256 CUs x 2); the slice count is the smallest one that fills at least one such
+// round and wastes under a tenth of its last round, subject to >= 256 rows per slice
+// and a 512 MiB cap on the partial buffers.
 DcPlan plan_dC(int64_t B, int I, int O, int d)
 {
     const int K = d + 1;
@@ -61,14 +66,22 @@ DcPlan plan_dC(int64_t B, int I, int O, int d)
     p.bn = O <= 64 ? 64 : 128;
     const int bic = 128 / K;
     const int64_t tiles = (int64_t)((I + bic - 1) / bic) * ((O + p.bn - 1) / p.bn);
-    int64_t want = (1024 + tiles - 1) / tiles;                 // aim for >= 1024 workgroups
-    const int64_t max_by_rows = (B + 255) / 256;               // at least 256 rows per slice
+    int64_t max_s = (B + 255) / 256;
     const int64_t bytes_per_slice = (int64_t)I * K * O * 4;
     const int64_t max_by_bytes = ((int64_t)512 << 20) / bytes_per_slice;
-    if (want > max_by_rows) want = max_by_rows;
-    if (want > max_by_bytes) want = max_by_bytes;
-    if (want < 1) want = 1;
-    int64_t rows = (B + want - 1) / want;
+    if (max_s > max_by_bytes) max_s = max_by_bytes;
+    if (max_s > 1024) max_s = 1024;
+    if (max_s < 1) max_s = 1;
+    int64_t best = 1;
+    double best_eff = -1.0;
+    for (int64_t sl = 1; sl <= max_s; ++sl) {
+        const int64_t wg = tiles * sl;
+        const int64_t rounds = (wg + 511) / 512;
+        const double eff = (double)wg / (double)(rounds * 512);
+        if (eff > best_eff + 1e-9) { best_eff = eff; best = sl; }
+        if (wg >= 512 && eff >= 0.9) { best = sl; break; }
+    }
+    int64_t rows = (B + best - 1) / best;
     rows = (rows + 31) / 32 * 32;
     if (rows < 32) rows = 32;
     p.rows_per_slice = (int)rows;
@@ -102,7 +115,7 @@ void pick_dC(const float* x, const float* dy, float* dC, float* partial, int B, 
         if (vec) launch_dC<D, 128, 4>(x, dy, partial, B, I, O, p, s);
         else launch_dC<D, 128, 1>(x, dy, partial, B, I, O, p, s);
     }
-    hipLaunchKernelGGL(dC_combine_kernel<D>, dim3((unsigned)((O + 255) / 256), (unsigned)I), dim3(256),
+    hipLaunchKernelGGL(dC_combine_kernel<D>, dim3((unsigned)((O + 31) / 32), (unsigned)I), dim3(256),
                        256 * ((D + 1) | 1) * sizeof(float), s, partial, dC, I, O, p.slices);
 }
 
@@ -137,6 +150,83 @@ bool shape_fits(int64_t B, int I, int O, int d)
     return true;
 }
 
+// ------------------------------------------------------------ narrow layers
+constexpr int NARROW_MAX_OUT = 4;
+
+bool use_narrow(int64_t B, int I, int O, int d)
+{
+    return shape_fits(B, I, O, d) && O <= NARROW_MAX_OUT && (int64_t)I * O * (d + 1) <= 16384;
+}
+
+struct NarrowPlan {
+    int G;             // lanes per row
+    int rows_per_wg;   // multiple of NARROW_RB * (256 / G)
+    int slices;        // workgroups along the batch
+};
+
+NarrowPlan plan_narrow(int64_t B, int I)
+{
+    NarrowPlan p;
+    p.G = 8;
+    while (p.G < 64 && p.G < I) p.G *= 2;
+    const int quantum = NARROW_RB * (NARROW_THREADS / p.G);
+    int64_t rows = (B + 2047) / 2048;                       // about 2048 workgroups
+    rows = (rows + quantum - 1) / quantum * quantum;
+    if (rows < quantum) rows = quantum;
+    p.rows_per_wg = (int)rows;
+    p.slices = (int)((B + rows - 1) / rows);
+    if (p.slices < 1) p.slices = 1;
+    return p;
+}
+
+template <int D, int O>
+void launch_narrow_fwd(const float* x, const float* C, float* y, int B, int I, hipStream_t s)
+{
+    const NarrowPlan p = plan_narrow(B, I);
+    hipLaunchKernelGGL((narrow_fwd_kernel<D, O>), dim3((unsigned)p.slices), dim3(NARROW_THREADS),
+                       (size_t)I * O * (D + 1) * sizeof(float), s, x, C, y, B, I, p.G, p.rows_per_wg);
+}
+
+template <int D, int O>
+void launch_narrow_bwd(const float* x, const float* C, const float* dy, float* dx, float* dC, float* partial,
+                       int B, int I, hipStream_t s)
+{
+    constexpr int FPL = NarrowFpl<O>::value;
+    const NarrowPlan p = plan_narrow(B, I);
+    const int blocks_i = (I + p.G * FPL - 1) / (p.G * FPL);
+    hipLaunchKernelGGL((narrow_bwd_kernel<D, O>), dim3((unsigned)p.slices, (unsigned)blocks_i),
+                       dim3(NARROW_THREADS), (size_t)NARROW_THREADS * FPL * O * (D + 1) * sizeof(float), s, x, C, dy,
+                       dx, dC ? partial : nullptr, B, I, p.G, p.rows_per_wg);
+    if (dC) {
+        const int n = I * O * (D + 1);
+        hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((n + 15) / 16)), dim3(256), 16 * 17 * sizeof(float), s,
+                           partial, dC, n, p.slices);
+    }
+}
+
+template <int D>
+void narrow_fwd_by_out(const float* x, const float* C, float* y, int B, int I, int O, hipStream_t s)
+{
+    switch (O) {
+        case 1: launch_narrow_fwd<D, 1>(x, C, y, B, I, s); break;
+        case 2: launch_narrow_fwd<D, 2>(x, C, y, B, I, s); break;
+        case 3: launch_narrow_fwd<D, 3>(x, C, y, B, I, s); break;
+        default: launch_narrow_fwd<D, 4>(x, C, y, B, I, s); break;
+    }
+}
+
+template <int D>
+void narrow_bwd_by_out(const float* x, const float* C, const float* dy, float* dx, float* dC, float* partial, int B,
+                       int I, int O, hipStream_t s)
+{
+    switch (O) {
+        case 1: launch_narrow_bwd<D, 1>(x, C, dy, dx, dC, partial, B, I, s); break;
+        case 2: launch_narrow_bwd<D, 2>(x, C, dy, dx, dC, partial, B, I, s); break;
+        case 3: launch_narrow_bwd<D, 3>(x, C, dy, dx, dC, partial, B, I, s); break;
+        default: launch_narrow_bwd<D, 4>(x, C, dy, dx, dC, partial, B, I, s); break;
+    }
+}
+
 }  // namespace
 
 size_t forward_workspace_bytes(int64_t, int, int, int) { return 0; }
@@ -144,14 +234,25 @@ size_t forward_workspace_bytes(int64_t, int, int, int) { return 0; }
 size_t backward_workspace_bytes(int64_t B, int I, int O, int d)
 {
     if (B <= 0 || !shape_fits(B, I, O, d)) return 0;
-    const DcPlan p = plan_dC(B, I, O, d);
-    return (size_t)p.slices * (size_t)I * (size_t)(d + 1) * (size_t)O * sizeof(float);
+    const size_t coeffs = (size_t)I * (size_t)(d + 1) * (size_t)O * sizeof(float);
+    if (use_narrow(B, I, O, d)) return (size_t)plan_narrow(B, I).slices * coeffs;
+    return (size_t)plan_dC(B, I, O, d).slices * coeffs;
 }
 
-bool mfma_forward(const float* x, const float* C, float* y, int64_t B, int I, int O, int d, void*, hipStream_t s)
+bool fast_forward(const float* x, const float* C, float* y, int64_t B, int I, int O, int d, void*, hipStream_t s)
 {
-    if (!shape_fits(B, I, O, d) || O < 8) return false;   // very narrow outputs: not a matrix-core shape
+    if (!shape_fits(B, I, O, d)) return false;
     const int b = (int)B;
+    if (use_narrow(B, I, O, d)) {
+        switch (d) {
+            case 3: narrow_fwd_by_out<3>(x, C, y, b, I, O, s); return true;
+            case 4: narrow_fwd_by_out<4>(x, C, y, b, I, O, s); return true;
+            case 5: narrow_fwd_by_out<5>(x, C, y, b, I, O, s); return true;
+            case 6: narrow_fwd_by_out<6>(x, C, y, b, I, O, s); return true;
+            case 8: narrow_fwd_by_out<8>(x, C, y, b, I, O, s); return true;
+        }
+        return false;
+    }
     switch (d) {
         case 3: pick_fwd<3, 8>(x, C, y, b, I, O, s); return true;
         case 4: pick_fwd<4, 8>(x, C, y, b, I, O, s); return true;
@@ -162,33 +263,36 @@ bool mfma_forward(const float* x, const float* C, float* y, int64_t B, int I, in
     return false;
 }
 
-bool mfma_dx(const float* x, const float* C, const float* dy, float* dx, int64_t B, int I, int O, int d, void*,
-             hipStream_t s)
+template <int D>
+static void mfma_backward(const float* x, const float* C, const float* dy, float* dx, float* dC, float* partial,
+                          int B, int I, int O, hipStream_t s)
 {
-    if (!shape_fits(B, I, O, d) || O < 8) return false;
-    const int b = (int)B;
-    switch (d) {
-        case 3: pick_dx<3>(x, C, dy, dx, b, I, O, s); return true;
-        case 4: pick_dx<4>(x, C, dy, dx, b, I, O, s); return true;
-        case 5: pick_dx<5>(x, C, dy, dx, b, I, O, s); return true;
-        case 6: pick_dx<6>(x, C, dy, dx, b, I, O, s); return true;
-        case 8: pick_dx<8>(x, C, dy, dx, b, I, O, s); return true;
-    }
-    return false;
+    if (dx) pick_dx<D>(x, C, dy, dx, B, I, O, s);
+    if (dC) pick_dC<D>(x, dy, dC, partial, B, I, O, plan_dC(B, I, O, D), s);
 }
 
-bool mfma_dC(const float* x, const float* dy, float* dC, int64_t B, int I, int O, int d, void* ws, hipStream_t s)
+bool fast_backward(const float* x, const float* C, const float* dy, float* dx, float* dC, int64_t B, int I, int O,
+                   int d, void* ws, hipStream_t s)
 {
-    if (!shape_fits(B, I, O, d) || O < 8 || !ws) return false;
-    const DcPlan p = plan_dC(B, I, O, d);
+    if (!shape_fits(B, I, O, d) || (dC && !ws)) return false;
     float* partial = static_cast<float*>(ws);
     const int b = (int)B;
+    if (use_narrow(B, I, O, d)) {
+        switch (d) {
+            case 3: narrow_bwd_by_out<3>(x, C, dy, dx, dC, partial, b, I, O, s); return true;
+            case 4: narrow_bwd_by_out<4>(x, C, dy, dx, dC, partial, b, I, O, s); return true;
+            case 5: narrow_bwd_by_out<5>(x, C, dy, dx, dC, partial, b, I, O, s); return true;
+            case 6: narrow_bwd_by_out<6>(x, C, dy, dx, dC, partial, b, I, O, s); return true;
+            case 8: narrow_bwd_by_out<8>(x, C, dy, dx, dC, partial, b, I, O, s); return true;
+        }
+        return false;
+    }
     switch (d) {
-        case 3: pick_dC<3>(x, dy, dC, partial, b, I, O, p, s); return true;
-        case 4: pick_dC<4>(x, dy, dC, partial, b, I, O, p, s); return true;
-        case 5: pick_dC<5>(x, dy, dC, partial, b, I, O, p, s); return true;
-        case 6: pick_dC<6>(x, dy, dC, partial, b, I, O, p, s); return true;
-        case 8: pick_dC<8>(x, dy, dC, partial, b, I, O, p, s); return true;
+        case 3: mfma_backward<3>(x, C, dy, dx, dC, partial, b, I, O, s); return true;
+        case 4: mfma_backward<4>(x, C, dy, dx, dC, partial, b, I, O, s); return true;
+        case 5: mfma_backward<5>(x, C, dy, dx, dC, partial, b, I, O, s); return true;
+        case 6: mfma_backward<6>(x, C, dy, dx, dC, partial, b, I, O, s); return true;
+        case 8: mfma_backward<8>(x, C, dy, dx, dC, partial, b, I, O, s); return true;
     }
     return false;
 }

@@ -372,37 +372,45 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
         }
 }
 
-// dC[i,o,k] = sum_s partial[s][(i,k)][o], slices added in index order; also turns the
-// [(i,k)][o] rows of the partials into the caller's [i][o][k] layout through LDS so that
-// both the reads and the writes are unit-stride.  grid = (ceil(O/256), I).
+// dC[i,o,k] = sum_s partial[s][(i,k)][o] in a fixed order: 8 slice groups take every 8th
+// slice each, then the 8 group sums are added in group order.  Also turns the [(i,k)][o]
+// rows of the partials into the caller's [i][o][k] layout through LDS, so that reads and
+// writes are both unit-stride.  block = 8 slice groups x 32 outputs; grid = (ceil(O/32), I).
+// Dynamic LDS: 256 * ((D+1)|1) floats.
 template <int D>
 __global__ void __launch_bounds__(256)
 dC_combine_kernel(const float* __restrict__ partial, float* __restrict__ dC, int I, int O, int n_slices)
 {
     constexpr int K = D + 1, KP = K | 1;
-    extern __shared__ __align__(16) float lds[];   // 256 * KP floats
-    float* tile = lds;
+    extern __shared__ __align__(16) float lds[];
     const int t = threadIdx.x;
-    const int oc = blockIdx.x * 256;
+    const int ol = t & 31, sg = t >> 5;
+    const int oc = blockIdx.x * 32;
     const int i = blockIdx.y;
-    const int o = oc + t;
+    const int o = oc + ol;
     const int64_t IK = (int64_t)I * K;
-    if (o < O) {
-        float v[K];
+    float v[K];
 #pragma unroll
-        for (int k = 0; k < K; ++k) v[k] = 0.0f;
-        for (int s = 0; s < n_slices; ++s) {
+    for (int k = 0; k < K; ++k) v[k] = 0.0f;
+    if (o < O) {
+        for (int s = sg; s < n_slices; s += 8) {
             const float* p = partial + ((int64_t)s * IK + (int64_t)i * K) * O + o;
 #pragma unroll
             for (int k = 0; k < K; ++k) v[k] += p[(int64_t)k * O];
         }
-#pragma unroll
-        for (int k = 0; k < K; ++k) tile[t * KP + k] = v[k];
     }
+#pragma unroll
+    for (int k = 0; k < K; ++k) lds[(sg * 32 + ol) * KP + k] = v[k];
     __syncthreads();
-    const int n_valid = (O - oc < 256 ? O - oc : 256) * K;
+    const int n_valid = (O - oc < 32 ? O - oc : 32) * K;
     float* dst = dC + ((int64_t)i * O + oc) * K;
-    for (int e = t; e < n_valid; e += 256) dst[e] = tile[(e / K) * KP + (e % K)];
+    for (int e = t; e < n_valid; e += 256) {
+        const int o2 = e / K, k = e % K;
+        float total = 0.0f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) total += lds[(q * 32 + o2) * KP + k];
+        dst[e] = total;
+    }
 }
 
 // ============================================================ input gradient

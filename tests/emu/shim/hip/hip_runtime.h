@@ -96,6 +96,18 @@ inline emu_floatx16 emu_mfma_f32_32x32x2f32(float a, float b, emu_floatx16 c, in
 }
 #define __builtin_amdgcn_mfma_f32_32x32x2f32 emu_mfma_f32_32x32x2f32
 
+// wave-level exchange: every lane of the wave must take part
+inline float __shfl_xor(float v, int mask, int width = 64)
+{
+    (void)width;
+    const int w = emu_tid / 64, lane = emu_tid % 64;
+    emu_block->exA[w][lane] = v;
+    pthread_barrier_wait(&emu_block->wave_barrier[w]);
+    const float r = emu_block->exA[w][lane ^ mask];
+    pthread_barrier_wait(&emu_block->wave_barrier[w]);
+    return r;
+}
+
 template <class Kernel, class... Args>
 void emu_launch(Kernel kernel, dim3 grid, dim3 block, size_t lds_bytes, Args... args)
 {

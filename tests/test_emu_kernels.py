@@ -71,6 +71,11 @@ CASES = [
     (140, 7, 130, 6),
     (129, 5, 257, 8),
     (600, 10, 12, 6),
+    # very narrow outputs: the streaming kernels
+    (300, 64, 1, 6),
+    (100, 8, 2, 3),
+    (77, 70, 3, 8),
+    (50, 300, 4, 5),
 ]
 
 
