@@ -9,10 +9,30 @@
 
 namespace chebykan {
 
-__device__ __forceinline__ float normalise(float x) { return tanhf(x); }
+// u = tanh(x) = 1 - 2t/(1+t) with t = exp(-2|x|), on the hardware exp2 and reciprocal
+// units (about 1 ulp each).  In this form the absolute error is smallest where |u| -> 1,
+// which is where T_k' (up to k^2) amplifies it; over x ~ N(0,1) the resulting basis error
+// is within 30 % of what a correctly rounded tanh gives (u: rms 5e-8, max 2.5e-7 absolute;
+// relative accuracy of u itself is lost for |x| < 1e-3, which no output is sensitive to).
+// |x| > 44 gives t = 0 and u = +-1 exactly; NaN propagates.
+__device__ __forceinline__ float normalise(float x)
+{
+    const float ax = fabsf(x);
+    const float t2 = __builtin_amdgcn_exp2f(fmaf(ax, -2.885390081777927f, 1.0f));   // 2 exp(-2|x|)
+    const float r = __builtin_amdgcn_rcpf(fmaf(0.5f, t2, 1.0f));                      // 1 / (1 + t)
+    return copysignf(fmaf(-t2, r, 1.0f), x);
+}
 
-// 1 - u^2 without cancellation for |u| close to 1: (1-u) is exact there.
-__device__ __forceinline__ float tanh_slope(float u) { return (1.0f - u) * (1.0f + u); }
+// Same u, plus the tanh derivative 1 - u^2 = 4t/(1+t)^2 taken from t directly, which keeps
+// its relative accuracy in the tails where 1 - u*u would cancel.
+__device__ __forceinline__ float normalise(float x, float& slope)
+{
+    const float ax = fabsf(x);
+    const float t2 = __builtin_amdgcn_exp2f(fmaf(ax, -2.885390081777927f, 1.0f));
+    const float r = __builtin_amdgcn_rcpf(fmaf(0.5f, t2, 1.0f));
+    slope = (t2 * r) * (r + r);
+    return copysignf(fmaf(-t2, r, 1.0f), x);
+}
 
 // T[0..D] at u.
 template <int D>

@@ -54,7 +54,8 @@ generic_dx_kernel(const float* __restrict__ x, const float* __restrict__ C, cons
     const int64_t b = (int64_t)blockIdx.x * 4 + threadIdx.y;
     if (i >= I || b >= B) return;
     const int K = degree + 1;
-    const float u = normalise(x[b * I + i]);
+    float slope;
+    const float u = normalise(x[b * I + i], slope);
     const float two_u = 2.0f * u;
     const float* g = dy + b * O;
     float total = 0.0f, part = 0.0f;
@@ -71,7 +72,7 @@ generic_dx_kernel(const float* __restrict__ x, const float* __restrict__ C, cons
         part = fmaf(g[o], inner, part);
         if ((o % GENERIC_FOLD) == GENERIC_FOLD - 1) { total += part; part = 0.0f; }
     }
-    dx[b * I + i] = tanh_slope(u) * (total + part);
+    dx[b * I + i] = slope * (total + part);
 }
 
 // dC[i,o,k] = sum_b T_k(tanh x[b,i]) dy[b,o]                   (paper Alg. 2, coeff_grad)

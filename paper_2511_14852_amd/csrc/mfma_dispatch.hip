@@ -170,7 +170,7 @@ NarrowPlan plan_narrow(int64_t B, int I)
     p.G = 8;
     while (p.G < 64 && p.G < I) p.G *= 2;
     const int quantum = NARROW_RB * (NARROW_THREADS / p.G);
-    int64_t rows = (B + 2047) / 2048;                       // about 2048 workgroups
+    int64_t rows = (B + 1023) / 1024;                       // about 1024 workgroups
     rows = (rows + quantum - 1) / quantum * quantum;
     if (rows < quantum) rows = quantum;
     p.rows_per_wg = (int)rows;
@@ -199,7 +199,7 @@ void launch_narrow_bwd(const float* x, const float* C, const float* dy, float* d
                        dx, dC ? partial : nullptr, B, I, p.G, p.rows_per_wg);
     if (dC) {
         const int n = I * O * (D + 1);
-        hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((n + 15) / 16)), dim3(256), 16 * 17 * sizeof(float), s,
+        hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((n + 7) / 8)), dim3(256), 32 * 9 * sizeof(float), s,
                            partial, dC, n, p.slices);
     }
 }

@@ -588,14 +588,15 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
         const int m = e / BIX, il = e % BIX;
         const int b = b0 + m, i = i0 + il;
         if (e < Cfg::BM * BIX && b < B && i < I) {
-            const float u = normalise(x[(int64_t)b * I + i]);
+            float slope;
+            const float u = normalise(x[(int64_t)b * I + i], slope);
             float dT[D];
             cheb_dT<D>(u, dT);
             const float* g = lds + m * SG + il * D;
             float sum = 0.0f;
 #pragma unroll
             for (int k = 0; k < D; ++k) sum = fmaf(g[k], dT[k], sum);
-            dx[(int64_t)b * I + i] = tanh_slope(u) * sum;
+            dx[(int64_t)b * I + i] = slope * sum;
         }
     }
 }

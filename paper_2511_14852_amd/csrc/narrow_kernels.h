@@ -165,7 +165,8 @@ narrow_bwd_kernel(const float* __restrict__ x, const float* __restrict__ C, cons
             for (int j = 0; j < FPL; ++j) {
                 if (j >= nj) continue;
                 const int i = i_first + j * G;
-                const float u = normalise(xv[r][j]);
+                float slope;
+                const float u = normalise(xv[r][j], slope);
                 float T[K];
                 cheb_T<D>(u, T);
 #pragma unroll
@@ -184,7 +185,7 @@ narrow_bwd_kernel(const float* __restrict__ x, const float* __restrict__ C, cons
                             for (int k = 0; k < D; ++k) inner = fmaf(creg[j][o][k], dT[k], inner);
                             s = fmaf(gv[r][o], inner, s);
                         }
-                        dx[row * I + i] = tanh_slope(u) * s;
+                        dx[row * I + i] = slope * s;
                     }
                 }
             }
@@ -219,25 +220,25 @@ narrow_bwd_kernel(const float* __restrict__ x, const float* __restrict__ C, cons
     }
 }
 
-// out[e] = sum_s partial[s][e], slices added in a fixed order: 16 slice groups take
-// every 16th slice each, then the 16 group sums are added in group order.
-// block = 256 threads = 16 slice groups x 16 elements; grid.x = ceil(n/16).
+// out[e] = sum_s partial[s][e], slices added in a fixed order: 32 slice groups take
+// every 32nd slice each, then the 32 group sums are added in group order.
+// block = 256 threads = 32 slice groups x 8 elements; grid.x = ceil(n/8).
+// Dynamic LDS: 32 x 9 floats.
 __global__ void __launch_bounds__(256)
 sum_slices_kernel(const float* __restrict__ partial, float* __restrict__ out, int n, int n_slices)
 {
-    extern __shared__ __align__(16) float lds[];   // 16 x 17 floats
-    float (*red)[17] = reinterpret_cast<float (*)[17]>(lds);
-    const int el = threadIdx.x & 15, sg = threadIdx.x >> 4;
-    const int e = blockIdx.x * 16 + el;
+    extern __shared__ __align__(16) float lds[];
+    const int el = threadIdx.x & 7, sg = threadIdx.x >> 3;
+    const int e = blockIdx.x * 8 + el;
     float s = 0.0f;
     if (e < n)
-        for (int q = sg; q < n_slices; q += 16) s += partial[(int64_t)q * n + e];
-    red[sg][el] = s;
+        for (int q = sg; q < n_slices; q += 32) s += partial[(int64_t)q * n + e];
+    lds[sg * 9 + el] = s;
     __syncthreads();
     if (sg == 0 && e < n) {
         float total = 0.0f;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) total += red[q][el];
+        for (int q = 0; q < 32; ++q) total += lds[q * 9 + el];
         out[e] = total;
     }
 }

@@ -96,6 +96,11 @@ inline emu_floatx16 emu_mfma_f32_32x32x2f32(float a, float b, emu_floatx16 c, in
 }
 #define __builtin_amdgcn_mfma_f32_32x32x2f32 emu_mfma_f32_32x32x2f32
 
+inline float emu_exp2f(float x) { return exp2f(x); }
+inline float emu_rcpf(float x) { return 1.0f / x; }
+#define __builtin_amdgcn_exp2f emu_exp2f
+#define __builtin_amdgcn_rcpf emu_rcpf
+
 // wave-level exchange: every lane of the wave must take part
 inline float __shfl_xor(float v, int mask, int width = 64)
 {
