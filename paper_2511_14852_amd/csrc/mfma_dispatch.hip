@@ -1,6 +1,7 @@
 // Host side of the MFMA kernel family: which shapes it takes, tile choice,
 // batch-slice plan for the coefficient gradient, launches.
 #include <hip/hip_runtime.h>
+#include <stdlib.h>
 
 #include "dispatch.h"
 #include "mfma_kernels.h"
@@ -14,6 +15,17 @@ bool degree_specialised(int d) { return d == 3 || d == 4 || d == 5 || d == 6 || 
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Tuning switches for kernel experiments: integer bit mask in the environment variable
+// CHEBYKAN_TUNE, read once.  Bit 0: forward kernel without producer/MFMA interleaving.
+int tune_flags()
+{
+    static const int flags = [] {
+        const char* e = getenv("CHEBYKAN_TUNE");
+        return e ? atoi(e) : 0;
+    }();
+    return flags;
+}
+
 // Dynamic LDS above 64 KiB has to be allowed per kernel once.
 template <class KernelT>
 void allow_lds(KernelT kernel, int bytes)
@@ -23,16 +35,23 @@ void allow_lds(KernelT kernel, int bytes)
 }
 
 // ------------------------------------------------------------------ forward
-template <int D, int BN, int BI, int VEC>
-void launch_fwd(const float* x, const float* C, float* y, int B, int I, int O, hipStream_t s)
+template <int D, int BN, int BI, int VEC, int PIPE>
+void launch_fwd_cfg(const float* x, const float* C, float* y, int B, int I, int O, hipStream_t s)
 {
-    using Cfg = FwdCfg<D, BN, BI, VEC>;
+    using Cfg = FwdCfg<D, BN, BI, VEC, PIPE>;
     static bool once = (allow_lds(fwd_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
     (void)once;
     const int tiles_o = (O + BN - 1) / BN;
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * tiles_o;
     hipLaunchKernelGGL(fwd_mfma_kernel<Cfg>, dim3((unsigned)tiles), dim3(MFMA_THREADS), Cfg::LDS_BYTES, s, x, C,
                        y, B, I, O, tiles_o);
+}
+
+template <int D, int BN, int BI, int VEC>
+void launch_fwd(const float* x, const float* C, float* y, int B, int I, int O, hipStream_t s)
+{
+    if (tune_flags() & 1) launch_fwd_cfg<D, BN, BI, VEC, 0>(x, C, y, B, I, O, s);
+    else launch_fwd_cfg<D, BN, BI, VEC, 1>(x, C, y, B, I, O, s);
 }
 
 template <int D, int BI>
@@ -120,10 +139,10 @@ void pick_dC(const float* x, const float* dy, float* dC, float* partial, int B, 
 }
 
 // --------------------------------------------------------------------- dx
-template <int D, int VEC>
+template <int D, int NB, int VEC>
 void launch_dx(const float* x, const float* C, const float* dy, float* dx, int B, int I, int O, hipStream_t s)
 {
-    using Cfg = DxCfg<D, VEC>;
+    using Cfg = DxCfg<D, NB, VEC>;
     static bool once = (allow_lds(dx_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
     (void)once;
     const int tiles_i = (I + Cfg::BIX - 1) / Cfg::BIX;
@@ -132,12 +151,38 @@ void launch_dx(const float* x, const float* C, const float* dy, float* dx, int B
                        dx, B, I, O, tiles_i);
 }
 
+// Column blocks per tile: the count (1..4) that covers the I*D columns of G with the
+// fewest 32-column MFMA blocks; ties go to the wider tile (more reuse of the dy tile).
+int dx_column_blocks(int I, int D)
+{
+    int best = 4;
+    int64_t best_cost = -1;
+    for (int nb = 4; nb >= 1; --nb) {
+        const int bix = 32 * nb / D;
+        if (bix < 1) continue;
+        const int64_t cost = (int64_t)((I + bix - 1) / bix) * nb;
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = nb; }
+    }
+    return best;
+}
+
+template <int D, int VEC>
+void pick_dx_nb(const float* x, const float* C, const float* dy, float* dx, int B, int I, int O, hipStream_t s)
+{
+    switch (dx_column_blocks(I, D)) {
+        case 1: launch_dx<D, 1, VEC>(x, C, dy, dx, B, I, O, s); break;
+        case 2: launch_dx<D, 2, VEC>(x, C, dy, dx, B, I, O, s); break;
+        case 3: launch_dx<D, 3, VEC>(x, C, dy, dx, B, I, O, s); break;
+        default: launch_dx<D, 4, VEC>(x, C, dy, dx, B, I, O, s); break;
+    }
+}
+
 template <int D>
 void pick_dx(const float* x, const float* C, const float* dy, float* dx, int B, int I, int O, hipStream_t s)
 {
     const bool vec = aligned16(C) && aligned16(dy) && O % 4 == 0;   // O%4==0 makes every slab run 16-byte aligned
-    if (vec) launch_dx<D, 4>(x, C, dy, dx, B, I, O, s);
-    else launch_dx<D, 1>(x, C, dy, dx, B, I, O, s);
+    if (vec) pick_dx_nb<D, 4>(x, C, dy, dx, B, I, O, s);
+    else pick_dx_nb<D, 1>(x, C, dy, dx, B, I, O, s);
 }
 
 bool shape_fits(int64_t B, int I, int O, int d)
@@ -170,7 +215,7 @@ NarrowPlan plan_narrow(int64_t B, int I)
     p.G = 8;
     while (p.G < 64 && p.G < I) p.G *= 2;
     const int quantum = NARROW_RB * (NARROW_THREADS / p.G);
-    int64_t rows = (B + 1023) / 1024;                       // about 1024 workgroups
+    int64_t rows = (B + 511) / 512;                         // about 512 workgroups
     rows = (rows + quantum - 1) / quantum * quantum;
     if (rows < quantum) rows = quantum;
     p.rows_per_wg = (int)rows;
@@ -191,11 +236,10 @@ template <int D, int O>
 void launch_narrow_bwd(const float* x, const float* C, const float* dy, float* dx, float* dC, float* partial,
                        int B, int I, hipStream_t s)
 {
-    constexpr int FPL = NarrowFpl<O>::value;
     const NarrowPlan p = plan_narrow(B, I);
-    const int blocks_i = (I + p.G * FPL - 1) / (p.G * FPL);
+    const int blocks_i = (I + p.G - 1) / p.G;
     hipLaunchKernelGGL((narrow_bwd_kernel<D, O>), dim3((unsigned)p.slices, (unsigned)blocks_i),
-                       dim3(NARROW_THREADS), (size_t)NARROW_THREADS * FPL * O * (D + 1) * sizeof(float), s, x, C, dy,
+                       dim3(NARROW_THREADS), (size_t)NARROW_THREADS * O * (D + 1) * sizeof(float), s, x, C, dy,
                        dx, dC ? partial : nullptr, B, I, p.G, p.rows_per_wg);
     if (dC) {
         const int n = I * O * (D + 1);

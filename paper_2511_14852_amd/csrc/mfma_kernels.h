@@ -53,10 +53,11 @@ __device__ __forceinline__ floatx16 zero16()
 __device__ __forceinline__ int mfma_row(int r, int h) { return 8 * (r >> 2) + 4 * h + (r & 3); }
 
 // ============================================================== forward
-template <int D_, int BN_, int BI_, int VEC_>
+template <int D_, int BN_, int BI_, int VEC_, int PIPE_ = 0>
 struct FwdCfg {
     static constexpr int D = D_, K = D_ + 1, KP = K | 1;      // KP: odd per-output stride in LDS
     static constexpr int BM = 128, BN = BN_, BI = BI_, VEC = VEC_;
+    static constexpr bool PIPE = PIPE_ != 0;                   // producer work inside the MFMA stream
     static constexpr int WN = BN / 2, TM = 2, TN = WN / 32;
     static constexpr int CH = BI * K;                          // contraction terms per chunk
     static constexpr int SA = CH | 1;                          // odd row stride of the Phi tile
@@ -166,18 +167,9 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
 #pragma unroll
         for (int j = 0; j < TN; ++j) { acc[i][j] = zero16(); total[i][j] = zero16(); }
 
-    const int n_chunks = (I + BI - 1) / BI;
-    load_chunk(0);
-    for (int c = 0; c < n_chunks; ++c) {
-        float* sA = lds + (c & 1) * Cfg::STAGE;
-        float* sB = sA + Cfg::A_FLOATS;
-        store_chunk(sA, sB);
-        if (c + 1 < n_chunks) load_chunk((c + 1) * BI);
-        __syncthreads();
-        const float* pA = sA + aBase;
-        const float* pB = sB + bBase;
+    auto mfma_steps = [&](const float* pA, const float* pB, int s0, int s1) {
 #pragma unroll
-        for (int s = 0; s < Cfg::NSTEP; ++s) {
+        for (int s = s0; s < s1; ++s) {
             const int ih = s / K, k = s % K;
             float a[TM], b[TN];
 #pragma unroll
@@ -189,11 +181,43 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
         }
+    };
+    auto fold = [&](int c) {
         if ((c + 1) % Cfg::FOLD == 0) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) { total[i][j] += acc[i][j]; acc[i][j] = zero16(); }
+        }
+    };
+
+    const int n_chunks = (I + BI - 1) / BI;
+    load_chunk(0);
+    if constexpr (Cfg::PIPE) {
+        // chunk c+1 is generated and written to the other LDS stage between the two halves of
+        // chunk c's MFMA sequence, so the vector-ALU work runs while the matrix pipe is busy
+        store_chunk(lds, lds + Cfg::A_FLOATS);
+        if (n_chunks > 1) load_chunk(BI);
+        for (int c = 0; c < n_chunks; ++c) {
+            __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
+            float* sA = lds + (c & 1) * Cfg::STAGE;
+            float* sB = sA + Cfg::A_FLOATS;
+            float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
+            mfma_steps(sA + aBase, sB + bBase, 0, Cfg::NSTEP / 2);
+            if (c + 1 < n_chunks) store_chunk(nA, nA + Cfg::A_FLOATS);
+            if (c + 2 < n_chunks) load_chunk((c + 2) * BI);
+            mfma_steps(sA + aBase, sB + bBase, Cfg::NSTEP / 2, Cfg::NSTEP);
+            fold(c);
+        }
+    } else {
+        for (int c = 0; c < n_chunks; ++c) {
+            float* sA = lds + (c & 1) * Cfg::STAGE;
+            float* sB = sA + Cfg::A_FLOATS;
+            store_chunk(sA, sB);
+            if (c + 1 < n_chunks) load_chunk((c + 1) * BI);
+            __syncthreads();
+            mfma_steps(sA + aBase, sB + bBase, 0, Cfg::NSTEP);
+            fold(c);
         }
     }
 
@@ -414,19 +438,20 @@ dC_combine_kernel(const float* __restrict__ partial, float* __restrict__ dC, int
 }
 
 // ============================================================ input gradient
-template <int D_, int VEC_>
+template <int D_, int NB_, int VEC_>
 struct DxCfg {
-    static constexpr int D = D_, K = D_ + 1, VEC = VEC_;
+    static constexpr int D = D_, K = D_ + 1, NB = NB_, VEC = VEC_;
     static constexpr int BM = 128;
-    static constexpr int BIX = 128 / D;                 // input features per tile
-    static constexpr int BNR = BIX * D;                 // real columns (i, k=1..D) of the 128-col tile
+    static constexpr int BNC = 32 * NB;                 // tile columns (NB MFMA column blocks)
+    static constexpr int BIX = BNC / D;                 // input features per tile
+    static constexpr int BNR = BIX * D;                 // real columns (i, k=1..D)
     static constexpr int BO = 32;                       // outputs per contraction chunk
     static constexpr int SAX = BO + 1;                  // odd row stride of the dy tile
     static constexpr int SSX = BO * K + (D % 32);       // slab stride = D (mod 32): column n hits bank n
     static constexpr int A_FLOATS = (BM * SAX + 3) & ~3;
     static constexpr int B_FLOATS = (BIX * SSX + 3) & ~3;
     static constexpr int STAGE = A_FLOATS + B_FLOATS;
-    static constexpr int SG = 129;                      // row stride of the G tile in the epilogue
+    static constexpr int SG = BNC + 1;                  // row stride of the G tile in the epilogue
     static constexpr int LDS_FLOATS = (2 * STAGE > BM * SG) ? 2 * STAGE : BM * SG;
     static constexpr int LDS_BYTES = LDS_FLOATS * 4;
     static constexpr int NSTEP = BO / 2;
@@ -436,22 +461,23 @@ struct DxCfg {
     static constexpr int NEB = BIX * BO * K;
     static constexpr int CPT = (NEB / VEC + MFMA_THREADS - 1) / MFMA_THREADS;
     static constexpr int EPT = (BM * BIX + MFMA_THREADS - 1) / MFMA_THREADS;
-    static_assert(D >= 1, "degree 0 has no input gradient");
+    static_assert(D >= 1 && BIX >= 1, "degree 0 has no input gradient");
     static_assert((BO * K) % VEC == 0 && NEA % (VEC * MFMA_THREADS) == 0, "vector width");
 };
 
 // dx[b,i] = (1-u^2) sum_o dy[b,o] sum_{k>=1} C[i,o,k] T_k'(u),  u = tanh x[b,i]
 // (paper Alg. 2, x_grad, with the chain rule through tanh).  The sum over o runs on the
 // matrix cores as G = dy * W^T; the sum over k is the epilogue.  No atomics: one
-// workgroup owns all outputs o for its (b,i) tile.  grid.x = ceil(B/128) * ceil(I/BIX).
+// workgroup owns all outputs o for its (b,i) tile.  Each of the four waves takes 32 rows
+// and all NB column blocks; NB is chosen on the host so that the feature count wastes
+// as few columns as possible.  grid.x = ceil(B/128) * ceil(I/BIX).
 template <class Cfg>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
                float* __restrict__ dx, int B, int I, int O, int n_tiles_i)
 {
-    constexpr int D = Cfg::D, K = Cfg::K, VEC = Cfg::VEC, BIX = Cfg::BIX, BO = Cfg::BO;
+    constexpr int D = Cfg::D, K = Cfg::K, VEC = Cfg::VEC, BIX = Cfg::BIX, BO = Cfg::BO, NB = Cfg::NB;
     constexpr int SAX = Cfg::SAX, SSX = Cfg::SSX, SG = Cfg::SG;
-    constexpr int TM = 2, TN = 2;
     extern __shared__ __align__(16) float lds[];
 
     const int t = threadIdx.x;
@@ -522,65 +548,61 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
     };
 
     const int lane = t & 63, wave = t >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, h = lane >> 5;
-    const int aBase = (wm * 64 + l32) * SAX + h * (BO / 2);
-    int bBase[TN];
+    const int aBase = (wave * 32 + l32) * SAX + h * (BO / 2);
+    int bBase[NB];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = wn * 64 + j * 32 + l32;
+    for (int j = 0; j < NB; ++j) {
+        const int n = j * 32 + l32;
         int il = n / D;
         const int kq = n % D;
         if (il > BIX - 1) il = BIX - 1;            // padding columns read valid memory, result unused
         bBase[j] = il * SSX + h * (BO / 2) * K + kq + 1;
     }
 
-    floatx16 acc[TM][TN], total[TM][TN];
+    floatx16 acc[NB], total[NB];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < NB; ++j) { acc[j] = zero16(); total[j] = zero16(); }
+
+    auto mfma_steps = [&](const float* sA, const float* sB, int s0, int s1) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) { acc[i][j] = zero16(); total[i][j] = zero16(); }
+        for (int s = s0; s < s1; ++s) {
+            const float a = sA[aBase + s];
+            float b[NB];
+#pragma unroll
+            for (int j = 0; j < NB; ++j) b[j] = sB[bBase[j] + s * K];
+#pragma unroll
+            for (int j = 0; j < NB; ++j) acc[j] = mfma32(a, b[j], acc[j]);
+        }
+    };
 
     const int n_chunks = (O + BO - 1) / BO;
     load_chunk(0);
+    store_chunk(lds, lds + Cfg::A_FLOATS);
+    if (n_chunks > 1) load_chunk(BO);
     for (int c = 0; c < n_chunks; ++c) {
+        __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
         float* sA = lds + (c & 1) * Cfg::STAGE;
-        float* sB = sA + Cfg::A_FLOATS;
-        store_chunk(sA, sB);
-        if (c + 1 < n_chunks) load_chunk((c + 1) * BO);
-        __syncthreads();
-        const float* pA = sA + aBase;
-#pragma unroll
-        for (int s = 0; s < Cfg::NSTEP; ++s) {
-            float a[TM], b[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = pA[i * 32 * SAX + s];
-#pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = sB[bBase[j] + s * K];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
-        }
+        float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
+        mfma_steps(sA, sA + Cfg::A_FLOATS, 0, Cfg::NSTEP / 2);
+        if (c + 1 < n_chunks) store_chunk(nA, nA + Cfg::A_FLOATS);
+        if (c + 2 < n_chunks) load_chunk((c + 2) * BO);
+        mfma_steps(sA, sA + Cfg::A_FLOATS, Cfg::NSTEP / 2, Cfg::NSTEP);
         if ((c + 1) % Cfg::FOLD == 0) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) { total[i][j] += acc[i][j]; acc[i][j] = zero16(); }
+            for (int j = 0; j < NB; ++j) { total[j] += acc[j]; acc[j] = zero16(); }
         }
     }
 
     // --- epilogue: G tile to LDS, then each thread finishes (row, feature) pairs
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < NB; ++j) {
+        const floatx16 v = total[j] + acc[j];
+        const int col = j * 32 + l32;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const floatx16 v = total[i][j] + acc[i][j];
-            const int col = wn * 64 + j * 32 + l32;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) lds[(wm * 64 + i * 32 + mfma_row(r, h)) * SG + col] = v[r];
-        }
+        for (int r = 0; r < 16; ++r) lds[(wave * 32 + mfma_row(r, h)) * SG + col] = v[r];
+    }
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < Cfg::EPT; ++j) {

@@ -25,7 +25,7 @@
 namespace chebykan {
 
 constexpr int NARROW_THREADS = 256;
-constexpr int NARROW_RB = 4;   // rows in flight per lane (memory-level parallelism)
+constexpr int NARROW_RB = 8;   // consecutive rows per lane group and step (memory-level parallelism)
 
 // lanes [0,G) of each aligned group of G lanes hold partial sums of one row
 __device__ __forceinline__ float group_sum(float v, int G)
@@ -34,159 +34,167 @@ __device__ __forceinline__ float group_sum(float v, int G)
     return v;
 }
 
-// grid.x workgroups, each owning `rows_per_wg` consecutive rows; G = lanes per row
-// (power of two, 8..64).  Dynamic LDS: I*O*(D+1) floats, coefficients as [k][o][i].
+// Row layout shared by both kernels: a workgroup owns `rows_per_wg` consecutive rows
+// (a multiple of NARROW_RB * 256/G); lane group rg of step `it` takes the NARROW_RB
+// consecutive rows starting at first + (it * 256/G + rg) * NARROW_RB.  G = lanes per row
+// (power of two, 8..64); lane g of a group takes input features g, g+G, ...
+
+// grid.x workgroups.  Dynamic LDS: I*O*(D+1) floats, coefficients as [k][o][i].
+// The x values of the next step are requested before the current step is computed.
 template <int D, int O>
 __global__ void __launch_bounds__(NARROW_THREADS)
 narrow_fwd_kernel(const float* __restrict__ x, const float* __restrict__ C, float* __restrict__ y,
                   int B, int I, int G, int rows_per_wg)
 {
-    constexpr int K = D + 1;
+    constexpr int K = D + 1, RB = NARROW_RB;
     extern __shared__ __align__(16) float lds[];
     const int t = threadIdx.x;
+    const int g = t % G, rg = t / G, RPW = NARROW_THREADS / G;
+    const int64_t first = (int64_t)blockIdx.x * rows_per_wg;
+    int64_t last = first + rows_per_wg;
+    if (last > B) last = B;
+    const int nj = (I + G - 1) / G;
+    // every thread runs the same number of steps (the group sums need whole waves)
+    const int n_iter = rows_per_wg / (RB * RPW);
+    const int n_items = n_iter * nj;
+
+    auto load_item = [&](int w, float (&xv)[RB]) {
+        const int it = w / nj, j = w % nj;
+        const int i = g + j * G;
+        const int64_t row0 = first + ((int64_t)it * RPW + rg) * RB;
+#pragma unroll
+        for (int r = 0; r < RB; ++r) xv[r] = (i < I && row0 + r < last) ? x[(row0 + r) * I + i] : 0.0f;
+    };
+
+    float xnext[RB];
+    load_item(0, xnext);
     for (int e = t; e < I * O * K; e += NARROW_THREADS) {
         const int k = e % K, o = (e / K) % O, i = e / (K * O);
         lds[(k * O + o) * I + i] = C[e];
     }
     __syncthreads();
 
-    const int g = t % G, rg = t / G, RPW = NARROW_THREADS / G;
-    const int64_t first = (int64_t)blockIdx.x * rows_per_wg;
-    int64_t last = first + rows_per_wg;
-    if (last > B) last = B;
-    const int nj = (I + G - 1) / G;
-
-    // every thread runs the same number of iterations (the group sums below need whole waves)
-    const int n_iter = (rows_per_wg + NARROW_RB * RPW - 1) / (NARROW_RB * RPW);
-    for (int it = 0; it < n_iter; ++it) {
-        const int64_t row0 = first + rg + (int64_t)it * NARROW_RB * RPW;
-        float part[NARROW_RB][O];
+    float part[RB][O];
+    for (int w = 0; w < n_items; ++w) {
+        float xv[RB];
 #pragma unroll
-        for (int r = 0; r < NARROW_RB; ++r)
+        for (int r = 0; r < RB; ++r) xv[r] = xnext[r];
+        if (w + 1 < n_items) load_item(w + 1, xnext);
+        const int it = w / nj, j = w % nj;
+        const int i = g + j * G;
+        if (j == 0) {
 #pragma unroll
-            for (int o = 0; o < O; ++o) part[r][o] = 0.0f;
-        for (int j = 0; j < nj; ++j) {
-            const int i = g + j * G;
-            if (i < I) {
-                float xv[NARROW_RB];
+            for (int r = 0; r < RB; ++r)
 #pragma unroll
-                for (int r = 0; r < NARROW_RB; ++r) {
-                    const int64_t row = row0 + (int64_t)r * RPW;
-                    xv[r] = row < last ? x[row * I + i] : 0.0f;
-                }
-                float cs[O][K];
+                for (int o = 0; o < O; ++o) part[r][o] = 0.0f;
+        }
+        if (i < I) {
+            float cs[O][K];
 #pragma unroll
-                for (int o = 0; o < O; ++o)
+            for (int o = 0; o < O; ++o)
 #pragma unroll
-                    for (int k = 0; k < K; ++k) cs[o][k] = lds[(k * O + o) * I + i];
+                for (int k = 0; k < K; ++k) cs[o][k] = lds[(k * O + o) * I + i];
 #pragma unroll
-                for (int r = 0; r < NARROW_RB; ++r) {
-                    float T[K];
-                    cheb_T<D>(normalise(xv[r]), T);
+            for (int r = 0; r < RB; ++r) {
+                float T[K];
+                cheb_T<D>(normalise(xv[r]), T);
 #pragma unroll
-                    for (int o = 0; o < O; ++o) {
-                        float s = 0.0f;
+                for (int o = 0; o < O; ++o) {
+                    float s = 0.0f;
 #pragma unroll
-                        for (int k = 0; k < K; ++k) s = fmaf(cs[o][k], T[k], s);
-                        part[r][o] += s;
-                    }
+                    for (int k = 0; k < K; ++k) s = fmaf(cs[o][k], T[k], s);
+                    part[r][o] += s;
                 }
             }
         }
+        if (j == nj - 1) {
+            const int64_t row0 = first + ((int64_t)it * RPW + rg) * RB;
 #pragma unroll
-        for (int r = 0; r < NARROW_RB; ++r) {
-            const int64_t row = row0 + (int64_t)r * RPW;
+            for (int r = 0; r < RB; ++r)
 #pragma unroll
-            for (int o = 0; o < O; ++o) {
-                const float s = group_sum(part[r][o], G);
-                if (g == 0 && row < last) y[row * O + o] = s;
-            }
+                for (int o = 0; o < O; ++o) {
+                    const float s = group_sum(part[r][o], G);
+                    if (g == 0 && row0 + r < last) y[(row0 + r) * O + o] = s;
+                }
         }
     }
 }
 
-template <int O> struct NarrowFpl { static constexpr int value = (4 / O) > 0 ? (4 / O) : 1; };
-
-// grid = (row slices, feature blocks of G*FPL features).  Writes dx (if non-null) and
-// partial[slice][i][o][k] (if non-null).  Dynamic LDS: 256*FPL*O*(D+1) floats.
+// grid = (row slices, ceil(I/G) feature groups).  Writes dx (if non-null) and
+// partial[slice][i][o][k] (if non-null).  Dynamic LDS: 256*O*(D+1) floats.
 template <int D, int O>
 __global__ void __launch_bounds__(NARROW_THREADS)
 narrow_bwd_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
                   float* __restrict__ dx, float* __restrict__ partial, int B, int I, int G, int rows_per_wg)
 {
-    constexpr int K = D + 1, FPL = NarrowFpl<O>::value;
+    constexpr int K = D + 1, RB = NARROW_RB;
     extern __shared__ __align__(16) float lds[];
     const int t = threadIdx.x;
     const int g = t % G, rg = t / G, RPW = NARROW_THREADS / G;
-    const int i_first = blockIdx.y * G * FPL + g;
+    const int i = blockIdx.y * G + g;
+    const bool i_ok = i < I;
     const int64_t first = (int64_t)blockIdx.x * rows_per_wg;
     int64_t last = first + rows_per_wg;
     if (last > B) last = B;
+    const int n_iter = rows_per_wg / (RB * RPW);
 
-    // feature groups of this block that exist at all (uniform over the workgroup)
-    int nj = (I - (int)blockIdx.y * G * FPL + G - 1) / G;
-    if (nj > FPL) nj = FPL;
-
-    float creg[FPL][O][D > 0 ? D : 1];   // C[i,o,1..D]: only the input gradient needs coefficients
-    float acc[FPL][O][K];
+    auto load_item = [&](int it, float (&xv)[RB], float (&gv)[RB][O]) {
+        const int64_t row0 = first + ((int64_t)it * RPW + rg) * RB;
 #pragma unroll
-    for (int j = 0; j < FPL; ++j) {
-        const int i = i_first + j * G;
+        for (int r = 0; r < RB; ++r) {
+            const bool ok = row0 + r < last;
+            xv[r] = (ok && i_ok) ? x[(row0 + r) * I + i] : 0.0f;
 #pragma unroll
-        for (int o = 0; o < O; ++o) {
-#pragma unroll
-            for (int k = 0; k < K; ++k) acc[j][o][k] = 0.0f;
-#pragma unroll
-            for (int k = 1; k < K; ++k) creg[j][o][k - 1] = (i < I && dx) ? C[((int64_t)i * O + o) * K + k] : 0.0f;
+            for (int o = 0; o < O; ++o) gv[r][o] = ok ? dy[(row0 + r) * O + o] : 0.0f;   // zero rows add nothing
         }
+    };
+
+    float xnext[RB], gnext[RB][O];
+    load_item(0, xnext, gnext);
+
+    float creg[O][D > 0 ? D : 1];   // C[i,o,1..D]: only the input gradient needs coefficients
+    float acc[O][K];
+#pragma unroll
+    for (int o = 0; o < O; ++o) {
+#pragma unroll
+        for (int k = 0; k < K; ++k) acc[o][k] = 0.0f;
+#pragma unroll
+        for (int k = 1; k < K; ++k) creg[o][k - 1] = (i_ok && dx) ? C[((int64_t)i * O + o) * K + k] : 0.0f;
     }
 
-    const int n_iter = (rows_per_wg + NARROW_RB * RPW - 1) / (NARROW_RB * RPW);
     for (int it = 0; it < n_iter; ++it) {
-        const int64_t row0 = first + rg + (int64_t)it * NARROW_RB * RPW;
-        float xv[NARROW_RB][FPL];
-        float gv[NARROW_RB][O];
+        float xv[RB], gv[RB][O];
 #pragma unroll
-        for (int r = 0; r < NARROW_RB; ++r) {
-            const int64_t row = row0 + (int64_t)r * RPW;
-            const bool ok = row < last;
+        for (int r = 0; r < RB; ++r) {
+            xv[r] = xnext[r];
 #pragma unroll
-            for (int o = 0; o < O; ++o) gv[r][o] = ok ? dy[row * O + o] : 0.0f;   // zero rows add nothing
-#pragma unroll
-            for (int j = 0; j < FPL; ++j) {
-                const int i = i_first + j * G;
-                xv[r][j] = (j < nj && ok && i < I) ? x[row * I + i] : 0.0f;
-            }
+            for (int o = 0; o < O; ++o) gv[r][o] = gnext[r][o];
         }
+        if (it + 1 < n_iter) load_item(it + 1, xnext, gnext);
+        const int64_t row0 = first + ((int64_t)it * RPW + rg) * RB;
 #pragma unroll
-        for (int r = 0; r < NARROW_RB; ++r) {
-            const int64_t row = row0 + (int64_t)r * RPW;
+        for (int r = 0; r < RB; ++r) {
+            float slope;
+            const float u = normalise(xv[r], slope);
+            float T[K];
+            cheb_T<D>(u, T);
 #pragma unroll
-            for (int j = 0; j < FPL; ++j) {
-                if (j >= nj) continue;
-                const int i = i_first + j * G;
-                float slope;
-                const float u = normalise(xv[r][j], slope);
-                float T[K];
-                cheb_T<D>(u, T);
+            for (int o = 0; o < O; ++o)
 #pragma unroll
-                for (int o = 0; o < O; ++o)
+                for (int k = 0; k < K; ++k) acc[o][k] = fmaf(T[k], gv[r][o], acc[o][k]);
+            if constexpr (D >= 1) {
+                if (dx && i_ok && row0 + r < last) {
+                    float dT[D];
+                    cheb_dT<D>(u, dT);
+                    float s = 0.0f;
 #pragma unroll
-                    for (int k = 0; k < K; ++k) acc[j][o][k] = fmaf(T[k], gv[r][o], acc[j][o][k]);
-                if constexpr (D >= 1) {
-                    if (dx && row < last && i < I) {
-                        float dT[D];
-                        cheb_dT<D>(u, dT);
-                        float s = 0.0f;
+                    for (int o = 0; o < O; ++o) {
+                        float inner = 0.0f;
 #pragma unroll
-                        for (int o = 0; o < O; ++o) {
-                            float inner = 0.0f;
-#pragma unroll
-                            for (int k = 0; k < D; ++k) inner = fmaf(creg[j][o][k], dT[k], inner);
-                            s = fmaf(gv[r][o], inner, s);
-                        }
-                        dx[row * I + i] = slope * s;
+                        for (int k = 0; k < D; ++k) inner = fmaf(creg[o][k], dT[k], inner);
+                        s = fmaf(gv[r][o], inner, s);
                     }
+                    dx[(row0 + r) * I + i] = slope * s;
                 }
             }
         }
@@ -194,27 +202,19 @@ narrow_bwd_kernel(const float* __restrict__ x, const float* __restrict__ C, cons
 
     if (partial) {
         // row groups of this workgroup, added in index order
-        constexpr int PER = FPL * O * K;
+        constexpr int PER = O * K;
 #pragma unroll
-        for (int j = 0; j < FPL; ++j)
+        for (int o = 0; o < O; ++o)
 #pragma unroll
-            for (int o = 0; o < O; ++o)
-#pragma unroll
-                for (int k = 0; k < K; ++k) lds[(rg * PER + (j * O + o) * K + k) * G + g] = acc[j][o][k];
+            for (int k = 0; k < K; ++k) lds[(rg * PER + o * K + k) * G + g] = acc[o][k];
         __syncthreads();
-        if (rg == 0) {
-            float* out = partial + (int64_t)blockIdx.x * I * O * K;
+        if (rg == 0 && i_ok) {
+            float* out = partial + (int64_t)blockIdx.x * I * O * K + (int64_t)i * O * K;
 #pragma unroll
-            for (int j = 0; j < FPL; ++j) {
-                const int i = i_first + j * G;
-#pragma unroll
-                for (int o = 0; o < O; ++o)
-#pragma unroll
-                    for (int k = 0; k < K; ++k) {
-                        float s = 0.0f;
-                        for (int q = 0; q < RPW; ++q) s += lds[(q * PER + (j * O + o) * K + k) * G + g];
-                        if (i < I) out[((int64_t)i * O + o) * K + k] = s;
-                    }
+            for (int e = 0; e < PER; ++e) {
+                float s = 0.0f;
+                for (int q = 0; q < RPW; ++q) s += lds[(q * PER + e) * G + g];
+                out[e] = s;
             }
         }
     }
