@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--family", type=int, default=0, help="kernel family override (0 auto)")
+    ap.add_argument("--probe", type=int, default=0,
+                    help="counter-collection mode for rocprofv3 --pmc: run this many steps of the split calls plus "
+                         "one plain 256 MiB device copy (the calibration kernel of known size), then exit")
     return ap.parse_args()
 
 
@@ -155,6 +158,18 @@ def main():
     w = wl.WORKLOADS[args.workload]
     st = Stack(w, max(1, args.rotate), torch, binding, wl)
     B = w.batch
+
+    if args.probe > 0:
+        src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        with torch.cuda.stream(st.stream):
+            dst.copy_(src)                      # reads 256 MiB, writes 256 MiB
+        for k in range(args.probe):
+            for (_tag, _l, thunk) in st.calls(k):
+                thunk()
+        torch.cuda.synchronize()
+        print(json.dumps({"probe_steps": args.probe, "copy_bytes_each_way": src.numel() * 4}), flush=True)
+        return
 
     # ---- throughput: W warm-up steps, then exactly K timed steps
     for k in range(args.warmup):

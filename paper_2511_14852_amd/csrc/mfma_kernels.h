@@ -53,11 +53,18 @@ __device__ __forceinline__ floatx16 zero16()
 __device__ __forceinline__ int mfma_row(int r, int h) { return 8 * (r >> 2) + 4 * h + (r & 3); }
 
 // ============================================================== forward
-template <int D_, int BN_, int BI_, int VEC_, int PIPE_ = 0>
+// MODE 0: every wave both produces and consumes (256 threads, 2 workgroups per CU).
+// MODE 1: same, with the producer work placed inside the MFMA sequence.
+// MODE 2: wave-specialised, 512 threads: waves 0-3 only issue MFMAs, waves 4-7 only load,
+//         generate the basis and fill the other LDS stage (1 workgroup per CU, larger chunks).
+template <int D_, int BN_, int BI_, int VEC_, int MODE_ = 0>
 struct FwdCfg {
     static constexpr int D = D_, K = D_ + 1, KP = K | 1;      // KP: odd per-output stride in LDS
     static constexpr int BM = 128, BN = BN_, BI = BI_, VEC = VEC_;
-    static constexpr bool PIPE = PIPE_ != 0;                   // producer work inside the MFMA stream
+    static constexpr int MODE = MODE_;
+    static constexpr bool PIPE = MODE_ == 1;                   // producer work inside the MFMA stream
+    static constexpr bool WS = MODE_ == 2;                     // wave-specialised
+    static constexpr int THREADS = WS ? 2 * MFMA_THREADS : MFMA_THREADS;
     static constexpr int WN = BN / 2, TM = 2, TN = WN / 32;
     static constexpr int CH = BI * K;                          // contraction terms per chunk
     static constexpr int SA = CH | 1;                          // odd row stride of the Phi tile
@@ -78,7 +85,7 @@ struct FwdCfg {
 // y[b,o] = sum_i sum_k C[i,o,k] T_k(tanh x[b,i])      (paper Eq. 2-3; Alg. 1 as a function)
 // grid.x = ceil(B/128) * ceil(O/BN), output-tile index fastest.
 template <class Cfg>
-__global__ void __launch_bounds__(MFMA_THREADS, 2)
+__global__ void __launch_bounds__(Cfg::THREADS, 2)
 fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float* __restrict__ y,
                 int B, int I, int O, int n_tiles_o)
 {
@@ -86,7 +93,9 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
     constexpr int SA = Cfg::SA, SS = Cfg::SS, TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
     extern __shared__ __align__(16) float lds[];
 
-    const int t = threadIdx.x;
+    const int t = threadIdx.x & (MFMA_THREADS - 1);            // index inside the role
+    const bool producer = !Cfg::WS || threadIdx.x >= MFMA_THREADS;
+    const bool consumer = !Cfg::WS || threadIdx.x < MFMA_THREADS;
     const int tile_o = blockIdx.x % n_tiles_o;
     const int tile_b = blockIdx.x / n_tiles_o;
     const int b0 = tile_b * Cfg::BM;
@@ -192,8 +201,29 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
     };
 
     const int n_chunks = (I + BI - 1) / BI;
-    load_chunk(0);
-    if constexpr (Cfg::PIPE) {
+    if constexpr (Cfg::WS) {
+        // producers run one chunk ahead of the consumers; one barrier per chunk hands a
+        // finished stage over and releases the stage the consumers have just read
+        if (producer) {
+            load_chunk(0);
+            store_chunk(lds, lds + Cfg::A_FLOATS);
+            if (n_chunks > 1) load_chunk(BI);
+        }
+        __syncthreads();
+        for (int c = 0; c < n_chunks; ++c) {
+            float* sA = lds + (c & 1) * Cfg::STAGE;
+            float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
+            if (producer) {
+                if (c + 1 < n_chunks) store_chunk(nA, nA + Cfg::A_FLOATS);
+                if (c + 2 < n_chunks) load_chunk((c + 2) * BI);
+            } else {
+                mfma_steps(sA + aBase, sA + Cfg::A_FLOATS + bBase, 0, Cfg::NSTEP);
+                fold(c);
+            }
+            __syncthreads();
+        }
+    } else if constexpr (Cfg::PIPE) {
+        load_chunk(0);
         // chunk c+1 is generated and written to the other LDS stage between the two halves of
         // chunk c's MFMA sequence, so the vector-ALU work runs while the matrix pipe is busy
         store_chunk(lds, lds + Cfg::A_FLOATS);
@@ -210,6 +240,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
             fold(c);
         }
     } else {
+        load_chunk(0);
         for (int c = 0; c < n_chunks; ++c) {
             float* sA = lds + (c & 1) * Cfg::STAGE;
             float* sB = sA + Cfg::A_FLOATS;
@@ -221,6 +252,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
         }
     }
 
+    if (!consumer) return;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
