@@ -36,38 +36,28 @@ void allow_lds(KernelT kernel, int bytes)
 }
 
 // ------------------------------------------------------------------ forward
-template <int D, int BN, int BI, int VEC, int MODE>
-void launch_fwd_cfg(const float* x, const float* C, float* y, int B, int I, int O, hipStream_t s)
+template <int D, int BN, int BI, int VEC>
+void launch_fwd(const float* x, const float* C, float* y, int B, int I, int O, hipStream_t s)
 {
-    using Cfg = FwdCfg<D, BN, BI, VEC, MODE>;
+    using Cfg = FwdCfg<D, BN, BI, VEC>;
     static bool once = (allow_lds(fwd_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
     (void)once;
     const int tiles_o = (O + BN - 1) / BN;
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * tiles_o;
-    hipLaunchKernelGGL(fwd_mfma_kernel<Cfg>, dim3((unsigned)tiles), dim3(Cfg::THREADS), Cfg::LDS_BYTES, s, x, C,
+    hipLaunchKernelGGL(fwd_mfma_kernel<Cfg>, dim3((unsigned)tiles), dim3(MFMA_THREADS), Cfg::LDS_BYTES, s, x, C,
                        y, B, I, O, tiles_o);
 }
 
-// BI: input features per chunk for the 256-thread kernel, BIW: for the wave-specialised one
-template <int D, int BN, int BI, int BIW, int VEC>
-void launch_fwd(const float* x, const float* C, float* y, int B, int I, int O, hipStream_t s)
-{
-    const int tune = tune_flags();
-    if (tune & 1) launch_fwd_cfg<D, BN, BI, VEC, 0>(x, C, y, B, I, O, s);
-    else if (tune & 2) launch_fwd_cfg<D, BN, BI, VEC, 1>(x, C, y, B, I, O, s);
-    else launch_fwd_cfg<D, BN, BIW, VEC, 2>(x, C, y, B, I, O, s);
-}
-
-template <int D, int BI, int BIW>
+template <int D, int BI>
 void pick_fwd(const float* x, const float* C, float* y, int B, int I, int O, hipStream_t s)
 {
     const bool vec = aligned16(C) && ((int64_t)O * (D + 1)) % 4 == 0;
     if (O <= 64) {
-        if (vec) launch_fwd<D, 64, BI, BIW, 4>(x, C, y, B, I, O, s);
-        else launch_fwd<D, 64, BI, BIW, 1>(x, C, y, B, I, O, s);
+        if (vec) launch_fwd<D, 64, BI, 4>(x, C, y, B, I, O, s);
+        else launch_fwd<D, 64, BI, 1>(x, C, y, B, I, O, s);
     } else {
-        if (vec) launch_fwd<D, 128, BI, BIW, 4>(x, C, y, B, I, O, s);
-        else launch_fwd<D, 128, BI, BIW, 1>(x, C, y, B, I, O, s);
+        if (vec) launch_fwd<D, 128, BI, 4>(x, C, y, B, I, O, s);
+        else launch_fwd<D, 128, BI, 1>(x, C, y, B, I, O, s);
     }
 }
 
@@ -193,6 +183,7 @@ bool shape_fits(int64_t B, int I, int O, int d)
 {
     if (!degree_specialised(d)) return false;
     if (B > 0x7fffffff || I > 65535) return false;
+    if ((int64_t)I * O * (d + 1) >= ((int64_t)1 << 30)) return false;   // 32-bit byte offsets into C
     // grid.x limits: tiles stay below 2^31
     const int64_t tb = (B + 127) / 128;
     if (tb * ((O + 63) / 64) > 0x7fffffff || tb * I > 0x7fffffff) return false;
@@ -302,11 +293,11 @@ bool fast_forward(const float* x, const float* C, float* y, int64_t B, int I, in
         return false;
     }
     switch (d) {
-        case 3: pick_fwd<3, 8, 16>(x, C, y, b, I, O, s); return true;
-        case 4: pick_fwd<4, 8, 12>(x, C, y, b, I, O, s); return true;
-        case 5: pick_fwd<5, 6, 10>(x, C, y, b, I, O, s); return true;
-        case 6: pick_fwd<6, 4, 8>(x, C, y, b, I, O, s); return true;
-        case 8: pick_fwd<8, 4, 8>(x, C, y, b, I, O, s); return true;
+        case 3: pick_fwd<3, 8>(x, C, y, b, I, O, s); return true;
+        case 4: pick_fwd<4, 8>(x, C, y, b, I, O, s); return true;
+        case 5: pick_fwd<5, 6>(x, C, y, b, I, O, s); return true;
+        case 6: pick_fwd<6, 4>(x, C, y, b, I, O, s); return true;
+        case 8: pick_fwd<8, 4>(x, C, y, b, I, O, s); return true;
     }
     return false;
 }

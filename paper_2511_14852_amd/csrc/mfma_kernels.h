@@ -27,6 +27,7 @@
 #include <stdint.h>
 
 #include "basis.h"
+#include "buffer_io.h"
 
 namespace chebykan {
 
@@ -53,18 +54,10 @@ __device__ __forceinline__ floatx16 zero16()
 __device__ __forceinline__ int mfma_row(int r, int h) { return 8 * (r >> 2) + 4 * h + (r & 3); }
 
 // ============================================================== forward
-// MODE 0: every wave both produces and consumes (256 threads, 2 workgroups per CU).
-// MODE 1: same, with the producer work placed inside the MFMA sequence.
-// MODE 2: wave-specialised, 512 threads: waves 0-3 only issue MFMAs, waves 4-7 only load,
-//         generate the basis and fill the other LDS stage (1 workgroup per CU, larger chunks).
-template <int D_, int BN_, int BI_, int VEC_, int MODE_ = 0>
+template <int D_, int BN_, int BI_, int VEC_>
 struct FwdCfg {
     static constexpr int D = D_, K = D_ + 1, KP = K | 1;      // KP: odd per-output stride in LDS
     static constexpr int BM = 128, BN = BN_, BI = BI_, VEC = VEC_;
-    static constexpr int MODE = MODE_;
-    static constexpr bool PIPE = MODE_ == 1;                   // producer work inside the MFMA stream
-    static constexpr bool WS = MODE_ == 2;                     // wave-specialised
-    static constexpr int THREADS = WS ? 2 * MFMA_THREADS : MFMA_THREADS;
     static constexpr int WN = BN / 2, TM = 2, TN = WN / 32;
     static constexpr int CH = BI * K;                          // contraction terms per chunk
     static constexpr int SA = CH | 1;                          // odd row stride of the Phi tile
@@ -77,15 +70,24 @@ struct FwdCfg {
     static constexpr int FOLD = (FOLD_TERMS / CH) > 0 ? (FOLD_TERMS / CH) : 1;
     static constexpr int XPT = BI / 2;                         // x values per thread per chunk
     static constexpr int NE = BI * BN * K;                     // coefficient floats per chunk
-    static constexpr int CPT = (NE / VEC + MFMA_THREADS - 1) / MFMA_THREADS;  // loads per thread
+    // every thread loads NFULL vectors of VEC floats plus NREM single floats: no ragged round
+    static constexpr int NFULL = NE / (VEC * MFMA_THREADS);
+    static constexpr int NREM = (NE - NFULL * VEC * MFMA_THREADS) / MFMA_THREADS;
+    static constexpr int NMFMA = NSTEP * TM * TN;              // MFMA instructions per chunk and wave
     static_assert(BI % 2 == 0 && BN % 64 == 0, "tile shape");
-    static_assert((BN * K) % VEC == 0, "vector width");
+    static_assert((BN * K) % VEC == 0 && NE % MFMA_THREADS == 0, "vector width");
 };
 
 // y[b,o] = sum_i sum_k C[i,o,k] T_k(tanh x[b,i])      (paper Eq. 2-3; Alg. 1 as a function)
 // grid.x = ceil(B/128) * ceil(O/BN), output-tile index fastest.
+//
+// Per chunk c: barrier; first half of chunk c's MFMA steps; generate chunk c+1 into the
+// other LDS stage; request chunk c+2 from HBM; second half of the MFMA steps.  All loads go
+// through bounds-checked buffer views (zeros beyond the tensor), so this body has no
+// branches and the vector-ALU, LDS-write and load instructions can be scheduled between
+// MFMA issues of the same wave.
 template <class Cfg>
-__global__ void __launch_bounds__(Cfg::THREADS, 2)
+__global__ void __launch_bounds__(MFMA_THREADS, 2)
 fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float* __restrict__ y,
                 int B, int I, int O, int n_tiles_o)
 {
@@ -93,47 +95,56 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
     constexpr int SA = Cfg::SA, SS = Cfg::SS, TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
     extern __shared__ __align__(16) float lds[];
 
-    const int t = threadIdx.x & (MFMA_THREADS - 1);            // index inside the role
-    const bool producer = !Cfg::WS || threadIdx.x >= MFMA_THREADS;
-    const bool consumer = !Cfg::WS || threadIdx.x < MFMA_THREADS;
+    const int t = threadIdx.x;
     const int tile_o = blockIdx.x % n_tiles_o;
     const int tile_b = blockIdx.x / n_tiles_o;
     const int b0 = tile_b * Cfg::BM;
     const int o0 = tile_o * BN;
-    const int o_valid_floats = (O - o0 < BN ? O - o0 : BN) * K;   // valid floats of one slab
 
-    // --- producer roles
+    // --- producer role.  Views are based at this tile so that 32-bit offsets suffice.
+    const int rows_here = B - b0 < Cfg::BM ? B - b0 : Cfg::BM;
+    const BufferView xv = make_view(x + (int64_t)b0 * I, (int64_t)rows_here * I);
+    // Coefficient view from this tile's first output to the end of the tensor: features past
+    // I fall outside and read as zero.  A partial output tile reads into the next feature's
+    // slab; those columns are never stored.
+    const BufferView cv = make_view(C + (int64_t)o0 * K, (int64_t)I * O * K - (int64_t)o0 * K);
     const int xr_row = t >> 1;                     // row of the tile this thread generates basis for
     const int xr_f0 = (t & 1) * Cfg::XPT;          // first feature (inside the chunk)
-    const bool row_ok = (b0 + xr_row) < B;
-    const float* xrow = x + (int64_t)(b0 + xr_row) * I;
+    const uint32_t x_off = (uint32_t)xr_row * (uint32_t)I + (uint32_t)xr_f0;
+    const uint32_t OK_ = (uint32_t)O * (uint32_t)K;
 
     float xreg[Cfg::XPT];
-    float creg[Cfg::CPT * VEC];
+    float creg[Cfg::NFULL * VEC + Cfg::NREM];
 
     auto load_chunk = [&](int i0) {
 #pragma unroll
         for (int j = 0; j < Cfg::XPT; ++j) {
-            const int i = i0 + xr_f0 + j;
-            xreg[j] = (row_ok && i < I) ? xrow[i] : 0.0f;
+            // a feature index past I would read the next row: keep that out of the basis
+            const float v = load1(xv, x_off + (uint32_t)(i0 + j));
+            xreg[j] = (i0 + xr_f0 + j < I) ? v : 0.0f;
         }
 #pragma unroll
-        for (int j = 0; j < Cfg::CPT; ++j) {
+        for (int j = 0; j < Cfg::NFULL; ++j) {
             const int e = (t + j * MFMA_THREADS) * VEC;
-            const int il = e / (BN * K);
-            const int rem = e % (BN * K);
-            const bool ok = (e < Cfg::NE) && (i0 + il < I) && (rem < o_valid_floats);
-            const float* src = C + ((int64_t)(i0 + il) * O + o0) * K + rem;
+            const uint32_t off = (uint32_t)(i0 + e / (BN * K)) * OK_ + (uint32_t)(e % (BN * K));
             if constexpr (VEC == 4) {
-                floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (ok) v = *reinterpret_cast<const floatx4*>(src);
+                const bufx4 v = load4(cv, off);
                 creg[j * 4 + 0] = v[0]; creg[j * 4 + 1] = v[1]; creg[j * 4 + 2] = v[2]; creg[j * 4 + 3] = v[3];
             } else {
-                creg[j] = ok ? *src : 0.0f;
+                creg[j] = load1(cv, off);
             }
+        }
+#pragma unroll
+        for (int j = 0; j < Cfg::NREM; ++j) {
+            const int e = Cfg::NFULL * VEC * MFMA_THREADS + t + j * MFMA_THREADS;
+            creg[Cfg::NFULL * VEC + j] = load1(cv, (uint32_t)(i0 + e / (BN * K)) * OK_ + (uint32_t)(e % (BN * K)));
         }
     };
 
+    auto store_coeff = [&](float* sB, int e, float v) {
+        const int il = e / (BN * K), rem = e % (BN * K);
+        sB[il * SS + (rem / K) * KP + rem % K] = v;
+    };
     auto store_chunk = [&](float* sA, float* sB) {
 #pragma unroll
         for (int j = 0; j < Cfg::XPT; ++j) {
@@ -144,26 +155,22 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
             for (int k = 0; k < K; ++k) dst[k] = T[k];
         }
 #pragma unroll
-        for (int j = 0; j < Cfg::CPT; ++j) {
+        for (int j = 0; j < Cfg::NFULL; ++j) {
             const int e = (t + j * MFMA_THREADS) * VEC;
-            if (e < Cfg::NE) {
-                const int il = e / (BN * K);
-                const int rem = e % (BN * K);
-                if constexpr (VEC == 4 && KP == K) {
-                    floatx4 v = {creg[j * 4 + 0], creg[j * 4 + 1], creg[j * 4 + 2], creg[j * 4 + 3]};
-                    *reinterpret_cast<floatx4*>(sB + il * SS + rem) = v;
-                } else {
+            if constexpr (VEC == 4 && KP == K) {
+                floatx4 v = {creg[j * 4 + 0], creg[j * 4 + 1], creg[j * 4 + 2], creg[j * 4 + 3]};
+                *reinterpret_cast<floatx4*>(sB + (e / (BN * K)) * SS + e % (BN * K)) = v;
+            } else {
 #pragma unroll
-                    for (int q = 0; q < VEC; ++q) {
-                        const int n = (rem + q) / K, k = (rem + q) % K;
-                        sB[il * SS + n * KP + k] = creg[j * VEC + q];
-                    }
-                }
+                for (int q = 0; q < VEC; ++q) store_coeff(sB, e + q, creg[j * VEC + q]);
             }
         }
+#pragma unroll
+        for (int j = 0; j < Cfg::NREM; ++j)
+            store_coeff(sB, Cfg::NFULL * VEC * MFMA_THREADS + t + j * MFMA_THREADS, creg[Cfg::NFULL * VEC + j]);
     };
 
-    // --- consumer roles
+    // --- consumer role
     const int lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, h = lane >> 5;
@@ -191,68 +198,39 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
                 for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
         }
     };
-    auto fold = [&](int c) {
+
+    // Chunks past the last one are loaded and stored too: their views return zeros and the
+    // stage they land in is never read.  That keeps the loop body free of conditions.
+    const int n_chunks = (I + BI - 1) / BI;
+    load_chunk(0);
+    store_chunk(lds, lds + Cfg::A_FLOATS);
+    load_chunk(BI);
+    for (int c = 0; c < n_chunks; ++c) {
+        __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
+        float* sA = lds + (c & 1) * Cfg::STAGE;
+        float* sB = sA + Cfg::A_FLOATS;
+        float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
+        mfma_steps(sA + aBase, sB + bBase, 0, Cfg::NSTEP / 2);
+        store_chunk(nA, nA + Cfg::A_FLOATS);
+        load_chunk((c + 2) * BI);
+        mfma_steps(sA + aBase, sB + bBase, Cfg::NSTEP / 2, Cfg::NSTEP);
+        // ask the scheduler to spread the producer instructions between the MFMA issues
+#pragma unroll
+        for (int q = 0; q < Cfg::NMFMA; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+            __builtin_amdgcn_sched_group_barrier(0x402, 2, 0);   // two vector-ALU / transcendental
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+        }
         if ((c + 1) % Cfg::FOLD == 0) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) { total[i][j] += acc[i][j]; acc[i][j] = zero16(); }
         }
-    };
-
-    const int n_chunks = (I + BI - 1) / BI;
-    if constexpr (Cfg::WS) {
-        // producers run one chunk ahead of the consumers; one barrier per chunk hands a
-        // finished stage over and releases the stage the consumers have just read
-        if (producer) {
-            load_chunk(0);
-            store_chunk(lds, lds + Cfg::A_FLOATS);
-            if (n_chunks > 1) load_chunk(BI);
-        }
-        __syncthreads();
-        for (int c = 0; c < n_chunks; ++c) {
-            float* sA = lds + (c & 1) * Cfg::STAGE;
-            float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
-            if (producer) {
-                if (c + 1 < n_chunks) store_chunk(nA, nA + Cfg::A_FLOATS);
-                if (c + 2 < n_chunks) load_chunk((c + 2) * BI);
-            } else {
-                mfma_steps(sA + aBase, sA + Cfg::A_FLOATS + bBase, 0, Cfg::NSTEP);
-                fold(c);
-            }
-            __syncthreads();
-        }
-    } else if constexpr (Cfg::PIPE) {
-        load_chunk(0);
-        // chunk c+1 is generated and written to the other LDS stage between the two halves of
-        // chunk c's MFMA sequence, so the vector-ALU work runs while the matrix pipe is busy
-        store_chunk(lds, lds + Cfg::A_FLOATS);
-        if (n_chunks > 1) load_chunk(BI);
-        for (int c = 0; c < n_chunks; ++c) {
-            __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
-            float* sA = lds + (c & 1) * Cfg::STAGE;
-            float* sB = sA + Cfg::A_FLOATS;
-            float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
-            mfma_steps(sA + aBase, sB + bBase, 0, Cfg::NSTEP / 2);
-            if (c + 1 < n_chunks) store_chunk(nA, nA + Cfg::A_FLOATS);
-            if (c + 2 < n_chunks) load_chunk((c + 2) * BI);
-            mfma_steps(sA + aBase, sB + bBase, Cfg::NSTEP / 2, Cfg::NSTEP);
-            fold(c);
-        }
-    } else {
-        load_chunk(0);
-        for (int c = 0; c < n_chunks; ++c) {
-            float* sA = lds + (c & 1) * Cfg::STAGE;
-            float* sB = sA + Cfg::A_FLOATS;
-            store_chunk(sA, sB);
-            if (c + 1 < n_chunks) load_chunk((c + 1) * BI);
-            __syncthreads();
-            mfma_steps(sA + aBase, sB + bBase, 0, Cfg::NSTEP);
-            fold(c);
-        }
     }
 
-    if (!consumer) return;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll

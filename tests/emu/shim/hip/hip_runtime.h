@@ -96,9 +96,31 @@ inline emu_floatx16 emu_mfma_f32_32x32x2f32(float a, float b, emu_floatx16 c, in
 }
 #define __builtin_amdgcn_mfma_f32_32x32x2f32 emu_mfma_f32_32x32x2f32
 
+// stand-in for csrc/buffer_io.h (same include guard): bounds-checked loads, 0 beyond the end
+#define CHEBYKAN_BUFFER_IO_H
+namespace chebykan {
+typedef float bufx4 __attribute__((ext_vector_type(4)));
+struct BufferView { const float* base; int64_t n; };
+inline BufferView make_view(const float* base, int64_t n_floats)
+{
+    int64_t n = n_floats > 0 ? n_floats : 0;
+    if (n > 0x3fffffffLL) n = 0x3fffffffLL;
+    return BufferView{base, n};
+}
+inline float load1(const BufferView& v, uint32_t index) { return (int64_t)index < v.n ? v.base[index] : 0.0f; }
+inline bufx4 load4(const BufferView& v, uint32_t index)
+{
+    bufx4 r = {0.0f, 0.0f, 0.0f, 0.0f};
+    if ((index & 3u) != 0 || (reinterpret_cast<uintptr_t>(v.base) & 15u) != 0) { fprintf(stderr, "load4: misaligned\n"); abort(); }
+    if ((int64_t)index + 4 <= v.n) r = *reinterpret_cast<const bufx4*>(v.base + index);
+    return r;
+}
+}  // namespace chebykan
+
 inline float emu_exp2f(float x) { return exp2f(x); }
 inline float emu_rcpf(float x) { return 1.0f / x; }
 #define __builtin_amdgcn_exp2f emu_exp2f
+#define __builtin_amdgcn_sched_group_barrier(mask, size, id) ((void)0)
 #define __builtin_amdgcn_rcpf emu_rcpf
 
 // wave-level exchange: every lane of the wave must take part
