@@ -61,6 +61,8 @@ void pick_fwd(const float* x, const float* C, float* y, int B, int I, int O, hip
     }
 }
 
+bool use_narrow_shape(int I, int O, int d) { return O <= 4 && (int64_t)I * O * (d + 1) <= 16384; }
+
 // --------------------------------------------------------------------- dC
 struct DcPlan {
     int bn;              // output tile width
@@ -184,6 +186,11 @@ bool shape_fits(int64_t B, int I, int O, int d)
     if (!degree_specialised(d)) return false;
     if (B > 0x7fffffff || I > 65535) return false;
     if ((int64_t)I * O * (d + 1) >= ((int64_t)1 << 30)) return false;   // 32-bit byte offsets into C
+    // 32-bit byte offsets inside one batch slice of x and dy (a slice never exceeds B rows)
+    if (B * (int64_t)(I > O ? I : O) >= ((int64_t)1 << 30) && !use_narrow_shape(I, O, d)) {
+        const DcPlan p = plan_dC(B, I, O, d);
+        if ((int64_t)p.rows_per_slice * (I > O ? I : O) >= ((int64_t)1 << 30)) return false;
+    }
     // grid.x limits: tiles stay below 2^31
     const int64_t tb = (B + 127) / 128;
     if (tb * ((O + 63) / 64) > 0x7fffffff || tb * I > 0x7fffffff) return false;

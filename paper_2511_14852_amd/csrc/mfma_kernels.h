@@ -272,7 +272,9 @@ struct DcCfg {
 // partial[s][(i,k)][o] = sum over the rows of batch slice s of T_k(tanh x[b,i]) dy[b,o]
 // (paper Alg. 2, coeff_grad; the batch axis is split into slices whose partial sums a
 // second kernel adds in a fixed order - the two-stage reduction of Sec. 4.4 in place
-// of atomics).  grid = (tiles_ik * tiles_o, n_slices).
+// of atomics).  grid = (tiles_ik * tiles_o, n_slices).  Same chunk pipeline as the
+// forward kernel: loads through buffer views based at the slice (rows past the slice
+// read as zero dy, so they add nothing), producer work between MFMA issues.
 template <class Cfg>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ partial,
@@ -291,31 +293,39 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
     const int64_t r_begin = (int64_t)slice * rows_per_slice;
     int64_t r_end = r_begin + rows_per_slice;
     if (r_end > B) r_end = B;
+    const int64_t n_rows = r_end > r_begin ? r_end - r_begin : 0;
+
+    // Views over this slice.  A feature index past I reads the next row of x and a column
+    // past O the next row of dy: both only reach outputs that are never stored.
+    const BufferView xv = make_view(x + r_begin * I + i0, n_rows * I - i0);
+    const BufferView gv = make_view(dy + r_begin * O + o0, n_rows * O - o0);
 
     float xreg[Cfg::XPT];
     float greg[Cfg::GPT * VEC];
+    // element of the Phi^T chunk this thread generates; past-the-end threads repeat the last one
+    int xe[Cfg::XPT];
+#pragma unroll
+    for (int j = 0; j < Cfg::XPT; ++j) {
+        const int e = t + j * MFMA_THREADS;
+        xe[j] = e < Cfg::NEA ? e : Cfg::NEA - 1;
+    }
 
-    auto load_chunk = [&](int64_t r0) {
+    auto load_chunk = [&](int c) {
+        const uint32_t row0 = (uint32_t)c * BB;
 #pragma unroll
         for (int j = 0; j < Cfg::XPT; ++j) {
-            const int e = t + j * MFMA_THREADS;
-            const int bl = e / BIC, il = e % BIC;
-            const bool ok = (e < Cfg::NEA) && (r0 + bl < r_end) && (i0 + il < I);
-            xreg[j] = ok ? x[(r0 + bl) * I + i0 + il] : 0.0f;
+            const int bl = xe[j] / BIC, il = xe[j] % BIC;
+            xreg[j] = load1(xv, (row0 + (uint32_t)bl) * (uint32_t)I + (uint32_t)il);
         }
 #pragma unroll
         for (int j = 0; j < Cfg::GPT; ++j) {
             const int e = (t + j * MFMA_THREADS) * VEC;
-            const int bl = e / BN, n = e % BN;
-            // rows past the slice and columns past O are zero: they then add nothing
-            const bool ok = (r0 + bl < r_end) && (o0 + n < O);
-            const float* src = dy + (r0 + bl) * O + o0 + n;
+            const uint32_t off = (row0 + (uint32_t)(e / BN)) * (uint32_t)O + (uint32_t)(e % BN);
             if constexpr (VEC == 4) {
-                floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (ok) v = *reinterpret_cast<const floatx4*>(src);
+                const bufx4 v = load4(gv, off);
                 greg[j * 4 + 0] = v[0]; greg[j * 4 + 1] = v[1]; greg[j * 4 + 2] = v[2]; greg[j * 4 + 3] = v[3];
             } else {
-                greg[j] = ok ? *src : 0.0f;
+                greg[j] = load1(gv, off);
             }
         }
     };
@@ -323,16 +333,13 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
     auto store_chunk = [&](float* sA, float* sB) {
 #pragma unroll
         for (int j = 0; j < Cfg::XPT; ++j) {
-            const int e = t + j * MFMA_THREADS;
-            if (e < Cfg::NEA) {
-                const int bl = e / BIC, il = e % BIC;
-                float T[D + 1];
-                cheb_T<D>(normalise(xreg[j]), T);
-                // SMA = BMR (mod 32): consecutive e land K words apart across row ends too
-                float* dst = sA + bl * SMA + il * K;
+            const int bl = xe[j] / BIC, il = xe[j] % BIC;
+            float T[D + 1];
+            cheb_T<D>(normalise(xreg[j]), T);
+            // SMA = BMR (mod 32): consecutive elements land K words apart across row ends too
+            float* dst = sA + bl * SMA + il * K;
 #pragma unroll
-                for (int k = 0; k < K; ++k) dst[k] = T[k];
-            }
+            for (int k = 0; k < K; ++k) dst[k] = T[k];
         }
 #pragma unroll
         for (int j = 0; j < Cfg::GPT; ++j) {
@@ -359,18 +366,9 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
 #pragma unroll
         for (int j = 0; j < TN; ++j) { acc[i][j] = zero16(); total[i][j] = zero16(); }
 
-    const int n_chunks = r_end > r_begin ? (int)((r_end - r_begin + BB - 1) / BB) : 0;
-    if (n_chunks > 0) load_chunk(r_begin);
-    for (int c = 0; c < n_chunks; ++c) {
-        float* sA = lds + (c & 1) * Cfg::STAGE;
-        float* sB = sA + Cfg::A_FLOATS;
-        store_chunk(sA, sB);
-        if (c + 1 < n_chunks) load_chunk(r_begin + (int64_t)(c + 1) * BB);
-        __syncthreads();
-        const float* pA = sA + aBase;
-        const float* pB = sB + bBase;
+    auto mfma_steps = [&](const float* pA, const float* pB, int s0, int s1) {
 #pragma unroll
-        for (int s = 0; s < Cfg::NSTEP; ++s) {
+        for (int s = s0; s < s1; ++s) {
             float a[TM], b[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i) a[i] = pA[s * SMA + i * 32];
@@ -380,6 +378,28 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
+        }
+    };
+
+    const int n_chunks = (int)((n_rows + BB - 1) / BB);
+    load_chunk(0);
+    store_chunk(lds, lds + Cfg::A_FLOATS);
+    load_chunk(1);
+    for (int c = 0; c < n_chunks; ++c) {
+        __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
+        float* sA = lds + (c & 1) * Cfg::STAGE;
+        float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
+        mfma_steps(sA + aBase, sA + Cfg::A_FLOATS + bBase, 0, Cfg::NSTEP / 2);
+        store_chunk(nA, nA + Cfg::A_FLOATS);
+        load_chunk(c + 2);
+        mfma_steps(sA + aBase, sA + Cfg::A_FLOATS + bBase, Cfg::NSTEP / 2, Cfg::NSTEP);
+#pragma unroll
+        for (int q = 0; q < Cfg::NSTEP * TM * TN; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+            __builtin_amdgcn_sched_group_barrier(0x402, 2, 0);   // two vector-ALU / transcendental
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
         }
         if ((c + 1) % Cfg::FOLD == 0) {
 #pragma unroll
@@ -496,38 +516,49 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
     const int b0 = tile_b * Cfg::BM;
     const int i0 = tile_i * BIX;
 
+    // Views based at this tile.  Rows past B and features past I read as zero.  Outputs past O
+    // (last chunk only) would read the next dy row / the next feature's slab: the dy value is
+    // replaced by zero there, which removes the term whatever the coefficient operand holds.
+    const int rows_here = B - b0 < Cfg::BM ? B - b0 : Cfg::BM;
+    const BufferView gv = make_view(dy + (int64_t)b0 * O, (int64_t)rows_here * O);
+    const BufferView cv = make_view(C + (int64_t)i0 * O * K, (int64_t)(I - i0) * O * K);
+    const uint32_t OK_ = (uint32_t)O * (uint32_t)K;
+
     float areg[Cfg::APT * VEC];
     float creg[Cfg::CPT * VEC];
+    // coefficient element handled in round j; past-the-end threads repeat the last vector
+    int ce[Cfg::CPT];
+#pragma unroll
+    for (int j = 0; j < Cfg::CPT; ++j) {
+        const int e = (t + j * MFMA_THREADS) * VEC;
+        ce[j] = e < Cfg::NEB ? e : Cfg::NEB - VEC;
+    }
 
     auto load_chunk = [&](int oc) {
-        const int o_valid_floats = (O - oc < BO ? O - oc : BO) * K;
 #pragma unroll
         for (int j = 0; j < Cfg::APT; ++j) {
             const int e = (t + j * MFMA_THREADS) * VEC;
             const int m = e / BO, kk = e % BO;
-            const bool ok = (b0 + m < B) && (oc + kk < O);
-            const float* src = dy + (int64_t)(b0 + m) * O + oc + kk;
+            const bool ok = oc + kk < O;
+            const uint32_t off = (uint32_t)m * (uint32_t)O + (uint32_t)(oc + kk);
             if constexpr (VEC == 4) {
-                floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (ok) v = *reinterpret_cast<const floatx4*>(src);
-                areg[j * 4 + 0] = v[0]; areg[j * 4 + 1] = v[1]; areg[j * 4 + 2] = v[2]; areg[j * 4 + 3] = v[3];
+                const bufx4 v = load4(gv, off);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) areg[j * 4 + q] = ok ? v[q] : 0.0f;
             } else {
-                areg[j] = ok ? *src : 0.0f;
+                const float v = load1(gv, off);
+                areg[j] = ok ? v : 0.0f;
             }
         }
 #pragma unroll
         for (int j = 0; j < Cfg::CPT; ++j) {
-            const int e = (t + j * MFMA_THREADS) * VEC;
-            const int il = e / (BO * K);
-            const int rem = e % (BO * K);
-            const bool ok = (e < Cfg::NEB) && (i0 + il < I) && (rem < o_valid_floats);
-            const float* src = C + ((int64_t)(i0 + il) * O + oc) * K + rem;
+            const int il = ce[j] / (BO * K), rem = ce[j] % (BO * K);
+            const uint32_t off = (uint32_t)il * OK_ + (uint32_t)oc * (uint32_t)K + (uint32_t)rem;
             if constexpr (VEC == 4) {
-                floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (ok) v = *reinterpret_cast<const floatx4*>(src);
+                const bufx4 v = load4(cv, off);
                 creg[j * 4 + 0] = v[0]; creg[j * 4 + 1] = v[1]; creg[j * 4 + 2] = v[2]; creg[j * 4 + 3] = v[3];
             } else {
-                creg[j] = ok ? *src : 0.0f;
+                creg[j] = load1(cv, off);
             }
         }
     };
@@ -542,17 +573,13 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
         }
 #pragma unroll
         for (int j = 0; j < Cfg::CPT; ++j) {
-            const int e = (t + j * MFMA_THREADS) * VEC;
-            if (e < Cfg::NEB) {
-                const int il = e / (BO * K);
-                const int rem = e % (BO * K);
-                if constexpr (VEC == 4 && SSX % 4 == 0) {
-                    floatx4 v = {creg[j * 4 + 0], creg[j * 4 + 1], creg[j * 4 + 2], creg[j * 4 + 3]};
-                    *reinterpret_cast<floatx4*>(sB + il * SSX + rem) = v;
-                } else {
+            const int il = ce[j] / (BO * K), rem = ce[j] % (BO * K);
+            if constexpr (VEC == 4 && SSX % 4 == 0) {
+                floatx4 v = {creg[j * 4 + 0], creg[j * 4 + 1], creg[j * 4 + 2], creg[j * 4 + 3]};
+                *reinterpret_cast<floatx4*>(sB + il * SSX + rem) = v;
+            } else {
 #pragma unroll
-                    for (int q = 0; q < VEC; ++q) sB[il * SSX + rem + q] = creg[j * VEC + q];
-                }
+                for (int q = 0; q < VEC; ++q) sB[il * SSX + rem + q] = creg[j * VEC + q];
             }
         }
     };
@@ -586,18 +613,27 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
         }
     };
 
+    // chunks past the last one are loaded and stored too (all-zero dy, stage never read)
     const int n_chunks = (O + BO - 1) / BO;
     load_chunk(0);
     store_chunk(lds, lds + Cfg::A_FLOATS);
-    if (n_chunks > 1) load_chunk(BO);
+    load_chunk(BO);
     for (int c = 0; c < n_chunks; ++c) {
         __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
         float* sA = lds + (c & 1) * Cfg::STAGE;
         float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
         mfma_steps(sA, sA + Cfg::A_FLOATS, 0, Cfg::NSTEP / 2);
-        if (c + 1 < n_chunks) store_chunk(nA, nA + Cfg::A_FLOATS);
-        if (c + 2 < n_chunks) load_chunk((c + 2) * BO);
+        store_chunk(nA, nA + Cfg::A_FLOATS);
+        load_chunk((c + 2) * BO);
         mfma_steps(sA, sA + Cfg::A_FLOATS, Cfg::NSTEP / 2, Cfg::NSTEP);
+#pragma unroll
+        for (int q = 0; q < Cfg::NSTEP * NB; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+            __builtin_amdgcn_sched_group_barrier(0x402, 2, 0);   // two vector-ALU
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+        }
         if ((c + 1) % Cfg::FOLD == 0) {
 #pragma unroll
             for (int j = 0; j < NB; ++j) { total[j] += acc[j]; acc[j] = zero16(); }
