@@ -27,10 +27,35 @@ namespace chebykan {
 constexpr int NARROW_THREADS = 256;
 constexpr int NARROW_RB = 8;   // consecutive rows per lane group and step (memory-level parallelism)
 
-// lanes [0,G) of each aligned group of G lanes hold partial sums of one row
+// Sum over each aligned group of G lanes (G = 8, 16, 32 or 64) with data-parallel-primitive
+// adds: shifts inside a row of 16 lanes, then the two row broadcasts of wave64.  The sum of
+// a group ends up in its LAST lane; other lanes hold partial sums.  Out-of-row sources read
+// as zero (bound_ctrl).
+__device__ __forceinline__ float dpp_add(float v, float src, int ctrl_row_mask_sel)
+{
+    // ctrl_row_mask_sel selects one of the fixed (dpp_ctrl, row_mask) pairs below: the builtin
+    // needs compile-time constants
+    int r;
+    const int x = __builtin_bit_cast(int, src);
+    switch (ctrl_row_mask_sel) {
+        case 0: r = __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, true); break;   // row_shr:1
+        case 1: r = __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, true); break;   // row_shr:2
+        case 2: r = __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, true); break;   // row_shr:4
+        case 3: r = __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, true); break;   // row_shr:8
+        case 4: r = __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, true); break;   // row_bcast:15 -> rows 1,3
+        default: r = __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, true); break;  // row_bcast:31 -> rows 2,3
+    }
+    return v + __builtin_bit_cast(float, r);
+}
+
 __device__ __forceinline__ float group_sum(float v, int G)
 {
-    for (int m = G >> 1; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    v = dpp_add(v, v, 0);
+    v = dpp_add(v, v, 1);
+    v = dpp_add(v, v, 2);
+    if (G >= 16) v = dpp_add(v, v, 3);
+    if (G >= 32) v = dpp_add(v, v, 4);
+    if (G >= 64) v = dpp_add(v, v, 5);
     return v;
 }
 
@@ -114,7 +139,7 @@ narrow_fwd_kernel(const float* __restrict__ x, const float* __restrict__ C, floa
 #pragma unroll
                 for (int o = 0; o < O; ++o) {
                     const float s = group_sum(part[r][o], G);
-                    if (g == 0 && row0 + r < last) y[(row0 + r) * O + o] = s;
+                    if (g == G - 1 && row0 + r < last) y[(row0 + r) * O + o] = s;
                 }
         }
     }

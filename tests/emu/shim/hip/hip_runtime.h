@@ -117,6 +117,38 @@ inline bufx4 load4(const BufferView& v, uint32_t index)
 }
 }  // namespace chebykan
 
+// data-parallel-primitive move as used for the row reductions: row_shr:n (0x110+n),
+// row_bcast:15 (0x142), row_bcast:31 (0x143); every lane of the wave must take part.
+inline int emu_update_dpp(int old, int src, int ctrl, int row_mask, int bank_mask, bool bound_ctrl)
+{
+    (void)bank_mask;
+    const int w = emu_tid / 64, lane = emu_tid % 64;
+    int* ex = reinterpret_cast<int*>(emu_block->exA[w]);
+    ex[lane] = src;
+    pthread_barrier_wait(&emu_block->wave_barrier[w]);
+    int result = old;
+    const int row = lane / 16, pos = lane % 16;
+    if ((row_mask >> row) & 1) {
+        if (ctrl >= 0x111 && ctrl <= 0x11f) {
+            const int n = ctrl - 0x110;
+            if (pos - n >= 0) result = ex[lane - n];
+            else if (bound_ctrl) result = 0;
+        } else if (ctrl == 0x142) {
+            if (row > 0) result = ex[row * 16 - 1];
+            else if (bound_ctrl) result = 0;
+        } else if (ctrl == 0x143) {
+            if (row >= 2) result = ex[31];
+            else if (bound_ctrl) result = 0;
+        } else {
+            fprintf(stderr, "emu_update_dpp: control %x not emulated\n", ctrl);
+            abort();
+        }
+    }
+    pthread_barrier_wait(&emu_block->wave_barrier[w]);
+    return result;
+}
+#define __builtin_amdgcn_update_dpp emu_update_dpp
+
 inline float emu_exp2f(float x) { return exp2f(x); }
 inline float emu_rcpf(float x) { return 1.0f / x; }
 #define __builtin_amdgcn_exp2f emu_exp2f
