@@ -28,6 +28,18 @@ if ROOT not in sys.path:
 PEAK_MFMA_F32_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
 
+# HBM bytes per launch of a call (all kernels of the call), from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs scaled by the same counters on a 256 MiB copy (profiles/<workload>_counters.md).
+# Keyed by (workload, call, layer); a call that is not listed reports traffic = null.
+MEASURED_TRAFFIC_BYTES = {
+    ("c2", "dC", 1): 132.2e6 + 14.8e6,
+    ("c2", "dx", 1): 117.8e6,
+    ("c2", "fwd", 1): 26.8e6,
+    ("c5", "dC", 0): 898.8e6 + 188.8e6,
+    ("c5", "fwd", 0): 753.8e6,
+    ("c5", "dx", 0): 1774.9e6,
+}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -212,7 +224,8 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(dom["gbs"] / PEAK_HBM_GBS, 4)}
-    roof["traffic"] = None
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((w.name, dom["call"], dom["layer"]))
+    roof["algorithmic_bytes"] = by
     roof["kernel"] = "%s layer %d (%d->%d)" % (dom["call"], dom["layer"], I, O)
     roof["us"] = dom["us"]
 

@@ -199,6 +199,7 @@ bool shape_fits(int64_t B, int I, int O, int d)
 
 // ------------------------------------------------------------ narrow layers
 constexpr int NARROW_MAX_OUT = 4;
+constexpr int NARROW_FWD_WGS = 2048, NARROW_BWD_WGS = 512;
 
 bool use_narrow(int64_t B, int I, int O, int d)
 {
@@ -211,13 +212,15 @@ struct NarrowPlan {
     int slices;        // workgroups along the batch
 };
 
-NarrowPlan plan_narrow(int64_t B, int I)
+// `target`: workgroups to aim for (forward likes many short ones; backward pays for every
+// slice again in the slice sum)
+NarrowPlan plan_narrow(int64_t B, int I, int target)
 {
     NarrowPlan p;
     p.G = 8;
     while (p.G < 64 && p.G < I) p.G *= 2;
     const int quantum = NARROW_RB * (NARROW_THREADS / p.G);
-    int64_t rows = (B + 511) / 512;                         // about 512 workgroups
+    int64_t rows = (B + target - 1) / target;
     rows = (rows + quantum - 1) / quantum * quantum;
     if (rows < quantum) rows = quantum;
     p.rows_per_wg = (int)rows;
@@ -229,7 +232,7 @@ NarrowPlan plan_narrow(int64_t B, int I)
 template <int D, int O>
 void launch_narrow_fwd(const float* x, const float* C, float* y, int B, int I, hipStream_t s)
 {
-    const NarrowPlan p = plan_narrow(B, I);
+    const NarrowPlan p = plan_narrow(B, I, NARROW_FWD_WGS);
     hipLaunchKernelGGL((narrow_fwd_kernel<D, O>), dim3((unsigned)p.slices), dim3(NARROW_THREADS),
                        (size_t)I * O * (D + 1) * sizeof(float), s, x, C, y, B, I, p.G, p.rows_per_wg);
 }
@@ -238,7 +241,7 @@ template <int D, int O>
 void launch_narrow_bwd(const float* x, const float* C, const float* dy, float* dx, float* dC, float* partial,
                        int B, int I, hipStream_t s)
 {
-    const NarrowPlan p = plan_narrow(B, I);
+    const NarrowPlan p = plan_narrow(B, I, NARROW_BWD_WGS);
     const int blocks_i = (I + p.G - 1) / p.G;
     hipLaunchKernelGGL((narrow_bwd_kernel<D, O>), dim3((unsigned)p.slices, (unsigned)blocks_i),
                        dim3(NARROW_THREADS), (size_t)NARROW_THREADS * O * (D + 1) * sizeof(float), s, x, C, dy,
@@ -281,7 +284,7 @@ size_t backward_workspace_bytes(int64_t B, int I, int O, int d)
 {
     if (B <= 0 || !shape_fits(B, I, O, d)) return 0;
     const size_t coeffs = (size_t)I * (size_t)(d + 1) * (size_t)O * sizeof(float);
-    if (use_narrow(B, I, O, d)) return (size_t)plan_narrow(B, I).slices * coeffs;
+    if (use_narrow(B, I, O, d)) return (size_t)plan_narrow(B, I, NARROW_BWD_WGS).slices * coeffs;
     return (size_t)plan_dC(B, I, O, d).slices * coeffs;
 }
 

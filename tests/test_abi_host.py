@@ -75,6 +75,20 @@ def test_workspace_query_is_host_only_and_checked():
                     assert binding.raw_backward(P, P, P, P, P, B, I, O, d, P, n - 1) == binding.CHEBYKAN_ERR_WORKSPACE
 
 
+def test_workspace_matches_the_documented_partial_layout():
+    """Backward workspace = slices x in x out x (degree+1) floats for some whole slice count."""
+    for (B, I, O, d) in [(256, 64, 64, 4), (65536, 8, 64, 6), (65536, 64, 1, 6), (32768, 512, 256, 3),
+                         (16000, 257, 512, 5), (16384, 1024, 1024, 8)]:
+        n = binding.chebykan_workspace_bytes(B, I, O, d, binding.CHEBYKAN_PASS_BACKWARD)
+        per_slice = I * O * (d + 1) * 4
+        assert n > 0 and n % per_slice == 0
+        assert 1 <= n // per_slice <= max(1, (B + 31) // 32)
+        assert n <= (512 << 20) + per_slice
+    # degrees without specialised kernels need no workspace; forward never does
+    assert binding.chebykan_workspace_bytes(1024, 64, 64, 15, binding.CHEBYKAN_PASS_BACKWARD) == 0
+    assert binding.chebykan_workspace_bytes(1024, 64, 64, 6, binding.CHEBYKAN_PASS_FORWARD) == 0
+
+
 def test_kernel_family_switch_round_trips():
     prev = binding.chebykan_set_kernel_family(1)
     assert binding.chebykan_set_kernel_family(prev) == 1

@@ -80,6 +80,20 @@ SMALL_SHAPES = [
     (64, 24, 40, 15),
     (32, 16, 48, 24),
     (1, 64, 64, 4),
+    # every column-block count of the input-gradient tiles (1..4) and odd feature counts
+    (200, 5, 40, 6),
+    (150, 16, 72, 6),
+    (140, 21, 64, 3),
+    (131, 10, 100, 3),
+    (260, 12, 48, 5),
+    (129, 7, 520, 8),      # contraction over more than 512 outputs (accumulator fold in dx)
+    (1200, 70, 40, 8),     # more than 512 rows per batch slice and more than 14 feature chunks (folds in dC, forward)
+    # narrow outputs with every lane-group width and several feature groups
+    (333, 8, 1, 6),
+    (100, 20, 2, 3),
+    (77, 70, 3, 8),
+    (50, 300, 4, 5),
+    (2000, 64, 1, 6),
 ]
 
 
@@ -176,6 +190,32 @@ def test_outputs_outside_the_tensor_are_untouched():
     assert oracle.rel_err(yv.view(B, O).cpu().numpy(), oracle.forward(x, C)) <= TOL
 
 
+def test_base_pointers_only_four_byte_aligned():
+    """Every tensor starts one float past a 16-byte boundary: the vectorised paths must not be taken."""
+    for (B, I, O, d) in [(300, 64, 64, 6), (200, 40, 136, 8), (150, 64, 1, 6)]:
+        x, C, dy = _inputs(B, I, O, d, seed=41 + O)
+        K = d + 1
+
+        def shifted(a):
+            buf = torch.zeros(a.size + 5, device="cuda")
+            v = buf[1:1 + a.size]
+            v.copy_(torch.from_numpy(a.reshape(-1)))
+            assert v.data_ptr() % 16 == 4
+            return buf, v.view(*a.shape)
+
+        (_, xd), (_, Cd), (_, dyd) = shifted(x), shifted(C), shifted(dy)
+        (_, y), (_, dx), (_, dC) = (shifted(np.zeros((B, O), np.float32)), shifted(np.zeros((B, I), np.float32)),
+                                    shifted(np.zeros((I, O, K), np.float32)))
+        ws = binding.alloc_workspace(B, I, O, d)
+        binding.chebykan_forward(xd, Cd, y, ws)
+        binding.chebykan_backward(xd, Cd, dyd, dx, dC, ws)
+        torch.cuda.synchronize()
+        dx_ref, dC_ref = oracle.backward(x, C, dy)
+        assert oracle.rel_err(y.cpu().numpy(), oracle.forward(x, C)) <= TOL
+        assert oracle.rel_err(dx.cpu().numpy(), dx_ref) <= TOL
+        assert oracle.rel_err(dC.cpu().numpy(), dC_ref) <= TOL
+
+
 def test_non_default_stream():
     B, I, O, d = 300, 64, 64, 4
     x, C, dy = _inputs(B, I, O, d, seed=31)
@@ -205,6 +245,18 @@ def _sampled_layer_check(x, C, dy, y, dx, dC, rng, label, n=1500):
     print("%s y=%.2e dx=%.2e dC=%.2e" % (label, e_y, e_dx, e_dC), flush=True)
     assert np.isfinite(y).all() and np.isfinite(dx).all() and np.isfinite(dC).all()
     assert e_y <= TOL and e_dx <= TOL and e_dC <= TOL, (label, e_y, e_dx, e_dC)
+
+
+def test_full_size_row_block_elementwise():
+    """Audio-shaped first layer at its real widths (257 -> 512, degree 5, x ~ N(-2, 1.5^2)): every
+    element of y and dx for a block of rows that spans tiles and ends ragged, and all of dC."""
+    w = wl.WORKLOADS["c4"]
+    (I, O), d = w.layers[0], w.degree
+    B = 1000 + 37
+    x = wl.make_x(B, I, 4242, w.x_mean, w.x_std)
+    C = wl.make_coeff(I, O, d, 4243)
+    dy = wl.make_dy(B, O, 4244)
+    _check_full(x, C, dy, 0, "c4 first layer, %d rows" % B)
 
 
 @pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
