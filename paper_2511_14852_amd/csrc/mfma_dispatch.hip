@@ -16,8 +16,7 @@ bool degree_specialised(int d) { return d == 3 || d == 4 || d == 5 || d == 6 || 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Tuning switches for kernel experiments: integer bit mask in the environment variable
-// CHEBYKAN_TUNE, read once.  Forward kernel: bit 0 = plain 256-thread loop, bit 1 = 256-thread
-// loop with the producer work inside the MFMA sequence, neither = wave-specialised.
+// CHEBYKAN_TUNE, read once.  Bit 2 (value 4): always use the packed-column dx kernel.
 int tune_flags()
 {
     static const int flags = [] {
@@ -173,12 +172,39 @@ void pick_dx_nb(const float* x, const float* C, const float* dy, float* dx, int 
     }
 }
 
+template <int D, int VEC>
+void launch_dx2(const float* x, const float* C, const float* dy, float* dx, int B, int I, int O, hipStream_t s)
+{
+    using Cfg = Dx2Cfg<D, VEC>;
+    static bool once = (allow_lds(dx2_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
+    (void)once;
+    const int tiles_i = (I + Cfg::BF - 1) / Cfg::BF;
+    const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * tiles_i;
+    hipLaunchKernelGGL(dx2_mfma_kernel<Cfg>, dim3((unsigned)tiles), dim3(MFMA_THREADS), Cfg::LDS_BYTES, s, x, C, dy,
+                       dx, B, I, O, tiles_i);
+}
+
+// The feature-per-lane kernel works on 32-feature tiles; it is taken unless that wastes
+// clearly more MFMA blocks than the packed-column kernel would (very narrow inputs).
+bool dx_feature_per_lane(int I, int D)
+{
+    const int nb = dx_column_blocks(I, D);
+    const int64_t packed = (int64_t)((I + 32 * nb / D - 1) / (32 * nb / D)) * nb;
+    const int64_t per_lane = (int64_t)((I + 31) / 32) * D;
+    return per_lane * 100 <= packed * 120;
+}
+
 template <int D>
 void pick_dx(const float* x, const float* C, const float* dy, float* dx, int B, int I, int O, hipStream_t s)
 {
     const bool vec = aligned16(C) && aligned16(dy) && O % 4 == 0;   // O%4==0 makes every slab run 16-byte aligned
-    if (vec) pick_dx_nb<D, 4>(x, C, dy, dx, B, I, O, s);
-    else pick_dx_nb<D, 1>(x, C, dy, dx, B, I, O, s);
+    if (dx_feature_per_lane(I, D) && !(tune_flags() & 4)) {
+        if (vec) launch_dx2<D, 4>(x, C, dy, dx, B, I, O, s);
+        else launch_dx2<D, 1>(x, C, dy, dx, B, I, O, s);
+    } else {
+        if (vec) pick_dx_nb<D, 4>(x, C, dy, dx, B, I, O, s);
+        else pick_dx_nb<D, 1>(x, C, dy, dx, B, I, O, s);
+    }
 }
 
 bool shape_fits(int64_t B, int I, int O, int d)

@@ -680,4 +680,201 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
     }
 }
 
+// ------------------------------------------------ input gradient, feature-per-lane form
+// Same operation as dx_mfma_kernel, other column order: a tile is 128 rows x 32 input
+// features, and column block j of G holds degree k = j+1 for those 32 features.  The D
+// accumulators of one lane then all belong to the SAME (row, feature) pairs, so the sum over
+// k with T_k'(u) is taken in registers: no LDS round trip, no shuffles, and x / dx are
+// accessed with consecutive lanes on consecutive features.  Because that sum is linear in the
+// accumulators it is also what folds long contractions: every 512 outputs the accumulators
+// are folded into 16 running dx values per lane.  Used whenever the feature count fills the
+// 32-feature tiles reasonably; very narrow inputs stay with dx_mfma_kernel.
+template <int D_, int VEC_>
+struct Dx2Cfg {
+    static constexpr int D = D_, K = D_ + 1, VEC = VEC_;
+    static constexpr int BM = 128, BF = 32;
+    static constexpr int BO = D <= 4 ? 32 : 16;         // outputs per contraction chunk
+    static constexpr int SAX = BO + 1;                  // odd row stride of the dy tile
+    static constexpr int SSX = BO * K + 1;              // odd slab stride: lane i reads bank i + const
+    static constexpr int A_FLOATS = (BM * SAX + 3) & ~3;
+    static constexpr int B_FLOATS = (BF * SSX + 3) & ~3;
+    static constexpr int STAGE = A_FLOATS + B_FLOATS;
+    static constexpr int LDS_BYTES = 2 * STAGE * 4;
+    static constexpr int NSTEP = BO / 2;
+    static constexpr int FOLD = FOLD_TERMS / BO;
+    // producers: two threads per dy row, eight threads per feature slab; every address is a
+    // per-thread base plus a compile-time offset
+    static constexpr int A_PER = BO / 2;                // dy floats per thread and chunk
+    static constexpr int A_NV = A_PER / VEC;
+    static constexpr int RUN = BO * K;                  // floats of one feature's coefficient run
+    static constexpr int C_PER = RUN / 8;               // per thread
+    static constexpr int C_NV = VEC == 4 ? C_PER / 4 : 0;        // full vectors per thread
+    static constexpr int C_NS = C_PER - C_NV * 4;                // single floats per thread
+    static_assert(D >= 1, "degree 0 has no input gradient");
+    static_assert(A_PER % VEC == 0 && RUN % 8 == 0, "split");
+};
+
+// grid.x = ceil(B/128) * ceil(I/32), feature tile fastest.
+template <class Cfg>
+__global__ void __launch_bounds__(MFMA_THREADS, 2)
+dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
+                float* __restrict__ dx, int B, int I, int O, int n_tiles_i)
+{
+    constexpr int D = Cfg::D, K = Cfg::K, VEC = Cfg::VEC, BF = Cfg::BF, BO = Cfg::BO;
+    constexpr int SAX = Cfg::SAX, SSX = Cfg::SSX;
+    extern __shared__ __align__(16) float lds[];
+
+    const int t = threadIdx.x;
+    const int tile_i = blockIdx.x % n_tiles_i;
+    const int tile_b = blockIdx.x / n_tiles_i;
+    const int b0 = tile_b * Cfg::BM;
+    const int i0 = tile_i * BF;
+    const int lane = t & 63, wave = t >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+
+    // Views based at this tile: rows past B and features past I read as zero; outputs past O
+    // (last chunk) are removed by zeroing the dy operand.
+    const int rows_here = B - b0 < Cfg::BM ? B - b0 : Cfg::BM;
+    const BufferView gv = make_view(dy + (int64_t)b0 * O, (int64_t)rows_here * O);
+    const BufferView cv = make_view(C + (int64_t)i0 * O * K, (int64_t)(I - i0) * O * K);
+    const BufferView xv = make_view(x + (int64_t)b0 * I, (int64_t)rows_here * I);
+    const uint32_t OK_ = (uint32_t)O * (uint32_t)K;
+
+    // this lane's 16 (row, feature) pairs: requested now, used in the epilogue
+    const bool f_ok = i0 + l32 < I;
+    float xval[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float v = load1(xv, (uint32_t)(wave * 32 + mfma_row(r, h)) * (uint32_t)I + (uint32_t)(i0 + l32));
+        xval[r] = f_ok ? v : 0.0f;
+    }
+
+    float areg[Cfg::A_PER];
+    float creg[Cfg::C_PER];
+    const int pa_row = t >> 1, pa_part = t & 1;        // dy tile: row and half-row of this thread
+    const int pc_f = t >> 3, pc_part = t & 7;          // coefficient slab: feature and eighth
+    const uint32_t ga_off = (uint32_t)pa_row * (uint32_t)O + (uint32_t)(pa_part * VEC);
+    const uint32_t gc_off = (uint32_t)pc_f * OK_;
+    const int la_off = pa_row * SAX + pa_part * VEC;
+    const int lc_off = pc_f * SSX;
+
+    auto load_chunk = [&](int oc) {
+#pragma unroll
+        for (int j = 0; j < Cfg::A_NV; ++j) {
+            const int kk = pa_part * VEC + j * 2 * VEC;             // column inside the chunk
+            const bool ok = oc + kk < O;
+            const uint32_t off = ga_off + (uint32_t)(oc + j * 2 * VEC);
+            if constexpr (VEC == 4) {
+                const bufx4 v = load4(gv, off);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) areg[j * 4 + q] = ok ? v[q] : 0.0f;
+            } else {
+                const float v = load1(gv, off);
+                areg[j] = ok ? v : 0.0f;
+            }
+        }
+        const uint32_t base = gc_off + (uint32_t)oc * (uint32_t)K;
+#pragma unroll
+        for (int j = 0; j < Cfg::C_NV; ++j) {
+            const bufx4 v = load4(cv, base + (uint32_t)(pc_part * 4 + j * 32));
+            creg[j * 4 + 0] = v[0]; creg[j * 4 + 1] = v[1]; creg[j * 4 + 2] = v[2]; creg[j * 4 + 3] = v[3];
+        }
+#pragma unroll
+        for (int j = 0; j < Cfg::C_NS; ++j)
+            creg[Cfg::C_NV * 4 + j] = load1(cv, base + (uint32_t)(Cfg::C_NV * 32 + pc_part + j * 8));
+    };
+
+    auto store_chunk = [&](float* sA, float* sB) {
+#pragma unroll
+        for (int j = 0; j < Cfg::A_NV; ++j)
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) sA[la_off + j * 2 * VEC + q] = areg[j * VEC + q];
+#pragma unroll
+        for (int j = 0; j < Cfg::C_NV; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) sB[lc_off + pc_part * 4 + j * 32 + q] = creg[j * 4 + q];
+#pragma unroll
+        for (int j = 0; j < Cfg::C_NS; ++j) sB[lc_off + Cfg::C_NV * 32 + pc_part + j * 8] = creg[Cfg::C_NV * 4 + j];
+    };
+
+    const int aBase = (wave * 32 + l32) * SAX + h * (BO / 2);
+    const int bBase = l32 * SSX + h * (BO / 2) * K + 1;
+
+    floatx16 acc[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) acc[j] = zero16();
+    float dxacc[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dxacc[r] = 0.0f;
+
+    // dxacc += (1-u^2) sum_k acc_k T_k'(u), then acc = 0
+    auto fold = [&]() {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float slope;
+            const float u = normalise(xval[r], slope);
+            float dT[D];
+            cheb_dT<D>(u, dT);
+            float sum = 0.0f;
+#pragma unroll
+            for (int j = 0; j < D; ++j) sum = fmaf(acc[j][r], dT[j], sum);
+            dxacc[r] = fmaf(slope, sum, dxacc[r]);
+        }
+#pragma unroll
+        for (int j = 0; j < D; ++j) acc[j] = zero16();
+    };
+
+    constexpr int LA = D >= 6 ? 1 : 2;   // operand lookahead in steps; a step is already D MFMAs long
+    float aop[Cfg::NSTEP], bop[Cfg::NSTEP][D];
+    auto read_step = [&](const float* sA, const float* sB, int s) {
+        aop[s] = sA[aBase + s];
+#pragma unroll
+        for (int j = 0; j < D; ++j) bop[s][j] = sB[bBase + s * K + j];
+    };
+    auto mfma_steps = [&](const float* sA, const float* sB, int s0, int s1) {
+#pragma unroll
+        for (int s = s0; s < s1; ++s) {
+            if (s + LA < Cfg::NSTEP) read_step(sA, sB, s + LA);
+#pragma unroll
+            for (int j = 0; j < D; ++j) acc[j] = mfma32(aop[s], bop[s][j], acc[j]);
+        }
+    };
+
+    // chunks past the last one are loaded and stored too (all-zero dy, stage never read)
+    const int n_chunks = (O + BO - 1) / BO;
+    load_chunk(0);
+    store_chunk(lds, lds + Cfg::A_FLOATS);
+    load_chunk(BO);
+    for (int c = 0; c < n_chunks; ++c) {
+        __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
+        float* sA = lds + (c & 1) * Cfg::STAGE;
+        float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
+#pragma unroll
+        for (int q = 0; q < LA; ++q) read_step(sA, sA + Cfg::A_FLOATS, q);
+        mfma_steps(sA, sA + Cfg::A_FLOATS, 0, Cfg::NSTEP / 2);
+        store_chunk(nA, nA + Cfg::A_FLOATS);
+        load_chunk((c + 2) * BO);
+        mfma_steps(sA, sA + Cfg::A_FLOATS, Cfg::NSTEP / 2, Cfg::NSTEP);
+        __builtin_amdgcn_sched_group_barrier(0x100, LA * (1 + D), 0);
+#pragma unroll
+        for (int q = 0; q < Cfg::NSTEP * D; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // up to two LDS reads
+            __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);   // one vector-ALU
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+        }
+        if ((c + 1) % Cfg::FOLD == 0) fold();
+    }
+    fold();
+
+    if (f_ok) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = b0 + wave * 32 + mfma_row(r, h);
+            if (row < B) dx[(int64_t)row * I + i0 + l32] = dxacc[r];
+        }
+    }
+}
+
 }  // namespace chebykan

@@ -71,6 +71,12 @@ CASES = [
     (140, 7, 130, 6),
     (129, 5, 257, 8),
     (600, 10, 12, 6),
+    # enough input features for the feature-per-lane input-gradient kernel, ragged feature
+    # tiles, both chunk widths, a contraction longer than one fold
+    (140, 40, 72, 6),
+    (131, 70, 36, 8),
+    (130, 33, 20, 3),
+    (129, 34, 530, 4),
     # very narrow outputs: the streaming kernels
     (300, 64, 1, 6),
     (100, 8, 2, 3),
