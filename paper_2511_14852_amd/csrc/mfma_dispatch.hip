@@ -184,14 +184,17 @@ void launch_dx2(const float* x, const float* C, const float* dy, float* dx, int 
                        dx, B, I, O, tiles_i);
 }
 
-// The feature-per-lane kernel works on 32-feature tiles; it is taken unless that wastes
-// clearly more MFMA blocks than the packed-column kernel would (very narrow inputs).
+// The feature-per-lane kernel works on 32-feature tiles; it is taken for degrees up to 6
+// (measured slower at degree 8, where its eight accumulator blocks leave too few registers)
+// unless it needs over 5 % more MFMA blocks than the packed-column kernel (ragged or very
+// narrow feature counts).
 bool dx_feature_per_lane(int I, int D)
 {
+    if (D > 6) return false;
     const int nb = dx_column_blocks(I, D);
     const int64_t packed = (int64_t)((I + 32 * nb / D - 1) / (32 * nb / D)) * nb;
     const int64_t per_lane = (int64_t)((I + 31) / 32) * D;
-    return per_lane * 100 <= packed * 120;
+    return per_lane * 100 <= packed * 105;
 }
 
 template <int D>
