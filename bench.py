@@ -33,11 +33,11 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
 # Keyed by (workload, call, layer); a call that is not listed reports traffic = null.
 MEASURED_TRAFFIC_BYTES = {
     ("c2", "dC", 1): 132.2e6 + 14.8e6,
-    ("c2", "dx", 1): 117.8e6,
+    ("c2", "dx", 1): 80.6e6,
     ("c2", "fwd", 1): 26.8e6,
-    ("c5", "dC", 0): 898.8e6 + 188.8e6,
-    ("c5", "fwd", 0): 753.8e6,
-    ("c5", "dx", 0): 1774.9e6,
+    ("c5", "dC", 0): 900.1e6 + 188.8e6,
+    ("c5", "fwd", 0): 753.5e6,
+    ("c5", "dx", 0): 1781.8e6,
 }
 
 
