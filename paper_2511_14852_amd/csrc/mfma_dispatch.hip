@@ -113,8 +113,9 @@ void launch_dC(const float* x, const float* dy, float* partial, int B, int I, in
     (void)once;
     const int tiles_o = (O + BN - 1) / BN;
     const int tiles_i = (I + Cfg::BIC - 1) / Cfg::BIC;
-    hipLaunchKernelGGL(dC_mfma_kernel<Cfg>, dim3((unsigned)(tiles_i * tiles_o), (unsigned)p.slices),
-                       dim3(MFMA_THREADS), Cfg::LDS_BYTES, s, x, dy, partial, B, I, O, tiles_o, p.rows_per_slice);
+    hipLaunchKernelGGL(dC_mfma_kernel<Cfg>, dim3((unsigned)((int64_t)tiles_i * tiles_o * p.slices)),
+                       dim3(MFMA_THREADS), Cfg::LDS_BYTES, s, x, dy, partial, B, I, O, tiles_o, tiles_i, p.slices,
+                       p.rows_per_slice);
 }
 
 template <int D>

@@ -283,24 +283,41 @@ struct DcCfg {
 // partial[s][(i,k)][o] = sum over the rows of batch slice s of T_k(tanh x[b,i]) dy[b,o]
 // (paper Alg. 2, coeff_grad; the batch axis is split into slices whose partial sums a
 // second kernel adds in a fixed order - the two-stage reduction of Sec. 4.4 in place
-// of atomics).  grid = (tiles_ik * tiles_o, n_slices).  Same chunk pipeline as the
+// of atomics).  grid.x = tiles_ik * tiles_o * n_slices.  Same chunk pipeline as the
 // forward kernel: loads through buffer views based at the slice (rows past the slice
 // read as zero dy, so they add nothing), producer work between MFMA issues.
 template <class Cfg>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ partial,
-               int B, int I, int O, int n_tiles_o, int rows_per_slice)
+               int B, int I, int O, int n_tiles_o, int n_tiles_i, int n_slices, int rows_per_slice)
 {
     constexpr int D = Cfg::D, K = Cfg::K, BN = Cfg::BN, VEC = Cfg::VEC, BB = Cfg::BB, BIC = Cfg::BIC;
     constexpr int SMA = Cfg::SMA, SNB = Cfg::SNB, TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
     extern __shared__ __align__(16) float lds[];
 
     const int t = threadIdx.x;
-    const int tile_o = blockIdx.x % n_tiles_o;
-    const int tile_i = blockIdx.x / n_tiles_o;
+    // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.
+    // All tiles of one batch slice read the same x and dy rows, so they are given ids that are
+    // equal mod 8 and adjacent in time: the slice's rows then come from HBM once, not once per tile.
+    const int n_tiles = n_tiles_o * n_tiles_i;
+    int tile, slice;
+    {
+        const int L = blockIdx.x;
+        const int full = (n_slices / 8) * 8;               // slices in complete groups of 8
+        if (L < full * n_tiles) {
+            const int group = L / (8 * n_tiles), rem = L % (8 * n_tiles);
+            slice = group * 8 + rem % 8;
+            tile = rem / 8;
+        } else {                                           // last, incomplete group: plain order
+            const int rem = L - full * n_tiles;
+            slice = full + rem / n_tiles;
+            tile = rem % n_tiles;
+        }
+    }
+    const int tile_o = tile % n_tiles_o;
+    const int tile_i = tile / n_tiles_o;
     const int i0 = tile_i * BIC;
     const int o0 = tile_o * BN;
-    const int slice = blockIdx.y;
     const int64_t r_begin = (int64_t)slice * rows_per_slice;
     int64_t r_end = r_begin + rows_per_slice;
     if (r_end > B) r_end = B;
