@@ -46,7 +46,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "p1", "p2", "p3"])
     ap.add_argument("--rotate", type=int, default=4,
                     help="number of distinct (x, dy) input sets cycled through, so inputs are not cache-resident")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -1,0 +1,213 @@
+// Launch code of the specialised kernels for ONE degree.  Included by the per-degree
+// translation units (deg_NN.hip), each of which instantiates degree_forward<D> and
+// degree_backward<D> for its degree; the dispatcher only sees their declarations.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "mfma_kernels.h"
+#include "narrow_kernels.h"
+#include "plans.h"
+
+namespace chebykan {
+
+// Dynamic LDS above 64 KiB has to be allowed per kernel once.
+template <class KernelT>
+void allow_lds(KernelT kernel, int bytes)
+{
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              bytes);
+}
+
+// Many slices of a small tensor (coefficient gradients of narrow layers): 32 slice groups.
+// Few slices of a large tensor (split forward): 4 groups, 64 consecutive elements per block.
+inline void launch_sum_slices(const float* partial, float* out, int64_t n, int slices, hipStream_t s)
+{
+    if (slices > 16)
+        hipLaunchKernelGGL(sum_slices_kernel<32>, dim3((unsigned)((n + 7) / 8)), dim3(256), 32 * 9 * sizeof(float), s,
+                           partial, out, n, slices);
+    else
+        hipLaunchKernelGGL(sum_slices_kernel<4>, dim3((unsigned)((n + 63) / 64)), dim3(256), 4 * 65 * sizeof(float),
+                           s, partial, out, n, slices);
+}
+
+// ------------------------------------------------------------------ forward
+template <int D, int BN, int VEC>
+void launch_fwd(const float* x, const float* C, float* y, float* partial, int B, int I, int O, hipStream_t s)
+{
+    using Cfg = FwdCfg<D, BN, forward_chunk_features(D), VEC>;
+    static bool once = (allow_lds(fwd_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
+    (void)once;
+    const FwdPlan p = plan_forward(B, I, O, D);
+    const int tiles_o = (O + BN - 1) / BN;
+    const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * tiles_o;
+    float* out = p.splits > 1 ? partial : y;
+    hipLaunchKernelGGL(fwd_mfma_kernel<Cfg>, dim3((unsigned)tiles, (unsigned)p.splits), dim3(MFMA_THREADS),
+                       Cfg::LDS_BYTES, s, x, C, out, B, I, O, tiles_o, p.chunks_per_split);
+    if (p.splits > 1) launch_sum_slices(partial, y, (int64_t)B * O, p.splits, s);
+}
+
+template <int D>
+void pick_fwd(const float* x, const float* C, float* y, float* partial, int B, int I, int O, hipStream_t s)
+{
+    const bool vec = aligned16(C) && ((int64_t)O * (D + 1)) % 4 == 0;
+    if (O <= 64) {
+        if (vec) launch_fwd<D, 64, 4>(x, C, y, partial, B, I, O, s);
+        else launch_fwd<D, 64, 1>(x, C, y, partial, B, I, O, s);
+    } else {
+        if (vec) launch_fwd<D, 128, 4>(x, C, y, partial, B, I, O, s);
+        else launch_fwd<D, 128, 1>(x, C, y, partial, B, I, O, s);
+    }
+}
+
+// --------------------------------------------------------------------- dC
+template <int D, int BN, int VEC>
+void launch_dC(const float* x, const float* dy, float* partial, int B, int I, int O, const DcPlan& p,
+               hipStream_t s)
+{
+    using Cfg = DcCfg<D, BN, VEC>;
+    static bool once = (allow_lds(dC_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
+    (void)once;
+    const int tiles_o = (O + BN - 1) / BN;
+    const int tiles_i = (I + Cfg::BIC - 1) / Cfg::BIC;
+    hipLaunchKernelGGL(dC_mfma_kernel<Cfg>, dim3((unsigned)((int64_t)tiles_i * tiles_o * p.slices)),
+                       dim3(MFMA_THREADS), Cfg::LDS_BYTES, s, x, dy, partial, B, I, O, tiles_o, tiles_i, p.slices,
+                       p.rows_per_slice);
+}
+
+template <int D>
+void pick_dC(const float* x, const float* dy, float* dC, float* partial, int B, int I, int O, const DcPlan& p,
+             hipStream_t s)
+{
+    const bool vec = aligned16(dy) && O % 4 == 0;
+    if (p.bn == 64) {
+        if (vec) launch_dC<D, 64, 4>(x, dy, partial, B, I, O, p, s);
+        else launch_dC<D, 64, 1>(x, dy, partial, B, I, O, p, s);
+    } else {
+        if (vec) launch_dC<D, 128, 4>(x, dy, partial, B, I, O, p, s);
+        else launch_dC<D, 128, 1>(x, dy, partial, B, I, O, p, s);
+    }
+    hipLaunchKernelGGL(dC_combine_kernel<D>, dim3((unsigned)((O + 31) / 32), (unsigned)I), dim3(256),
+                       256 * ((D + 1) | 1) * sizeof(float), s, partial, dC, I, O, p.slices);
+}
+
+// --------------------------------------------------------------------- dx
+template <int D, int NB, int VEC>
+void launch_dx(const float* x, const float* C, const float* dy, float* dx, int B, int I, int O, hipStream_t s)
+{
+    using Cfg = DxCfg<D, NB, VEC>;
+    static bool once = (allow_lds(dx_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
+    (void)once;
+    const int tiles_i = (I + Cfg::BIX - 1) / Cfg::BIX;
+    const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * tiles_i;
+    hipLaunchKernelGGL(dx_mfma_kernel<Cfg>, dim3((unsigned)tiles), dim3(MFMA_THREADS), Cfg::LDS_BYTES, s, x, C, dy,
+                       dx, B, I, O, tiles_i);
+}
+
+template <int D, int VEC>
+void pick_dx_nb(const float* x, const float* C, const float* dy, float* dx, int B, int I, int O, hipStream_t s)
+{
+    switch (dx_column_blocks(I, D)) {
+        case 1: launch_dx<D, 1, VEC>(x, C, dy, dx, B, I, O, s); break;
+        case 2: launch_dx<D, 2, VEC>(x, C, dy, dx, B, I, O, s); break;
+        case 3: launch_dx<D, 3, VEC>(x, C, dy, dx, B, I, O, s); break;
+        default: launch_dx<D, 4, VEC>(x, C, dy, dx, B, I, O, s); break;
+    }
+}
+
+template <int D, int VEC>
+void launch_dx2(const float* x, const float* C, const float* dy, float* dx, int B, int I, int O, hipStream_t s)
+{
+    using Cfg = Dx2Cfg<D, VEC>;
+    static bool once = (allow_lds(dx2_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
+    (void)once;
+    const int tiles_i = (I + Cfg::BF - 1) / Cfg::BF;
+    const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * tiles_i;
+    hipLaunchKernelGGL(dx2_mfma_kernel<Cfg>, dim3((unsigned)tiles), dim3(MFMA_THREADS), Cfg::LDS_BYTES, s, x, C, dy,
+                       dx, B, I, O, tiles_i);
+}
+
+template <int D>
+void pick_dx(const float* x, const float* C, const float* dy, float* dx, int B, int I, int O, hipStream_t s)
+{
+    const bool vec = aligned16(C) && aligned16(dy) && O % 4 == 0;   // O%4==0 makes every slab run 16-byte aligned
+    if constexpr (D <= 6) {   // the feature-per-lane kernel exists for these degrees only
+        if (dx_feature_per_lane(I, D) && !(tune_flags() & 4)) {
+            if (vec) launch_dx2<D, 4>(x, C, dy, dx, B, I, O, s);
+            else launch_dx2<D, 1>(x, C, dy, dx, B, I, O, s);
+            return;
+        }
+    }
+    if (vec) pick_dx_nb<D, 4>(x, C, dy, dx, B, I, O, s);
+    else pick_dx_nb<D, 1>(x, C, dy, dx, B, I, O, s);
+}
+
+// ------------------------------------------------------------ narrow layers
+template <int D, int O>
+void launch_narrow_fwd(const float* x, const float* C, float* y, int B, int I, hipStream_t s)
+{
+    const NarrowPlan p = plan_narrow(B, I, NARROW_FWD_WGS);
+    hipLaunchKernelGGL((narrow_fwd_kernel<D, O>), dim3((unsigned)p.slices), dim3(NARROW_THREADS),
+                       (size_t)I * O * (D + 1) * sizeof(float), s, x, C, y, B, I, p.G, p.rows_per_wg);
+}
+
+template <int D, int O>
+void launch_narrow_bwd(const float* x, const float* C, const float* dy, float* dx, float* dC, float* partial,
+                       int B, int I, hipStream_t s)
+{
+    const NarrowPlan p = plan_narrow(B, I, NARROW_BWD_WGS);
+    const int blocks_i = (I + p.G - 1) / p.G;
+    hipLaunchKernelGGL((narrow_bwd_kernel<D, O>), dim3((unsigned)p.slices, (unsigned)blocks_i),
+                       dim3(NARROW_THREADS), (size_t)NARROW_THREADS * O * (D + 1) * sizeof(float), s, x, C, dy,
+                       dx, dC ? partial : nullptr, B, I, p.G, p.rows_per_wg);
+    if (dC) {
+        launch_sum_slices(partial, dC, (int64_t)I * O * (D + 1), p.slices, s);
+    }
+}
+
+template <int D>
+void narrow_fwd_by_out(const float* x, const float* C, float* y, int B, int I, int O, hipStream_t s)
+{
+    switch (O) {
+        case 1: launch_narrow_fwd<D, 1>(x, C, y, B, I, s); break;
+        case 2: launch_narrow_fwd<D, 2>(x, C, y, B, I, s); break;
+        case 3: launch_narrow_fwd<D, 3>(x, C, y, B, I, s); break;
+        default: launch_narrow_fwd<D, 4>(x, C, y, B, I, s); break;
+    }
+}
+
+template <int D>
+void narrow_bwd_by_out(const float* x, const float* C, const float* dy, float* dx, float* dC, float* partial, int B,
+                       int I, int O, hipStream_t s)
+{
+    switch (O) {
+        case 1: launch_narrow_bwd<D, 1>(x, C, dy, dx, dC, partial, B, I, s); break;
+        case 2: launch_narrow_bwd<D, 2>(x, C, dy, dx, dC, partial, B, I, s); break;
+        case 3: launch_narrow_bwd<D, 3>(x, C, dy, dx, dC, partial, B, I, s); break;
+        default: launch_narrow_bwd<D, 4>(x, C, dy, dx, dC, partial, B, I, s); break;
+    }
+}
+
+// ------------------------------------------------------- per-degree entry points
+// `ws` is the caller's workspace (partial outputs of a split forward contraction; partial
+// coefficient gradients of the batch slices).
+template <int D>
+void degree_forward(const float* x, const float* C, float* y, int B, int I, int O, void* ws, hipStream_t s)
+{
+    if (use_narrow(B, I, O, D)) narrow_fwd_by_out<D>(x, C, y, B, I, O, s);
+    else pick_fwd<D>(x, C, y, static_cast<float*>(ws), B, I, O, s);
+}
+
+template <int D>
+void degree_backward(const float* x, const float* C, const float* dy, float* dx, float* dC, int B, int I, int O,
+                     void* ws, hipStream_t s)
+{
+    float* partial = static_cast<float*>(ws);
+    if (use_narrow(B, I, O, D)) {
+        narrow_bwd_by_out<D>(x, C, dy, dx, dC, partial, B, I, O, s);
+        return;
+    }
+    if (dx) pick_dx<D>(x, C, dy, dx, B, I, O, s);
+    if (dC) pick_dC<D>(x, dy, dC, partial, B, I, O, plan_dC(B, I, O, D), s);
+}
+
+}  // namespace chebykan

@@ -73,14 +73,15 @@ struct FwdCfg {
     static constexpr int NE = BI * BN * K;                     // coefficient floats per chunk
     // every thread loads NFULL vectors of VEC floats plus NREM single floats: no ragged round
     static constexpr int NFULL = NE / (VEC * MFMA_THREADS);
-    static constexpr int NREM = (NE - NFULL * VEC * MFMA_THREADS) / MFMA_THREADS;
+    // (a last partial round repeats the final element in the idle threads: same value, same place)
+    static constexpr int NREM = (NE - NFULL * VEC * MFMA_THREADS + MFMA_THREADS - 1) / MFMA_THREADS;
     static constexpr int NMFMA = NSTEP * TM * TN;              // MFMA instructions per chunk and wave
     static_assert(BI % 2 == 0 && BN % 64 == 0, "tile shape");
-    static_assert((BN * K) % VEC == 0 && NE % MFMA_THREADS == 0, "vector width");
+    static_assert((BN * K) % VEC == 0, "vector width");
 };
 
 // y[b,o] = sum_i sum_k C[i,o,k] T_k(tanh x[b,i])      (paper Eq. 2-3; Alg. 1 as a function)
-// grid.x = ceil(B/128) * ceil(O/BN), output-tile index fastest.
+// grid.x = ceil(B/128) * ceil(O/BN), output-tile index fastest; grid.y = contraction ranges.
 //
 // Per chunk c: barrier; first half of chunk c's MFMA steps; generate chunk c+1 into the
 // other LDS stage; request chunk c+2 from HBM; second half of the MFMA steps.  All loads go
@@ -90,7 +91,7 @@ struct FwdCfg {
 template <class Cfg>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float* __restrict__ y,
-                int B, int I, int O, int n_tiles_o)
+                int B, int I, int O, int n_tiles_o, int chunks_per_split)
 {
     constexpr int D = Cfg::D, K = Cfg::K, KP = Cfg::KP, BN = Cfg::BN, BI = Cfg::BI, VEC = Cfg::VEC;
     constexpr int SA = Cfg::SA, SS = Cfg::SS, TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
@@ -137,7 +138,8 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
         }
 #pragma unroll
         for (int j = 0; j < Cfg::NREM; ++j) {
-            const int e = Cfg::NFULL * VEC * MFMA_THREADS + t + j * MFMA_THREADS;
+            int e = Cfg::NFULL * VEC * MFMA_THREADS + t + j * MFMA_THREADS;
+            if (e > Cfg::NE - 1) e = Cfg::NE - 1;
             creg[Cfg::NFULL * VEC + j] = load1(cv, (uint32_t)(i0 + e / (BN * K)) * OK_ + (uint32_t)(e % (BN * K)));
         }
     };
@@ -167,8 +169,11 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
             }
         }
 #pragma unroll
-        for (int j = 0; j < Cfg::NREM; ++j)
-            store_coeff(sB, Cfg::NFULL * VEC * MFMA_THREADS + t + j * MFMA_THREADS, creg[Cfg::NFULL * VEC + j]);
+        for (int j = 0; j < Cfg::NREM; ++j) {
+            int e = Cfg::NFULL * VEC * MFMA_THREADS + t + j * MFMA_THREADS;
+            if (e > Cfg::NE - 1) e = Cfg::NE - 1;
+            store_coeff(sB, e, creg[Cfg::NFULL * VEC + j]);
+        }
     };
 
     // --- consumer role
@@ -208,10 +213,15 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
 
     // Chunks past the last one are loaded and stored too: their views return zeros and the
     // stage they land in is never read.  That keeps the loop body free of conditions.
-    const int n_chunks = (I + BI - 1) / BI;
-    load_chunk(0);
+    // blockIdx.y selects a range of chunks (a split contraction writes partial outputs, one
+    // [B,O] plane per range, that a second kernel adds in range order)
+    const int n_chunks_all = (I + BI - 1) / BI;
+    const int c_begin = blockIdx.y * chunks_per_split;
+    const int n_chunks = n_chunks_all - c_begin < chunks_per_split ? n_chunks_all - c_begin : chunks_per_split;
+    y += (int64_t)blockIdx.y * B * O;
+    load_chunk(c_begin * BI);
     store_chunk(lds, lds + Cfg::A_FLOATS);
-    load_chunk(BI);
+    load_chunk((c_begin + 1) * BI);
     for (int c = 0; c < n_chunks; ++c) {
         __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
         float* sA = lds + (c & 1) * Cfg::STAGE;
@@ -221,7 +231,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
         for (int q = 0; q < LA; ++q) read_step(sA + aBase, sB + bBase, q);
         mfma_steps(sA + aBase, sB + bBase, 0, Cfg::NSTEP / 2);
         store_chunk(nA, nA + Cfg::A_FLOATS);
-        load_chunk((c + 2) * BI);
+        load_chunk((c_begin + c + 2) * BI);
         mfma_steps(sA + aBase, sB + bBase, Cfg::NSTEP / 2, Cfg::NSTEP);
         // ask the scheduler to keep the operand reads ahead and to spread the producer
         // instructions between the MFMA issues

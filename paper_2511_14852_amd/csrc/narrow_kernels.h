@@ -21,11 +21,10 @@
 #include <stdint.h>
 
 #include "basis.h"
+#include "plans.h"
 
 namespace chebykan {
 
-constexpr int NARROW_THREADS = 256;
-constexpr int NARROW_RB = 8;   // consecutive rows per lane group and step (memory-level parallelism)
 
 // Sum over each aligned group of G lanes (G = 8, 16, 32 or 64) with data-parallel-primitive
 // adds: shifts inside a row of 16 lanes, then the two row broadcasts of wave64.  The sum of
@@ -245,25 +244,27 @@ narrow_bwd_kernel(const float* __restrict__ x, const float* __restrict__ C, cons
     }
 }
 
-// out[e] = sum_s partial[s][e], slices added in a fixed order: 32 slice groups take
-// every 32nd slice each, then the 32 group sums are added in group order.
-// block = 256 threads = 32 slice groups x 8 elements; grid.x = ceil(n/8).
-// Dynamic LDS: 32 x 9 floats.
+// out[e] = sum_s partial[s][e], slices added in a fixed order: GROUPS slice groups take
+// every GROUPS-th slice each, then the group sums are added in group order.
+// block = 256 threads = GROUPS slice groups x 256/GROUPS elements; grid.x = ceil(n/(256/GROUPS)).
+// Dynamic LDS: GROUPS x (256/GROUPS + 1) floats.
+template <int GROUPS>
 __global__ void __launch_bounds__(256)
-sum_slices_kernel(const float* __restrict__ partial, float* __restrict__ out, int n, int n_slices)
+sum_slices_kernel(const float* __restrict__ partial, float* __restrict__ out, int64_t n, int n_slices)
 {
+    constexpr int EL = 256 / GROUPS;
     extern __shared__ __align__(16) float lds[];
-    const int el = threadIdx.x & 7, sg = threadIdx.x >> 3;
-    const int e = blockIdx.x * 8 + el;
+    const int el = threadIdx.x % EL, sg = threadIdx.x / EL;
+    const int64_t e = (int64_t)blockIdx.x * EL + el;
     float s = 0.0f;
     if (e < n)
-        for (int q = sg; q < n_slices; q += 32) s += partial[(int64_t)q * n + e];
-    lds[sg * 9 + el] = s;
+        for (int q = sg; q < n_slices; q += GROUPS) s += partial[(int64_t)q * n + e];
+    lds[sg * (EL + 1) + el] = s;
     __syncthreads();
     if (sg == 0 && e < n) {
         float total = 0.0f;
 #pragma unroll
-        for (int q = 0; q < 32; ++q) total += lds[q * 9 + el];
+        for (int q = 0; q < GROUPS; ++q) total += lds[q * (EL + 1) + el];
         out[e] = total;
     }
 }

@@ -1,0 +1,189 @@
+// Host-side planning shared by the dispatcher and the per-degree launch code:
+// which degrees have specialised kernels, which shapes they take, batch-slice and
+// feature-split plans.  No kernels here.
+#pragma once
+#include <stdint.h>
+#include <stdlib.h>
+
+namespace chebykan {
+
+// Degrees with specialised kernels.  Each one is compiled in its own translation unit
+// (deg_NN.hip); everything else runs on the any-degree kernels.
+#define CHEBYKAN_FOR_EACH_DEGREE(X) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(15) X(24)
+
+inline bool degree_specialised(int d)
+{
+#define CHEBYKAN_DEGREE_CASE(n) if (d == n) return true;
+    CHEBYKAN_FOR_EACH_DEGREE(CHEBYKAN_DEGREE_CASE)
+#undef CHEBYKAN_DEGREE_CASE
+    return false;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Tuning switches for kernel experiments: integer bit mask in the environment variable
+// CHEBYKAN_TUNE, read once.  Bit 2 (value 4): always use the packed-column dx kernel.
+// Bit 3 (value 8): never split the forward contraction.
+inline int tune_flags()
+{
+    static const int flags = [] {
+        const char* e = getenv("CHEBYKAN_TUNE");
+        return e ? atoi(e) : 0;
+    }();
+    return flags;
+}
+
+// Input features per forward chunk: about 28-50 contraction terms per chunk.
+constexpr int forward_chunk_features(int d)
+{
+    return d <= 2 ? 12 : d <= 4 ? 8 : d == 5 ? 6 : d <= 8 ? 4 : 2;
+}
+
+inline bool use_narrow_shape(int I, int O, int d) { return O <= 4 && (int64_t)I * O * (d + 1) <= 16384; }
+
+// --------------------------------------------------------------------- dC
+struct DcPlan {
+    int bn;              // output tile width
+    int slices;          // batch slices (partial buffers)
+    int rows_per_slice;  // multiple of 32
+};
+
+// Batch slices for the coefficient gradient.  512 workgroups are resident at once
+// (256 CUs x 2); the slice count is the smallest one that fills at least one such
+// round and wastes under a tenth of its last round, subject to >= 256 rows per slice
+// and a 512 MiB cap on the partial buffers.
+inline DcPlan plan_dC(int64_t B, int I, int O, int d)
+{
+    const int K = d + 1;
+    DcPlan p;
+    p.bn = O <= 64 ? 64 : 128;
+    const int bic = 128 / K;
+    const int64_t tiles = (int64_t)((I + bic - 1) / bic) * ((O + p.bn - 1) / p.bn);
+    int64_t max_s = (B + 255) / 256;
+    const int64_t bytes_per_slice = (int64_t)I * K * O * 4;
+    const int64_t max_by_bytes = ((int64_t)512 << 20) / bytes_per_slice;
+    if (max_s > max_by_bytes) max_s = max_by_bytes;
+    if (max_s > 1024) max_s = 1024;
+    if (max_s < 1) max_s = 1;
+    int64_t best = 1;
+    double best_eff = -1.0;
+    for (int64_t sl = 1; sl <= max_s; ++sl) {
+        const int64_t wg = tiles * sl;
+        const int64_t rounds = (wg + 511) / 512;
+        const double eff = (double)wg / (double)(rounds * 512);
+        if (eff > best_eff + 1e-9) { best_eff = eff; best = sl; }
+        if (wg >= 512 && eff >= 0.9) { best = sl; break; }
+    }
+    int64_t rows = (B + best - 1) / best;
+    rows = (rows + 31) / 32 * 32;
+    if (rows < 32) rows = 32;
+    p.rows_per_slice = (int)rows;
+    p.slices = (int)((B + rows - 1) / rows);
+    if (p.slices < 1) p.slices = 1;
+    return p;
+}
+
+// Column blocks per tile: the count (1..4) that covers the I*D columns of G with the
+// fewest 32-column MFMA blocks; ties go to the wider tile (more reuse of the dy tile).
+inline int dx_column_blocks(int I, int D)
+{
+    int best = 4;
+    int64_t best_cost = -1;
+    for (int nb = 4; nb >= 1; --nb) {
+        const int bix = 32 * nb / D;
+        if (bix < 1) continue;
+        const int64_t cost = (int64_t)((I + bix - 1) / bix) * nb;
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = nb; }
+    }
+    return best;
+}
+
+// The feature-per-lane kernel works on 32-feature tiles; it is taken for degrees up to 6
+// (measured slower at degree 8, where its eight accumulator blocks leave too few registers)
+// unless it needs over 5 % more MFMA blocks than the packed-column kernel (ragged or very
+// narrow feature counts).
+inline bool dx_feature_per_lane(int I, int D)
+{
+    if (D > 6) return false;
+    const int nb = dx_column_blocks(I, D);
+    const int64_t packed = (int64_t)((I + 32 * nb / D - 1) / (32 * nb / D)) * nb;
+    const int64_t per_lane = (int64_t)((I + 31) / 32) * D;
+    return per_lane * 100 <= packed * 105;
+}
+
+inline bool shape_fits(int64_t B, int I, int O, int d)
+{
+    if (!degree_specialised(d)) return false;
+    if (B > 0x7fffffff || I > 65535) return false;
+    if ((int64_t)I * O * (d + 1) >= ((int64_t)1 << 30)) return false;   // 32-bit byte offsets into C
+    // 32-bit byte offsets inside one batch slice of x and dy (a slice never exceeds B rows)
+    if (B * (int64_t)(I > O ? I : O) >= ((int64_t)1 << 30) && !use_narrow_shape(I, O, d)) {
+        const DcPlan p = plan_dC(B, I, O, d);
+        if ((int64_t)p.rows_per_slice * (I > O ? I : O) >= ((int64_t)1 << 30)) return false;
+    }
+    // grid.x limits: tiles stay below 2^31
+    const int64_t tb = (B + 127) / 128;
+    if (tb * ((O + 63) / 64) > 0x7fffffff || tb * I > 0x7fffffff) return false;
+    return true;
+}
+
+// ------------------------------------------------------------ narrow layers
+constexpr int NARROW_MAX_OUT = 4;
+constexpr int NARROW_THREADS = 256;
+constexpr int NARROW_RB = 8;   // consecutive rows per lane group and step (memory-level parallelism)
+constexpr int NARROW_FWD_WGS = 2048, NARROW_BWD_WGS = 512;
+
+inline bool use_narrow(int64_t B, int I, int O, int d)
+{
+    return shape_fits(B, I, O, d) && O <= NARROW_MAX_OUT && (int64_t)I * O * (d + 1) <= 16384;
+}
+
+struct NarrowPlan {
+    int G;             // lanes per row
+    int rows_per_wg;   // multiple of NARROW_RB * (256 / G)
+    int slices;        // workgroups along the batch
+};
+
+// `target`: workgroups to aim for (forward likes many short ones; backward pays for every
+// slice again in the slice sum)
+inline NarrowPlan plan_narrow(int64_t B, int I, int target)
+{
+    NarrowPlan p;
+    p.G = 8;
+    while (p.G < 64 && p.G < I) p.G *= 2;
+    const int quantum = NARROW_RB * (NARROW_THREADS / p.G);
+    int64_t rows = (B + target - 1) / target;
+    rows = (rows + quantum - 1) / quantum * quantum;
+    if (rows < quantum) rows = quantum;
+    p.rows_per_wg = (int)rows;
+    p.slices = (int)((B + rows - 1) / rows);
+    if (p.slices < 1) p.slices = 1;
+    return p;
+}
+
+// Forward contraction split.  With few output tiles (small batch) one workgroup per tile
+// leaves most of the chip idle and each workgroup with a very long contraction, so the
+// input features are cut into `splits` ranges whose partial outputs a second kernel adds in
+// range order (the paper's Partial + Combine scheme of Sec. 4.4, used only where it pays).
+struct FwdPlan {
+    int splits;            // 1 = no split, no workspace
+    int chunks_per_split;  // forward chunks (of forward_chunk_features(d) features) per range
+};
+
+inline FwdPlan plan_forward(int64_t B, int I, int O, int d)
+{
+    const int bi = forward_chunk_features(d);
+    const int n_chunks = (I + bi - 1) / bi;
+    const int64_t tiles = ((B + 127) / 128) * ((O + (O <= 64 ? 63 : 127)) / (O <= 64 ? 64 : 128));
+    FwdPlan p{1, n_chunks};
+    if ((tune_flags() & 8) || tiles >= 256 || n_chunks < 16) return p;
+    int64_t want = (512 + tiles - 1) / tiles;
+    if (want > n_chunks / 8) want = n_chunks / 8;      // at least 8 chunks per range
+    if (want > 64) want = 64;
+    if (want < 2) return p;
+    p.chunks_per_split = (int)((n_chunks + want - 1) / want);
+    p.splits = (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split;
+    return p;
+}
+
+}  // namespace chebykan

@@ -44,6 +44,10 @@ WORKLOADS: Dict[str, Workload] = {
     "c4": Workload("c4", 4, 16 * 1000, (257, 512, 512, 257), 5, x_mean=-2.0, x_std=1.5,
                    note="audio-enhancement-shaped stack, 16 clips x 1000 STFT frames"),
     "c5": Workload("c5", 5, 16384, (1024, 1024), 8, note="large square layer"),
+    # the paper's own single-layer operator shapes (Table 5): tiny batch, high degree
+    "p1": Workload("p1", 11, 128, (40, 256), 8, note="paper operator shape 1 (speech-like)"),
+    "p2": Workload("p2", 12, 64, (256, 512), 15, note="paper operator shape 2 (VoiceBank-like)"),
+    "p3": Workload("p3", 13, 32, (512, 1024), 24, note="paper operator shape 3 (house-price-like)"),
 }
 
 _KIND = {"x": 0, "C": 1, "dy": 2}

@@ -30,13 +30,22 @@ def emu_driver():
     out_dir = os.path.join(EMU, "_build")
     os.makedirs(out_dir, exist_ok=True)
     exe = os.path.join(out_dir, "emu_driver")
-    srcs = [os.path.join(CSRC, "chebykan_api.hip"), os.path.join(CSRC, "mfma_dispatch.hip"),
-            os.path.join(EMU, "emu_state.cpp"), os.path.join(EMU, "emu_driver.cpp")]
+    hip_srcs = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
+    srcs = hip_srcs + [os.path.join(EMU, "emu_state.cpp"), os.path.join(EMU, "emu_driver.cpp")]
     deps = srcs + [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(EMU, "shim", "hip", "hip_runtime.h")]
     if not os.path.exists(exe) or os.path.getmtime(exe) < max(os.path.getmtime(p) for p in deps):
-        cmd = [CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address", "-fno-omit-frame-pointer", "-Wno-psabi",
-               "-I", os.path.join(EMU, "shim"), "-x", "c++", *srcs, "-o", exe + ".tmp", "-lpthread"]
-        subprocess.run(cmd, check=True, cwd=EMU)
+        from concurrent.futures import ThreadPoolExecutor
+        flags = [CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address", "-fno-omit-frame-pointer", "-Wno-psabi",
+                 "-I", os.path.join(EMU, "shim"), "-x", "c++"]
+
+        def compile_one(src):
+            obj = os.path.join(out_dir, os.path.basename(src) + ".o")
+            subprocess.run([*flags, "-c", src, "-o", obj], check=True, cwd=EMU)
+            return obj
+
+        with ThreadPoolExecutor(max_workers=8) as pool:
+            objs = list(pool.map(compile_one, srcs))
+        subprocess.run([CLANG, "-fsanitize=address", *objs, "-o", exe + ".tmp", "-lpthread"], check=True, cwd=EMU)
         os.replace(exe + ".tmp", exe)
     return exe
 
@@ -82,6 +91,11 @@ CASES = [
     (100, 8, 2, 3),
     (77, 70, 3, 8),
     (50, 300, 4, 5),
+    # degrees added for the paper's operator shapes; small batch with a split forward contraction
+    (40, 12, 70, 15),
+    (33, 6, 40, 24),
+    (64, 300, 72, 2),
+    (70, 20, 12, 7),
 ]
 
 

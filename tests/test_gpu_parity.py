@@ -94,6 +94,12 @@ SMALL_SHAPES = [
     (77, 70, 3, 8),
     (50, 300, 4, 5),
     (2000, 64, 1, 6),
+    # the paper's operator shapes (Table 5) and other small batches whose forward contraction is split
+    (128, 40, 256, 8),
+    (64, 256, 512, 15),
+    (32, 512, 1024, 24),
+    (100, 600, 130, 2),
+    (200, 130, 70, 7),
 ]
 
 
