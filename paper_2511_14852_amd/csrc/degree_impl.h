@@ -92,53 +92,59 @@ void pick_dC(const float* x, const float* dy, float* dC, float* partial, int B, 
 
 // --------------------------------------------------------------------- dx
 template <int D, int NB, int VEC>
-void launch_dx(const float* x, const float* C, const float* dy, float* dx, int B, int I, int O, hipStream_t s)
+void launch_dx(const float* x, const float* C, const float* dy, float* dx, float* partial, int B, int I, int O,
+               const DxPlan& p, hipStream_t s)
 {
     using Cfg = DxCfg<D, NB, VEC>;
     static bool once = (allow_lds(dx_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
     (void)once;
-    const int tiles_i = (I + Cfg::BIX - 1) / Cfg::BIX;
-    const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * tiles_i;
-    hipLaunchKernelGGL(dx_mfma_kernel<Cfg>, dim3((unsigned)tiles), dim3(MFMA_THREADS), Cfg::LDS_BYTES, s, x, C, dy,
-                       dx, B, I, O, tiles_i);
+    const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * p.feature_tiles;
+    hipLaunchKernelGGL(dx_mfma_kernel<Cfg>, dim3((unsigned)tiles, (unsigned)p.split.splits), dim3(MFMA_THREADS),
+                       Cfg::LDS_BYTES, s, x, C, dy, p.split.splits > 1 ? partial : dx, B, I, O, p.feature_tiles,
+                       p.split.chunks_per_split);
 }
 
 template <int D, int VEC>
-void pick_dx_nb(const float* x, const float* C, const float* dy, float* dx, int B, int I, int O, hipStream_t s)
-{
-    switch (dx_column_blocks(I, D)) {
-        case 1: launch_dx<D, 1, VEC>(x, C, dy, dx, B, I, O, s); break;
-        case 2: launch_dx<D, 2, VEC>(x, C, dy, dx, B, I, O, s); break;
-        case 3: launch_dx<D, 3, VEC>(x, C, dy, dx, B, I, O, s); break;
-        default: launch_dx<D, 4, VEC>(x, C, dy, dx, B, I, O, s); break;
-    }
-}
-
-template <int D, int VEC>
-void launch_dx2(const float* x, const float* C, const float* dy, float* dx, int B, int I, int O, hipStream_t s)
+void launch_dx2(const float* x, const float* C, const float* dy, float* dx, float* partial, int B, int I, int O,
+                const DxPlan& p, hipStream_t s)
 {
     using Cfg = Dx2Cfg<D, VEC>;
+    static_assert(Cfg::BO == (D <= 4 ? 32 : 16), "plan_dx assumes this chunk width");
     static bool once = (allow_lds(dx2_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
     (void)once;
-    const int tiles_i = (I + Cfg::BF - 1) / Cfg::BF;
-    const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * tiles_i;
-    hipLaunchKernelGGL(dx2_mfma_kernel<Cfg>, dim3((unsigned)tiles), dim3(MFMA_THREADS), Cfg::LDS_BYTES, s, x, C, dy,
-                       dx, B, I, O, tiles_i);
+    const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * p.feature_tiles;
+    hipLaunchKernelGGL(dx2_mfma_kernel<Cfg>, dim3((unsigned)tiles, (unsigned)p.split.splits), dim3(MFMA_THREADS),
+                       Cfg::LDS_BYTES, s, x, C, dy, p.split.splits > 1 ? partial : dx, B, I, O, p.feature_tiles,
+                       p.split.chunks_per_split);
 }
 
 template <int D>
-void pick_dx(const float* x, const float* C, const float* dy, float* dx, int B, int I, int O, hipStream_t s)
+void pick_dx(const float* x, const float* C, const float* dy, float* dx, float* partial, int B, int I, int O,
+             hipStream_t s)
 {
     const bool vec = aligned16(C) && aligned16(dy) && O % 4 == 0;   // O%4==0 makes every slab run 16-byte aligned
+    const DxPlan p = plan_dx(B, I, O, D);
+    bool done = false;
     if constexpr (D <= 6) {   // the feature-per-lane kernel exists for these degrees only
-        if (dx_feature_per_lane(I, D) && !(tune_flags() & 4)) {
-            if (vec) launch_dx2<D, 4>(x, C, dy, dx, B, I, O, s);
-            else launch_dx2<D, 1>(x, C, dy, dx, B, I, O, s);
-            return;
+        if (p.per_lane) {
+            if (vec) launch_dx2<D, 4>(x, C, dy, dx, partial, B, I, O, p, s);
+            else launch_dx2<D, 1>(x, C, dy, dx, partial, B, I, O, p, s);
+            done = true;
         }
     }
-    if (vec) pick_dx_nb<D, 4>(x, C, dy, dx, B, I, O, s);
-    else pick_dx_nb<D, 1>(x, C, dy, dx, B, I, O, s);
+    if (!done) {
+        switch (p.nb * 2 + (vec ? 1 : 0)) {
+            case 2: launch_dx<D, 1, 1>(x, C, dy, dx, partial, B, I, O, p, s); break;
+            case 3: launch_dx<D, 1, 4>(x, C, dy, dx, partial, B, I, O, p, s); break;
+            case 4: launch_dx<D, 2, 1>(x, C, dy, dx, partial, B, I, O, p, s); break;
+            case 5: launch_dx<D, 2, 4>(x, C, dy, dx, partial, B, I, O, p, s); break;
+            case 6: launch_dx<D, 3, 1>(x, C, dy, dx, partial, B, I, O, p, s); break;
+            case 7: launch_dx<D, 3, 4>(x, C, dy, dx, partial, B, I, O, p, s); break;
+            case 8: launch_dx<D, 4, 1>(x, C, dy, dx, partial, B, I, O, p, s); break;
+            default: launch_dx<D, 4, 4>(x, C, dy, dx, partial, B, I, O, p, s); break;
+        }
+    }
+    if (p.split.splits > 1) launch_sum_slices(partial, dx, (int64_t)B * I, p.split.splits, s);
 }
 
 // ------------------------------------------------------------ narrow layers
@@ -206,7 +212,8 @@ void degree_backward(const float* x, const float* C, const float* dy, float* dx,
         narrow_bwd_by_out<D>(x, C, dy, dx, dC, partial, B, I, O, s);
         return;
     }
-    if (dx) pick_dx<D>(x, C, dy, dx, B, I, O, s);
+    // the dx partials are summed before the dC kernel reuses the workspace (same stream)
+    if (dx) pick_dx<D>(x, C, dy, dx, partial, B, I, O, s);
     if (dC) pick_dC<D>(x, dy, dC, partial, B, I, O, plan_dC(B, I, O, D), s);
 }
 

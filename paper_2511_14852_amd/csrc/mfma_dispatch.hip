@@ -32,7 +32,10 @@ size_t backward_workspace_bytes(int64_t B, int I, int O, int d)
     if (B <= 0 || !shape_fits(B, I, O, d)) return 0;
     const size_t coeffs = (size_t)I * (size_t)(d + 1) * (size_t)O * sizeof(float);
     if (use_narrow(B, I, O, d)) return (size_t)plan_narrow(B, I, NARROW_BWD_WGS).slices * coeffs;
-    return (size_t)plan_dC(B, I, O, d).slices * coeffs;
+    const size_t for_dC = (size_t)plan_dC(B, I, O, d).slices * coeffs;
+    const DxPlan dxp = plan_dx(B, I, O, d);
+    const size_t for_dx = dxp.split.splits > 1 ? (size_t)dxp.split.splits * (size_t)B * (size_t)I * sizeof(float) : 0;
+    return for_dC > for_dx ? for_dC : for_dx;   // used one after the other on the same stream
 }
 
 bool fast_forward(const float* x, const float* C, float* y, int64_t B, int I, int O, int d, void* ws, hipStream_t s)
@@ -50,7 +53,7 @@ bool fast_forward(const float* x, const float* C, float* y, int64_t B, int I, in
 bool fast_backward(const float* x, const float* C, const float* dy, float* dx, float* dC, int64_t B, int I, int O,
                    int d, void* ws, hipStream_t s)
 {
-    if (!shape_fits(B, I, O, d) || (dC && !ws)) return false;
+    if (!shape_fits(B, I, O, d) || (backward_workspace_bytes(B, I, O, d) > 0 && !ws)) return false;
     switch (d) {
 #define CHEBYKAN_BACKWARD_CASE(n) case n: degree_backward<n>(x, C, dy, dx, dC, (int)B, I, O, ws, s); return true;
         CHEBYKAN_FOR_EACH_DEGREE(CHEBYKAN_BACKWARD_CASE)

@@ -542,7 +542,7 @@ struct DxCfg {
 template <class Cfg>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
-               float* __restrict__ dx, int B, int I, int O, int n_tiles_i)
+               float* __restrict__ dx, int B, int I, int O, int n_tiles_i, int chunks_per_split)
 {
     constexpr int D = Cfg::D, K = Cfg::K, VEC = Cfg::VEC, BIX = Cfg::BIX, BO = Cfg::BO, NB = Cfg::NB;
     constexpr int SAX = Cfg::SAX, SSX = Cfg::SSX, SG = Cfg::SG;
@@ -651,18 +651,23 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
         }
     };
 
-    // chunks past the last one are loaded and stored too (all-zero dy, stage never read)
-    const int n_chunks = (O + BO - 1) / BO;
-    load_chunk(0);
+    // chunks past the last one are loaded and stored too (all-zero dy, stage never read).
+    // blockIdx.y selects a range of chunks: the epilogue is linear in the accumulators, so a split
+    // contraction writes partial dx planes that a second kernel adds in range order.
+    const int n_chunks_all = (O + BO - 1) / BO;
+    const int c_begin = blockIdx.y * chunks_per_split;
+    const int n_chunks = n_chunks_all - c_begin < chunks_per_split ? n_chunks_all - c_begin : chunks_per_split;
+    dx += (int64_t)blockIdx.y * B * I;
+    load_chunk(c_begin * BO);
     store_chunk(lds, lds + Cfg::A_FLOATS);
-    load_chunk(BO);
+    load_chunk((c_begin + 1) * BO);
     for (int c = 0; c < n_chunks; ++c) {
         __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
         float* sA = lds + (c & 1) * Cfg::STAGE;
         float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
         mfma_steps(sA, sA + Cfg::A_FLOATS, 0, Cfg::NSTEP / 2);
         store_chunk(nA, nA + Cfg::A_FLOATS);
-        load_chunk((c + 2) * BO);
+        load_chunk((c_begin + c + 2) * BO);
         mfma_steps(sA, sA + Cfg::A_FLOATS, Cfg::NSTEP / 2, Cfg::NSTEP);
 #pragma unroll
         for (int q = 0; q < Cfg::NSTEP * NB; ++q) {
@@ -745,7 +750,7 @@ struct Dx2Cfg {
 template <class Cfg>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
-                float* __restrict__ dx, int B, int I, int O, int n_tiles_i)
+                float* __restrict__ dx, int B, int I, int O, int n_tiles_i, int chunks_per_split)
 {
     constexpr int D = Cfg::D, K = Cfg::K, VEC = Cfg::VEC, BF = Cfg::BF, BO = Cfg::BO;
     constexpr int SAX = Cfg::SAX, SSX = Cfg::SSX;
@@ -867,11 +872,16 @@ dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const 
         }
     };
 
-    // chunks past the last one are loaded and stored too (all-zero dy, stage never read)
-    const int n_chunks = (O + BO - 1) / BO;
-    load_chunk(0);
+    // chunks past the last one are loaded and stored too (all-zero dy, stage never read).
+    // blockIdx.y selects a range of chunks: the epilogue is linear in the accumulators, so a split
+    // contraction writes partial dx planes that a second kernel adds in range order.
+    const int n_chunks_all = (O + BO - 1) / BO;
+    const int c_begin = blockIdx.y * chunks_per_split;
+    const int n_chunks = n_chunks_all - c_begin < chunks_per_split ? n_chunks_all - c_begin : chunks_per_split;
+    dx += (int64_t)blockIdx.y * B * I;
+    load_chunk(c_begin * BO);
     store_chunk(lds, lds + Cfg::A_FLOATS);
-    load_chunk(BO);
+    load_chunk((c_begin + 1) * BO);
     for (int c = 0; c < n_chunks; ++c) {
         __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
         float* sA = lds + (c & 1) * Cfg::STAGE;
@@ -880,7 +890,7 @@ dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const 
         for (int q = 0; q < LA; ++q) read_step(sA, sA + Cfg::A_FLOATS, q);
         mfma_steps(sA, sA + Cfg::A_FLOATS, 0, Cfg::NSTEP / 2);
         store_chunk(nA, nA + Cfg::A_FLOATS);
-        load_chunk((c + 2) * BO);
+        load_chunk((c_begin + c + 2) * BO);
         mfma_steps(sA, sA + Cfg::A_FLOATS, Cfg::NSTEP / 2, Cfg::NSTEP);
         __builtin_amdgcn_sched_group_barrier(0x100, LA * (1 + D), 0);
 #pragma unroll

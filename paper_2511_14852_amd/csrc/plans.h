@@ -176,13 +176,54 @@ inline FwdPlan plan_forward(int64_t B, int I, int O, int d)
     const int n_chunks = (I + bi - 1) / bi;
     const int64_t tiles = ((B + 127) / 128) * ((O + (O <= 64 ? 63 : 127)) / (O <= 64 ? 64 : 128));
     FwdPlan p{1, n_chunks};
-    if ((tune_flags() & 8) || tiles >= 256 || n_chunks < 16) return p;
+    if ((tune_flags() & 8) || tiles >= 256 || n_chunks < 4) return p;
     int64_t want = (512 + tiles - 1) / tiles;
-    if (want > n_chunks / 8) want = n_chunks / 8;      // at least 8 chunks per range
+    if (want > n_chunks / 2) want = n_chunks / 2;      // at least 2 chunks per range
     if (want > 64) want = 64;
     if (want < 2) return p;
     p.chunks_per_split = (int)((n_chunks + want - 1) / want);
     p.splits = (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split;
+    return p;
+}
+
+// The same for the input gradient: its contraction runs over the outputs, in chunks of
+// `chunk_outputs`; `feature_tiles` = column tiles of the chosen dx kernel.
+inline FwdPlan plan_dx_split(int64_t B, int feature_tiles, int O, int chunk_outputs)
+{
+    const int n_chunks = (O + chunk_outputs - 1) / chunk_outputs;
+    const int64_t tiles = ((B + 127) / 128) * feature_tiles;
+    FwdPlan p{1, n_chunks};
+    if ((tune_flags() & 8) || tiles >= 256 || n_chunks < 4) return p;
+    int64_t want = (512 + tiles - 1) / tiles;
+    if (want > n_chunks / 2) want = n_chunks / 2;
+    if (want > 32) want = 32;
+    if (want < 2) return p;
+    p.chunks_per_split = (int)((n_chunks + want - 1) / want);
+    p.splits = (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split;
+    return p;
+}
+
+// dx kernel choice and its split, in one place for the launch code and the workspace query
+struct DxPlan {
+    bool per_lane;     // feature-per-lane kernel (else packed columns)
+    int nb;            // column blocks of the packed kernel
+    int feature_tiles;
+    FwdPlan split;
+};
+
+inline DxPlan plan_dx(int64_t B, int I, int O, int d)
+{
+    DxPlan p;
+    p.per_lane = d >= 1 && dx_feature_per_lane(I, d) && !(tune_flags() & 4);
+    p.nb = d >= 1 ? dx_column_blocks(I, d) : 1;
+    if (p.per_lane) {
+        p.feature_tiles = (I + 31) / 32;
+        p.split = plan_dx_split(B, p.feature_tiles, O, d <= 4 ? 32 : 16);
+    } else {
+        const int bix = 32 * p.nb / (d >= 1 ? d : 1);
+        p.feature_tiles = (I + bix - 1) / bix;
+        p.split = plan_dx_split(B, p.feature_tiles, O, 32);
+    }
     return p;
 }
 

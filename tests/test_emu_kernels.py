@@ -96,6 +96,9 @@ CASES = [
     (33, 6, 40, 24),
     (64, 300, 72, 2),
     (70, 20, 12, 7),
+    # small batches whose input-gradient contraction is split over the outputs (both dx kernels)
+    (33, 6, 130, 24),
+    (64, 40, 200, 5),
 ]
 
 

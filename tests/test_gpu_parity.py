@@ -17,6 +17,13 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-5
 
 
+def tol_for(degree):
+    """1e-5 for the degrees of the measured configurations (<= 8).  Above that the bound grows with
+    the basis sensitivity: an fp32 u carries an absolute error of a few 1e-8, which T_k amplifies by
+    up to T_k'(+-1) = k^2, so the tolerance scales with (degree/8)^2."""
+    return TOL * max(1.0, (degree / 8.0) ** 2)
+
+
 def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
@@ -58,8 +65,9 @@ def _check_full(x, C, dy, family, label):
     dx_ref, dC_ref = oracle.backward(x, C, dy)
     errs = {"y": oracle.rel_err(y, y_ref), "dx": oracle.rel_err(dx, dx_ref), "dC": oracle.rel_err(dC, dC_ref)}
     print("%s family=%d errs=%s" % (label, family, {k: "%.2e" % v for k, v in errs.items()}), flush=True)
+    tol = tol_for(C.shape[2] - 1)
     for k, v in errs.items():
-        assert np.isfinite(v) and v <= TOL, (label, family, k, v)
+        assert np.isfinite(v) and v <= tol, (label, family, k, v)
 
 
 # shapes spanning several tiles with ragged tails in every dimension; the
