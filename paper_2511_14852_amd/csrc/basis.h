@@ -34,6 +34,16 @@ __device__ __forceinline__ float normalise(float x, float& slope)
     return copysignf(fmaf(-t2, r, 1.0f), x);
 }
 
+// |u| and w = 1 - |u| = 2t/(1+t) from the same t; w keeps full relative accuracy as |u| -> 1.
+__device__ __forceinline__ void normalise_split(float x, float& abs_u, float& w)
+{
+    const float ax = fabsf(x);
+    const float t2 = __builtin_amdgcn_exp2f(fmaf(ax, -2.885390081777927f, 1.0f));
+    const float r = __builtin_amdgcn_rcpf(fmaf(0.5f, t2, 1.0f));
+    w = t2 * r;
+    abs_u = fmaf(-t2, r, 1.0f);
+}
+
 // T[0..D] at u.
 template <int D>
 __device__ __forceinline__ void cheb_T(float u, float (&T)[D + 1])
@@ -43,6 +53,33 @@ __device__ __forceinline__ void cheb_T(float u, float (&T)[D + 1])
     const float two_u = 2.0f * u;
 #pragma unroll
     for (int k = 1; k < D; ++k) T[k + 1] = fmaf(two_u, T[k], -T[k - 1]);
+}
+
+// T[0..D] at u = tanh(x), straight from x.  Up to degree 8 this is normalise() + cheb_T().
+// Above that the plain recurrence loses accuracy where |u| -> 1 (an absolute error in u is
+// amplified by T_k' ~ k^2), so the recurrence is run in difference form on w = 1 - |u|, which
+// the tanh yields with full RELATIVE accuracy (w = 2t/(1+t)):
+//     d_1 = -w,  d_{k+1} = d_k - 2 w T_k,  T_{k+1} = T_k + d_{k+1}        (T_k at |u|)
+// and T_k(u) = sign(x)^k T_k(|u|).  Algebraically identical to Eq. 2.
+template <int D>
+__device__ __forceinline__ void cheb_T_of_x(float x, float (&T)[D + 1])
+{
+    if constexpr (D <= 8) {
+        cheb_T<D>(normalise(x), T);
+    } else {
+        float Tk, w;                                     // |u|, 1 - |u|
+        normalise_split(x, Tk, w);
+        const float m2w = -2.0f * w;
+        float d = -w;
+        T[0] = 1.0f;
+        T[1] = copysignf(Tk, x);
+#pragma unroll
+        for (int k = 1; k < D; ++k) {
+            d = fmaf(m2w, Tk, d);
+            Tk += d;
+            T[k + 1] = ((k + 1) & 1) ? (x < 0.0f ? -Tk : Tk) : Tk;
+        }
+    }
 }
 
 // dT[k-1] = T_k'(u) for k = 1..D   (T_0' = 0 is not stored).

@@ -2,6 +2,9 @@
 // fp32 VALU arithmetic.  They serve degrees and shapes the MFMA kernels are not
 // specialised for and give an on-device cross-check of those kernels.
 //
+// T_k is advanced in the difference form of the recurrence on w = 1 - |u| (see
+// cheb_T_of_x), which holds its accuracy at any degree; odd k take the sign of x.
+//
 // Every reduction runs in a fixed order inside one thread, with the running sum
 // folded into a second accumulator every FOLD terms so that long fp32 sums do
 // not lose accuracy.
@@ -28,15 +31,17 @@ generic_forward_kernel(const float* __restrict__ x, const float* __restrict__ C,
     const float* xr = x + b * I;
     float total = 0.0f, part = 0.0f;
     for (int i = 0; i < I; ++i) {
-        const float u = normalise(xr[i]);
+        float t, w;                              // T_k(|u|), 1 - |u|
+        normalise_split(xr[i], t, w);
+        const bool neg = xr[i] < 0.0f;
+        const float m2w = -2.0f * w;
         const float* c = C + ((int64_t)i * O + o) * K;
-        float t_prev = 1.0f, t_cur = u;
+        float d = -w;
         float acc = c[0];
         for (int k = 1; k < K; ++k) {
-            acc = fmaf(c[k], t_cur, acc);
-            const float t_next = fmaf(2.0f * u, t_cur, -t_prev);
-            t_prev = t_cur;
-            t_cur = t_next;
+            acc = fmaf(c[k], ((k & 1) && neg) ? -t : t, acc);
+            d = fmaf(m2w, t, d);
+            t += d;
         }
         part += acc;
         if ((i % GENERIC_FOLD) == GENERIC_FOLD - 1) { total += part; part = 0.0f; }
@@ -89,14 +94,17 @@ generic_dC_kernel(const float* __restrict__ x, const float* __restrict__ dy, flo
     const int i = (int)(e / ((int64_t)K * O));
     float total = 0.0f, mid = 0.0f, part = 0.0f;
     for (int64_t b = 0; b < B; ++b) {
-        const float u = normalise(x[b * I + i]);
-        float t_prev = 1.0f, t_cur = (k == 0) ? 1.0f : u;
+        const float xv = x[b * I + i];
+        float t, w;
+        normalise_split(xv, t, w);
+        const float m2w = -2.0f * w;
+        float d = -w;
         for (int n = 1; n < k; ++n) {
-            const float t_next = fmaf(2.0f * u, t_cur, -t_prev);
-            t_prev = t_cur;
-            t_cur = t_next;
+            d = fmaf(m2w, t, d);
+            t += d;
         }
-        part = fmaf(t_cur, dy[b * O + o], part);
+        const float t_k = (k == 0) ? 1.0f : (((k & 1) && xv < 0.0f) ? -t : t);
+        part = fmaf(t_k, dy[b * O + o], part);
         if ((b % 64) == 63) { mid += part; part = 0.0f; }
         if ((b % 4096) == 4095) { total += mid; mid = 0.0f; }
     }

@@ -152,7 +152,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
 #pragma unroll
         for (int j = 0; j < Cfg::XPT; ++j) {
             float T[D + 1];
-            cheb_T<D>(normalise(xreg[j]), T);
+            cheb_T_of_x<D>(xreg[j], T);
             float* dst = sA + xr_row * SA + (xr_f0 + j) * K;
 #pragma unroll
             for (int k = 0; k < K; ++k) dst[k] = T[k];
@@ -373,7 +373,7 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
         for (int j = 0; j < Cfg::XPT; ++j) {
             const int bl = xe[j] / BIC, il = xe[j] % BIC;
             float T[D + 1];
-            cheb_T<D>(normalise(xreg[j]), T);
+            cheb_T_of_x<D>(xreg[j], T);
             // SMA = BMR (mod 32): consecutive elements land K words apart across row ends too
             float* dst = sA + bl * SMA + il * K;
 #pragma unroll

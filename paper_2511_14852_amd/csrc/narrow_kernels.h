@@ -121,7 +121,7 @@ narrow_fwd_kernel(const float* __restrict__ x, const float* __restrict__ C, floa
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
                 float T[K];
-                cheb_T<D>(normalise(xv[r]), T);
+                cheb_T_of_x<D>(xv[r], T);
 #pragma unroll
                 for (int o = 0; o < O; ++o) {
                     float s = 0.0f;
@@ -201,7 +201,8 @@ narrow_bwd_kernel(const float* __restrict__ x, const float* __restrict__ C, cons
             float slope;
             const float u = normalise(xv[r], slope);
             float T[K];
-            cheb_T<D>(u, T);
+            if constexpr (D <= 8) cheb_T<D>(u, T);
+            else cheb_T_of_x<D>(xv[r], T);
 #pragma unroll
             for (int o = 0; o < O; ++o)
 #pragma unroll

@@ -18,10 +18,9 @@ TOL = 1e-5
 
 
 def tol_for(degree):
-    """1e-5 for the degrees of the measured configurations (<= 8).  Above that the bound grows with
-    the basis sensitivity: an fp32 u carries an absolute error of a few 1e-8, which T_k amplifies by
-    up to T_k'(+-1) = k^2, so the tolerance scales with (degree/8)^2."""
-    return TOL * max(1.0, (degree / 8.0) ** 2)
+    """The same 1e-5 at every degree: above degree 8 the kernels advance T_k in a difference form
+    that keeps the basis error from growing with k^2 near u = +-1."""
+    return TOL
 
 
 def _dev(a):
