@@ -86,8 +86,15 @@ void pick_dC(const float* x, const float* dy, float* dC, float* partial, int B, 
         if (vec) launch_dC<D, 128, 4>(x, dy, partial, B, I, O, p, s);
         else launch_dC<D, 128, 1>(x, dy, partial, B, I, O, p, s);
     }
-    hipLaunchKernelGGL(dC_combine_kernel<D>, dim3((unsigned)((O + 31) / 32), (unsigned)I), dim3(256),
-                       256 * ((D + 1) | 1) * sizeof(float), s, partial, dC, I, O, p.slices);
+    const dim3 grid((unsigned)((O + 31) / 32), (unsigned)I);
+    static bool once = (allow_lds(dC_combine_kernel<D, 32>, 1024 * ((D + 1) | 1) * (int)sizeof(float)), true);
+    (void)once;
+    if (p.slices > 32)
+        hipLaunchKernelGGL((dC_combine_kernel<D, 32>), grid, dim3(1024), 1024 * ((D + 1) | 1) * sizeof(float), s,
+                           partial, dC, I, O, p.slices);
+    else
+        hipLaunchKernelGGL((dC_combine_kernel<D, 8>), grid, dim3(256), 256 * ((D + 1) | 1) * sizeof(float), s,
+                           partial, dC, I, O, p.slices);
 }
 
 // --------------------------------------------------------------------- dx

@@ -29,6 +29,12 @@
 #include "basis.h"
 #include "buffer_io.h"
 
+// Optional in-kernel time stamps for profiling builds (slot 0 kernel entry, 1 before the
+// chunk loop, 2 after it, 3 kernel exit); compiled out unless the includer defines it.
+#ifndef CHEBYKAN_PROBE
+#define CHEBYKAN_PROBE(slot)
+#endif
+
 namespace chebykan {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -96,6 +102,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
     constexpr int D = Cfg::D, K = Cfg::K, KP = Cfg::KP, BN = Cfg::BN, BI = Cfg::BI, VEC = Cfg::VEC;
     constexpr int SA = Cfg::SA, SS = Cfg::SS, TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
     extern __shared__ __align__(16) float lds[];
+    CHEBYKAN_PROBE(0);
 
     const int t = threadIdx.x;
     const int tile_o = blockIdx.x % n_tiles_o;
@@ -222,6 +229,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
     load_chunk(c_begin * BI);
     store_chunk(lds, lds + Cfg::A_FLOATS);
     load_chunk((c_begin + 1) * BI);
+    CHEBYKAN_PROBE(1);
     for (int c = 0; c < n_chunks; ++c) {
         __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
         float* sA = lds + (c & 1) * Cfg::STAGE;
@@ -251,6 +259,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
                 for (int j = 0; j < TN; ++j) { total[i][j] += acc[i][j]; acc[i][j] = zero16(); }
         }
     }
+    CHEBYKAN_PROBE(2);
 
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -264,6 +273,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
                 if (row < B && col < O) y[(int64_t)row * O + col] = v[r];
             }
         }
+    CHEBYKAN_PROBE(3);
 }
 
 // =================================================== coefficient gradient
@@ -304,6 +314,7 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
     constexpr int D = Cfg::D, K = Cfg::K, BN = Cfg::BN, VEC = Cfg::VEC, BB = Cfg::BB, BIC = Cfg::BIC;
     constexpr int SMA = Cfg::SMA, SNB = Cfg::SNB, TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
     extern __shared__ __align__(16) float lds[];
+    CHEBYKAN_PROBE(0);
 
     const int t = threadIdx.x;
     // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.
@@ -423,6 +434,7 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
     load_chunk(0);
     store_chunk(lds, lds + Cfg::A_FLOATS);
     load_chunk(1);
+    CHEBYKAN_PROBE(1);
     for (int c = 0; c < n_chunks; ++c) {
         __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
         float* sA = lds + (c & 1) * Cfg::STAGE;
@@ -447,6 +459,7 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
         }
     }
 
+    CHEBYKAN_PROBE(2);
     const int64_t IK = (int64_t)I * K;
     float* out = partial + (int64_t)slice * IK * O;
 #pragma unroll
@@ -462,15 +475,17 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
                 if (ml < Cfg::BMR && mg < IK && col < O) out[mg * O + col] = v[r];
             }
         }
+    CHEBYKAN_PROBE(3);
 }
 
-// dC[i,o,k] = sum_s partial[s][(i,k)][o] in a fixed order: 8 slice groups take every 8th
-// slice each, then the 8 group sums are added in group order.  Also turns the [(i,k)][o]
+// dC[i,o,k] = sum_s partial[s][(i,k)][o] in a fixed order: G slice groups take every G-th
+// slice each, then the G group sums are added in group order.  Also turns the [(i,k)][o]
 // rows of the partials into the caller's [i][o][k] layout through LDS, so that reads and
-// writes are both unit-stride.  block = 8 slice groups x 32 outputs; grid = (ceil(O/32), I).
-// Dynamic LDS: 256 * ((D+1)|1) floats.
-template <int D>
-__global__ void __launch_bounds__(256)
+// writes are both unit-stride.  block = G slice groups x 32 outputs; grid = (ceil(O/32), I).
+// G = 32 (1024 threads) shortens the serial chain per thread when there are many slices.
+// Dynamic LDS: G * 32 * ((D+1)|1) floats.
+template <int D, int G>
+__global__ void __launch_bounds__(G * 32)
 dC_combine_kernel(const float* __restrict__ partial, float* __restrict__ dC, int I, int O, int n_slices)
 {
     constexpr int K = D + 1, KP = K | 1;
@@ -481,12 +496,22 @@ dC_combine_kernel(const float* __restrict__ partial, float* __restrict__ dC, int
     const int i = blockIdx.y;
     const int o = oc + ol;
     const int64_t IK = (int64_t)I * K;
+    const int64_t slice_stride = IK * O;
     float v[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) v[k] = 0.0f;
     if (o < O) {
-        for (int s = sg; s < n_slices; s += 8) {
-            const float* p = partial + ((int64_t)s * IK + (int64_t)i * K) * O + o;
+        const float* p = partial + (int64_t)sg * slice_stride + (int64_t)i * K * O + o;
+        int s = sg;
+        // two slices per trip: both sets of loads are issued before either is added
+        for (; s + G < n_slices; s += 2 * G, p += 2 * G * slice_stride) {
+            float a[K], b[K];
+#pragma unroll
+            for (int k = 0; k < K; ++k) { a[k] = p[(int64_t)k * O]; b[k] = p[G * slice_stride + (int64_t)k * O]; }
+#pragma unroll
+            for (int k = 0; k < K; ++k) { v[k] += a[k]; v[k] += b[k]; }
+        }
+        if (s < n_slices) {
 #pragma unroll
             for (int k = 0; k < K; ++k) v[k] += p[(int64_t)k * O];
         }
@@ -496,11 +521,11 @@ dC_combine_kernel(const float* __restrict__ partial, float* __restrict__ dC, int
     __syncthreads();
     const int n_valid = (O - oc < 32 ? O - oc : 32) * K;
     float* dst = dC + ((int64_t)i * O + oc) * K;
-    for (int e = t; e < n_valid; e += 256) {
+    for (int e = t; e < n_valid; e += G * 32) {
         const int o2 = e / K, k = e % K;
         float total = 0.0f;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) total += lds[(q * 32 + o2) * KP + k];
+        for (int q = 0; q < G; ++q) total += lds[(q * 32 + o2) * KP + k];
         dst[e] = total;
     }
 }
@@ -547,6 +572,7 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
     constexpr int D = Cfg::D, K = Cfg::K, VEC = Cfg::VEC, BIX = Cfg::BIX, BO = Cfg::BO, NB = Cfg::NB;
     constexpr int SAX = Cfg::SAX, SSX = Cfg::SSX, SG = Cfg::SG;
     extern __shared__ __align__(16) float lds[];
+    CHEBYKAN_PROBE(0);
 
     const int t = threadIdx.x;
     const int tile_i = blockIdx.x % n_tiles_i;
@@ -755,6 +781,7 @@ dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const 
     constexpr int D = Cfg::D, K = Cfg::K, VEC = Cfg::VEC, BF = Cfg::BF, BO = Cfg::BO;
     constexpr int SAX = Cfg::SAX, SSX = Cfg::SSX;
     extern __shared__ __align__(16) float lds[];
+    CHEBYKAN_PROBE(0);
 
     const int t = threadIdx.x;
     const int tile_i = blockIdx.x % n_tiles_i;
@@ -882,6 +909,7 @@ dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const 
     load_chunk(c_begin * BO);
     store_chunk(lds, lds + Cfg::A_FLOATS);
     load_chunk((c_begin + 1) * BO);
+    CHEBYKAN_PROBE(1);
     for (int c = 0; c < n_chunks; ++c) {
         __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
         float* sA = lds + (c & 1) * Cfg::STAGE;
@@ -903,6 +931,7 @@ dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const 
         }
         if ((c + 1) % Cfg::FOLD == 0) fold();
     }
+    CHEBYKAN_PROBE(2);
     fold();
 
     if (f_ok) {
@@ -912,6 +941,7 @@ dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const 
             if (row < B) dx[(int64_t)row * I + i0 + l32] = dxacc[r];
         }
     }
+    CHEBYKAN_PROBE(3);
 }
 
 }  // namespace chebykan

@@ -258,8 +258,17 @@ sum_slices_kernel(const float* __restrict__ partial, float* __restrict__ out, in
     const int el = threadIdx.x % EL, sg = threadIdx.x / EL;
     const int64_t e = (int64_t)blockIdx.x * EL + el;
     float s = 0.0f;
-    if (e < n)
-        for (int q = sg; q < n_slices; q += GROUPS) s += partial[(int64_t)q * n + e];
+    if (e < n) {
+        const float* p = partial + (int64_t)sg * n + e;
+        const int64_t step = (int64_t)GROUPS * n;
+        int q = sg;
+        // four slices per trip: the loads are issued together, the adds keep slice order
+        for (; q + 3 * GROUPS < n_slices; q += 4 * GROUPS, p += 4 * step) {
+            const float a0 = p[0], a1 = p[step], a2 = p[2 * step], a3 = p[3 * step];
+            s += a0; s += a1; s += a2; s += a3;
+        }
+        for (; q < n_slices; q += GROUPS, p += step) s += p[0];
+    }
     lds[sg * (EL + 1) + el] = s;
     __syncthreads();
     if (sg == 0 && e < n) {
