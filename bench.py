@@ -126,6 +126,30 @@ def call_work(tag, B, I, O, d):
     return 2 * B * I * O * K, 4 * (B * I + B * O + I * O * K)
 
 
+def measured_peaks(torch, binding, stream):
+    """What this GPU sustains on a register-only fp32 MFMA loop and on a plain 256 MiB copy."""
+    sink = torch.empty(512 * 256, dtype=torch.float32, device="cuda")
+    src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(reps):
+            out = fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps, out
+
+    # 512 workgroups = one resident round of 2 per CU; 2000 trips of 32 MFMAs per wave (about 2 ms)
+    t_mfma, flops = timed(lambda: binding.chebykan_calibrate_mfma(sink, 512, 2000, stream), 5)
+    t_copy, nbytes = timed(lambda: binding.chebykan_calibrate_copy(dst, src, stream), 10)
+    return {"mfma_f32_tflops": round(flops / t_mfma / 1e12, 1), "copy_gbs_read_plus_write": round(2 * nbytes / t_copy / 1e9, 1),
+            "note": "register-only v_mfma_f32_32x32x2_f32 loop on 512 workgroups; 256 MiB device copy"}
+
+
 def cpu_baseline(w, wl, target_seconds):
     """Time the fp64 oracle on the host cores over a bounded row sample of the workload."""
     import oracle
@@ -244,6 +268,7 @@ def main():
         "roofline": roof,
         "calls": per_call,
     }
+    line["measured_peaks"] = measured_peaks(torch, binding, st.stream)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, wl, args.cpu_seconds)
     print(json.dumps(line), flush=True)

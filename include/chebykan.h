@@ -106,6 +106,27 @@ const char *chebykan_status_string(chebykan_status status);
  */
 int chebykan_set_kernel_family(int family);
 
+/*
+ * Roofline calibration (measurement aids, no part of the paper's method): what
+ * the GPU sustains on the two limits the layer kernels are priced against.
+ *
+ * chebykan_calibrate_mfma enqueues `workgroups` workgroups of 4 waves, each wave
+ * issuing iterations*32 register-only v_mfma_f32_32x32x2_f32 (no memory traffic
+ * in the loop).  `sink` is device memory of at least workgroups*256 floats that
+ * the kernel overwrites; *flops (host pointer, may be NULL) receives the number
+ * of floating-point operations of the launch.  The caller times the launch.
+ *
+ * chebykan_calibrate_copy enqueues dst[0..n) = src[0..n) as a plain streaming
+ * copy (16 bytes per thread): n*4 bytes read and n*4 bytes written.  dst and src
+ * are device pointers, 16-byte aligned, non-overlapping; n is a multiple of 4.
+ *
+ * Both return CHEBYKAN_ERR_NULL / CHEBYKAN_ERR_SHAPE for bad arguments and
+ * CHEBYKAN_ERR_LAUNCH if HIP refuses the launch; nothing is allocated.
+ */
+chebykan_status chebykan_calibrate_mfma(float *sink, int workgroups, int iterations, double *flops,
+                                        chebykan_stream_t stream);
+chebykan_status chebykan_calibrate_copy(float *dst, const float *src, int64_t n, chebykan_stream_t stream);
+
 /* Library/ABI version: major*1000 + minor. */
 int chebykan_version(void);
 

@@ -25,6 +25,7 @@ CHEBYKAN_MAX_DEGREE = 32
 EXPORTS = (
     "chebykan_workspace_bytes", "chebykan_forward", "chebykan_backward",
     "chebykan_status_string", "chebykan_set_kernel_family", "chebykan_version",
+    "chebykan_calibrate_mfma", "chebykan_calibrate_copy",
 )
 
 _lib: Optional[ctypes.CDLL] = None
@@ -60,6 +61,10 @@ def load() -> ctypes.CDLL:
         lib.chebykan_set_kernel_family.restype = ci
         lib.chebykan_version.argtypes = []
         lib.chebykan_version.restype = ci
+        lib.chebykan_calibrate_mfma.argtypes = [vp, ci, ci, ctypes.POINTER(ctypes.c_double), vp]
+        lib.chebykan_calibrate_mfma.restype = ci
+        lib.chebykan_calibrate_copy.argtypes = [vp, vp, i64, vp]
+        lib.chebykan_calibrate_copy.restype = ci
         _lib = lib
     return _lib
 
@@ -91,6 +96,29 @@ def chebykan_set_kernel_family(family: int) -> int:
 
 def chebykan_version() -> int:
     return int(load().chebykan_version())
+
+
+def chebykan_calibrate_mfma(sink, workgroups: int, iterations: int, stream=None) -> float:
+    """Enqueue the register-only MFMA loop; returns the flop count of the launch."""
+    _check(sink, "sink")
+    if sink.numel() < workgroups * 256:
+        raise ValueError("sink needs workgroups*256 floats")
+    flops = ctypes.c_double(0.0)
+    st = int(load().chebykan_calibrate_mfma(sink.data_ptr(), workgroups, iterations, ctypes.byref(flops),
+                                            _stream_ptr(stream)))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_calibrate_mfma")
+    return flops.value
+
+
+def chebykan_calibrate_copy(dst, src, stream=None) -> int:
+    """Enqueue dst = src as a plain streaming copy; returns the bytes moved each way."""
+    _check(src, "src")
+    _check(dst, "dst", src.shape)
+    st = int(load().chebykan_calibrate_copy(dst.data_ptr(), src.data_ptr(), src.numel(), _stream_ptr(stream)))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_calibrate_copy")
+    return src.numel() * 4
 
 
 # ------------------------------------------------------------ tensor calls

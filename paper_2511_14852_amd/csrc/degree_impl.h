@@ -60,11 +60,11 @@ void pick_fwd(const float* x, const float* C, float* y, float* partial, int B, i
 }
 
 // --------------------------------------------------------------------- dC
-template <int D, int BN, int VEC>
+template <int D, int BN, int VEC, int BIC>
 void launch_dC(const float* x, const float* dy, float* partial, int B, int I, int O, const DcPlan& p,
                hipStream_t s)
 {
-    using Cfg = DcCfg<D, BN, VEC>;
+    using Cfg = DcCfg<D, BN, VEC, BIC>;
     static bool once = (allow_lds(dC_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
     (void)once;
     const int tiles_o = (O + BN - 1) / BN;
@@ -74,17 +74,29 @@ void launch_dC(const float* x, const float* dy, float* partial, int B, int I, in
                        p.rows_per_slice);
 }
 
+template <int D, int BIC>
+void pick_dC_tile(const float* x, const float* dy, float* partial, int B, int I, int O, const DcPlan& p,
+                  hipStream_t s)
+{
+    const bool vec = aligned16(dy) && O % 4 == 0;
+    if (p.bn == 64) {
+        if (vec) launch_dC<D, 64, 4, BIC>(x, dy, partial, B, I, O, p, s);
+        else launch_dC<D, 64, 1, BIC>(x, dy, partial, B, I, O, p, s);
+    } else {
+        if (vec) launch_dC<D, 128, 4, BIC>(x, dy, partial, B, I, O, p, s);
+        else launch_dC<D, 128, 1, BIC>(x, dy, partial, B, I, O, p, s);
+    }
+}
+
 template <int D>
 void pick_dC(const float* x, const float* dy, float* dC, float* partial, int B, int I, int O, const DcPlan& p,
              hipStream_t s)
 {
-    const bool vec = aligned16(dy) && O % 4 == 0;
-    if (p.bn == 64) {
-        if (vec) launch_dC<D, 64, 4>(x, dy, partial, B, I, O, p, s);
-        else launch_dC<D, 64, 1>(x, dy, partial, B, I, O, p, s);
+    if constexpr (D == 6) {
+        if (dc_tile_features_for(I, D) == 16) pick_dC_tile<D, 16>(x, dy, partial, B, I, O, p, s);
+        else pick_dC_tile<D, dc_tile_features(D)>(x, dy, partial, B, I, O, p, s);
     } else {
-        if (vec) launch_dC<D, 128, 4>(x, dy, partial, B, I, O, p, s);
-        else launch_dC<D, 128, 1>(x, dy, partial, B, I, O, p, s);
+        pick_dC_tile<D, dc_tile_features(D)>(x, dy, partial, B, I, O, p, s);
     }
     const dim3 grid((unsigned)((O + 31) / 32), (unsigned)I);
     static bool once = (allow_lds(dC_combine_kernel<D, 32>, 1024 * ((D + 1) | 1) * (int)sizeof(float)), true);

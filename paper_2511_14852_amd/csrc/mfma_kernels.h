@@ -277,10 +277,10 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
 }
 
 // =================================================== coefficient gradient
-template <int D_, int BN_, int VEC_>
+template <int D_, int BN_, int VEC_, int BIC_ = 128 / (D_ + 1)>
 struct DcCfg {
     static constexpr int D = D_, K = D_ + 1, BN = BN_, VEC = VEC_;
-    static constexpr int BIC = 128 / K;                 // input features per tile
+    static constexpr int BIC = BIC_;                    // input features per tile
     static constexpr int BMR = BIC * K;                 // real rows (i,k) of the 128-row tile
     static constexpr int BB = 32;                       // batch rows per chunk
     static constexpr int SMA = 128 + (BMR % 32);        // Phi^T tile row stride (see store below)
@@ -298,6 +298,7 @@ struct DcCfg {
     static constexpr int GPT = NEB / VEC / MFMA_THREADS;
     static_assert(NEB % (VEC * MFMA_THREADS) == 0, "dy tile must split evenly");
     static_assert(A_FLOATS % 4 == 0, "dy tile must stay 16-byte aligned");
+    static_assert(BIC >= 1 && BMR <= 128, "tile rows");
 };
 
 // partial[s][(i,k)][o] = sum over the rows of batch slice s of T_k(tanh x[b,i]) dy[b,o]
