@@ -13,7 +13,7 @@ from typing import Optional, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "chebykan_oracle.c")
+_SRCS = [os.path.join(_HERE, "chebykan_oracle.c"), os.path.join(_HERE, "chebykan_lut_oracle.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib: Optional[ctypes.CDLL] = None
 
@@ -22,10 +22,10 @@ MAX_DEGREE = 64
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (-O2, OpenMP, no fast-math)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(s) for s in _SRCS):
         tmp = _LIB + ".tmp.%d" % os.getpid()
         cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-               "-ffp-contract=off", "-o", tmp, _SRC, "-lm"]
+               "-ffp-contract=off", "-o", tmp, *_SRCS, "-lm"]
         subprocess.run(cmd, check=True)
         os.replace(tmp, _LIB)
     return _LIB
@@ -57,6 +57,16 @@ def _load() -> ctypes.CDLL:
         lib.oracle_dx_at.restype = ctypes.c_int
         lib.oracle_dC_at.argtypes = [dp, dp, ip, ip, ip, i64, dp, i64, i64, i64, ctypes.c_int]
         lib.oracle_dC_at.restype = ctypes.c_int
+        i8p = ctypes.POINTER(ctypes.c_int8)
+        lib.oracle_lut_build.argtypes = [dp, ctypes.c_int, i64]
+        lib.oracle_lut_build.restype = ctypes.c_int
+        lib.oracle_lut_eval.argtypes = [dp, ctypes.c_int, i64, ctypes.c_double, ctypes.c_int, dp, dp,
+                                        ctypes.POINTER(ctypes.c_int64), dp]
+        lib.oracle_lut_eval.restype = None
+        lib.oracle_forward_lut.argtypes = [dp, dp, dp, i64, dp, i64, i64, i64, ctypes.c_int]
+        lib.oracle_forward_lut.restype = ctypes.c_int
+        lib.oracle_backward_lut.argtypes = [dp, dp, dp, dp, i64, i8p, dp, dp, dp, i64, i64, i64, ctypes.c_int]
+        lib.oracle_backward_lut.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -185,3 +195,61 @@ def rel_err(got, want) -> float:
     if rms == 0.0:
         return 0.0 if diff == 0.0 else float("inf")
     return diff / rms
+
+
+# ------------------------------------------------- table-interpolated variant
+
+def lut_build(degree: int, n: int) -> np.ndarray:
+    """LUT[k, i] = T_k(-1 + i*2/(n-1)) in fp64, shape [degree+1, n] (paper Sec. 4.2.1)."""
+    lut = np.empty((degree + 1, n), dtype=np.float64)
+    rc = _load().oracle_lut_build(_dp(lut), int(degree), int(n))
+    if rc != 0:
+        raise ValueError("oracle_lut_build failed")
+    return lut
+
+
+def lut_eval(lut, u: float, shift: int = 0):
+    """(T, dT, cell, frac) of the interpolated basis at u (paper Sec. 4.2.2)."""
+    lut = _f64(lut)
+    K, n = lut.shape
+    T = np.empty(K)
+    dT = np.empty(K)
+    cell = ctypes.c_int64(0)
+    frac = ctypes.c_double(0.0)
+    _load().oracle_lut_eval(_dp(lut), K - 1, n, float(u), int(shift), _dp(T), _dp(dT), ctypes.byref(cell),
+                            ctypes.byref(frac))
+    return T, dT, cell.value, frac.value
+
+
+def forward_lut(x, C, lut) -> np.ndarray:
+    B, I, O, d = _check_shapes(x, C)
+    x64, C64, lut = _f64(x), _f64(C), _f64(lut)
+    if lut.shape[0] != d + 1:
+        raise ValueError("table has %d rows, layer needs %d" % (lut.shape[0], d + 1))
+    y = np.empty((B, O), dtype=np.float64)
+    rc = _load().oracle_forward_lut(_dp(x64), _dp(C64), _dp(lut), lut.shape[1], _dp(y), B, I, O, d)
+    if rc != 0:
+        raise ValueError("oracle_forward_lut failed")
+    return y
+
+
+def backward_lut(x, C, dy, lut, need_dx: bool = True, need_dC: bool = True, shift=None, want_frac: bool = False):
+    """dx, dC (and the in-cell position of every input element when want_frac) of the interpolated layer."""
+    B, I, O, d = _check_shapes(x, C, dy)
+    x64, C64, dy64, lut = _f64(x), _f64(C), _f64(dy), _f64(lut)
+    if lut.shape[0] != d + 1:
+        raise ValueError("table has %d rows, layer needs %d" % (lut.shape[0], d + 1))
+    dx = np.empty((B, I), dtype=np.float64) if need_dx else None
+    dC = np.empty((I, O, d + 1), dtype=np.float64) if need_dC else None
+    frac = np.empty((B, I), dtype=np.float64) if want_frac else None
+    sh = None
+    if shift is not None:
+        sh = np.ascontiguousarray(shift, dtype=np.int8)
+        if sh.shape != (B, I):
+            raise ValueError("shift must be [batch, in]")
+    shp = sh.ctypes.data_as(ctypes.POINTER(ctypes.c_int8)) if sh is not None else None
+    rc = _load().oracle_backward_lut(_dp(x64), _dp(C64), _dp(dy64), _dp(lut), lut.shape[1], shp, _dp(dx), _dp(dC),
+                                     _dp(frac), B, I, O, d)
+    if rc != 0:
+        raise ValueError("oracle_backward_lut failed")
+    return (dx, dC, frac) if want_frac else (dx, dC)
