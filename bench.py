@@ -52,6 +52,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--family", type=int, default=0, help="kernel family override (0 auto)")
+    ap.add_argument("--basis", default="exact", choices=["exact", "lut"],
+                    help="exact = recurrences (default); lut = the paper's table-interpolated variant (Sec. 4.2)")
+    ap.add_argument("--lut-size", type=int, default=1025, help="table samples for --basis lut")
     ap.add_argument("--probe", type=int, default=0,
                     help="counter-collection mode for rocprofv3 --pmc: run this many steps of the split calls plus "
                          "one plain 256 MiB device copy (the calibration kernel of known size), then exit")
@@ -61,8 +64,9 @@ def parse_args():
 class Stack:
     """Device buffers and the launch sequence of one workload."""
 
-    def __init__(self, w, rotate, torch, binding, wl):
+    def __init__(self, w, rotate, torch, binding, wl, lut=None):
         self.w, self.torch, self.binding = w, torch, binding
+        self.lut = lut          # device table [degree+1, samples] or None for the exact basis
         B = w.batch
         self.B = B
         self.layers = w.layers
@@ -82,6 +86,20 @@ class Stack:
         self.ws = [binding.alloc_workspace(B, i, o, self.d) for (i, o) in self.layers]
         self.stream = torch.cuda.Stream()
 
+    def _fwd(self, xin, l, s):
+        b = self.binding
+        if self.lut is None:
+            b.chebykan_forward(xin, self.C[l], self.y[l], self.ws[l], s)
+        else:
+            b.chebykan_forward_lut(xin, self.C[l], self.lut, self.y[l], self.ws[l], s)
+
+    def _bwd(self, xin, l, dy, dx, dC, s):
+        b = self.binding
+        if self.lut is None:
+            b.chebykan_backward(xin, self.C[l], dy, dx, dC, self.ws[l], s)
+        else:
+            b.chebykan_backward_lut(xin, self.C[l], dy, self.lut, dx, dC, self.ws[l], s)
+
     def calls(self, step):
         """The ABI calls of one step, in order: (tag, layer, thunk)."""
         b, n = self.binding, len(self.layers)
@@ -91,14 +109,12 @@ class Stack:
         out = []
         for l in range(n):
             xin = x0 if l == 0 else self.y[l - 1]
-            out.append(("fwd", l, lambda l=l, xin=xin: b.chebykan_forward(xin, self.C[l], self.y[l], self.ws[l], s)))
+            out.append(("fwd", l, lambda l=l, xin=xin: self._fwd(xin, l, s)))
         for l in reversed(range(n)):
             xin = x0 if l == 0 else self.y[l - 1]
             dy = dyl if l == n - 1 else self.dx[l + 1]
-            out.append(("dx", l, lambda l=l, xin=xin, dy=dy:
-                        b.chebykan_backward(xin, self.C[l], dy, self.dx[l], None, self.ws[l], s)))
-            out.append(("dC", l, lambda l=l, xin=xin, dy=dy:
-                        b.chebykan_backward(xin, self.C[l], dy, None, self.dC[l], self.ws[l], s)))
+            out.append(("dx", l, lambda l=l, xin=xin, dy=dy: self._bwd(xin, l, dy, self.dx[l], None, s)))
+            out.append(("dC", l, lambda l=l, xin=xin, dy=dy: self._bwd(xin, l, dy, None, self.dC[l], s)))
         return out
 
     def step_fused_calls(self, step):
@@ -109,11 +125,11 @@ class Stack:
         s = self.stream
         for l in range(n):
             xin = x0 if l == 0 else self.y[l - 1]
-            b.chebykan_forward(xin, self.C[l], self.y[l], self.ws[l], s)
+            self._fwd(xin, l, s)
         for l in reversed(range(n)):
             xin = x0 if l == 0 else self.y[l - 1]
             dy = dyl if l == n - 1 else self.dx[l + 1]
-            b.chebykan_backward(xin, self.C[l], dy, self.dx[l], self.dC[l], self.ws[l], s)
+            self._bwd(xin, l, dy, self.dx[l], self.dC[l], s)
 
 
 def call_work(tag, B, I, O, d):
@@ -150,20 +166,21 @@ def measured_peaks(torch, binding, stream):
             "note": "register-only v_mfma_f32_32x32x2_f32 loop on 512 workgroups; 256 MiB device copy"}
 
 
-def cpu_baseline(w, wl, target_seconds):
+def cpu_baseline(w, wl, target_seconds, lut_size=0):
     """Time the fp64 oracle on the host cores over a bounded row sample of the workload."""
     import oracle
     threads = oracle.num_threads()
+    lut = oracle.lut_build(w.degree, lut_size).astype(np.float32) if lut_size else None
 
     def one_pass(rows):
         x0, Cs, dy_last = wl.workload_inputs(w, batch=rows)
         t0 = time.perf_counter()
         xs = [x0.astype(np.float64)]
         for C in Cs:
-            xs.append(oracle.forward(xs[-1], C))
+            xs.append(oracle.forward(xs[-1], C) if lut is None else oracle.forward_lut(xs[-1], C, lut))
         dy = dy_last.astype(np.float64)
         for l in reversed(range(len(Cs))):
-            dx, _ = oracle.backward(xs[l], Cs[l], dy)
+            dx, _ = oracle.backward(xs[l], Cs[l], dy) if lut is None else oracle.backward_lut(xs[l], Cs[l], dy, lut)
             dy = dx
         return time.perf_counter() - t0
 
@@ -192,7 +209,10 @@ def main():
     binding.load()
     binding.chebykan_set_kernel_family(args.family)
     w = wl.WORKLOADS[args.workload]
-    st = Stack(w, max(1, args.rotate), torch, binding, wl)
+    lut = None
+    if args.basis == "lut":
+        lut = binding.chebykan_lut_build(w.degree, args.lut_size).cuda()
+    st = Stack(w, max(1, args.rotate), torch, binding, wl, lut)
     B = w.batch
 
     if args.probe > 0:
@@ -248,7 +268,7 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(dom["gbs"] / PEAK_HBM_GBS, 4)}
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((w.name, dom["call"], dom["layer"]))
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((w.name, dom["call"], dom["layer"])) if lut is None else None
     roof["algorithmic_bytes"] = by
     roof["kernel"] = "%s layer %d (%d->%d)" % (dom["call"], dom["layer"], I, O)
     roof["us"] = dom["us"]
@@ -259,8 +279,10 @@ def main():
         "metric": "Cheby-KAN fwd+bwd samples/s", "value": B / (ms_per_step * 1e-3), "unit": "samples/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: %s, batch %d, widths %s, degree %d" % (
-            w.name, w.note, B, "->".join(map(str, w.widths)), w.degree), "input_sets_rotated": len(st.x0_sets)},
+        "config": {"workload": "%s: %s, batch %d, widths %s, degree %d%s" % (
+            w.name, w.note, B, "->".join(map(str, w.widths)), w.degree,
+            "" if lut is None else ", table-interpolated basis with %d samples" % args.lut_size),
+            "input_sets_rotated": len(st.x0_sets), "basis": args.basis},
         "tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
         "algorithmic_gbs": total_bytes / (ms_per_step * 1e-3) / 1e9,
         "mfma_frac": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS,
@@ -270,7 +292,7 @@ def main():
     }
     line["measured_peaks"] = measured_peaks(torch, binding, st.stream)
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(w, wl, args.cpu_seconds)
+        line["cpu_baseline"] = cpu_baseline(w, wl, args.cpu_seconds, args.lut_size if lut is not None else 0)
     print(json.dumps(line), flush=True)
 
 

@@ -12,8 +12,9 @@
  *   dx[b,i]   = (1 - u^2) * sum_o dy[b,o] * sum_{k=1..degree} C[i,o,k] * T_k'(u)
  *
  * There is no bias term.  dx is the gradient with respect to the raw input, so
- * it carries the tanh derivative.  The basis and its derivative are evaluated
- * exactly (three-term recurrences), not by table interpolation.
+ * it carries the tanh derivative.  chebykan_forward / chebykan_backward evaluate
+ * the basis and its derivative exactly (three-term recurrences); the *_lut entry
+ * points further down are the paper's table-interpolated variant.
  *
  * Conventions common to every entry point
  *  - All tensor pointers are DEVICE pointers owned by the caller, fp32,
@@ -94,6 +95,48 @@ chebykan_status chebykan_backward(const float *x, const float *C, const float *d
                                   int64_t batch, int in, int out, int degree,
                                   void *workspace, size_t workspace_bytes,
                                   chebykan_stream_t stream);
+
+/*
+ * Table-interpolated variant (paper Sec. 4.2, "Polynomial Operators Acceleration
+ * via LUT").  The basis is not evaluated by the recurrence but read from a table
+ *
+ *   LUT[k][i] = T_k(-1 + i*Delta),  Delta = 2/(lut_size-1),  k = 0..degree,
+ *                                                             i = 0..lut_size-1   (Sec. 4.2.1)
+ *
+ * by linear interpolation (Sec. 4.2.2): with u = tanh(x), pos = (u+1)/2*(lut_size-1),
+ * c = min(floor(pos), lut_size-2), f = pos - c,
+ *
+ *   T_k(u)  ~ LUT[k][c] + f*(LUT[k][c+1] - LUT[k][c])
+ *   T_k'(u) ~ (LUT[k][c+1] - LUT[k][c]) / Delta        (difference of adjacent samples)
+ *
+ * and y, dC, dx are formed from these exactly as in the exact entry points (dx
+ * again includes the factor 1 - u^2).  The result is an APPROXIMATION of the exact
+ * layer: the value error is at most Delta^2/8 * k^2(k^2-1)/3 per basis function,
+ * the derivative is only first-order accurate (error up to Delta * k^2(k^2-1)/3).
+ *
+ * chebykan_lut_build fills a HOST array of (degree+1)*lut_size floats, row k at
+ * lut + k*lut_size, from the recurrence in double precision (the "offline
+ * construction on the CPU" of Sec. 4.2.1); the caller copies it to the device.
+ *
+ * chebykan_forward_lut / chebykan_backward_lut take that table as a DEVICE
+ * pointer `lut` in the same layout; every other argument, the workspace size
+ * (chebykan_workspace_bytes of the same shape), ownership, overwrite semantics,
+ * reproducibility and error behaviour are those of chebykan_forward /
+ * chebykan_backward.  Tables of up to 80 KiB ((degree+1)*lut_size*4 bytes) at
+ * degrees 2..8 are staged in on-chip memory by the matrix-core kernels; larger
+ * tables and other degrees run on the any-degree kernels, which read the table
+ * from global memory.  2 <= lut_size <= CHEBYKAN_MAX_LUT_SIZE, else
+ * CHEBYKAN_ERR_SHAPE.
+ */
+#define CHEBYKAN_MAX_LUT_SIZE (1 << 20)
+chebykan_status chebykan_lut_build(float *lut, int degree, int lut_size);
+chebykan_status chebykan_forward_lut(const float *x, const float *C, const float *lut, int lut_size, float *y,
+                                     int64_t batch, int in, int out, int degree,
+                                     void *workspace, size_t workspace_bytes, chebykan_stream_t stream);
+chebykan_status chebykan_backward_lut(const float *x, const float *C, const float *dy, const float *lut,
+                                      int lut_size, float *dx, float *dC,
+                                      int64_t batch, int in, int out, int degree,
+                                      void *workspace, size_t workspace_bytes, chebykan_stream_t stream);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *chebykan_status_string(chebykan_status status);

@@ -67,6 +67,8 @@ def _load() -> ctypes.CDLL:
         lib.oracle_forward_lut.restype = ctypes.c_int
         lib.oracle_backward_lut.argtypes = [dp, dp, dp, dp, i64, i8p, dp, dp, dp, i64, i64, i64, ctypes.c_int]
         lib.oracle_backward_lut.restype = ctypes.c_int
+        lib.oracle_dC_lut_at.argtypes = [dp, dp, dp, i64, ip, ip, ip, i64, dp, i64, i64, i64, ctypes.c_int]
+        lib.oracle_dC_lut_at.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -253,3 +255,17 @@ def backward_lut(x, C, dy, lut, need_dx: bool = True, need_dC: bool = True, shif
     if rc != 0:
         raise ValueError("oracle_backward_lut failed")
     return (dx, dC, frac) if want_frac else (dx, dC)
+
+
+def dC_lut_at(x, dy, lut, is_, os_, ks) -> np.ndarray:
+    """Sampled dC[i, o, k] of the interpolated layer, one element at a time."""
+    x64, dy64, lut = _f64(x), _f64(dy), _f64(lut)
+    B, I = x64.shape
+    O = dy64.shape[1]
+    is_, os_, ks = _i64(is_), _i64(os_), _i64(ks)
+    out = np.empty(len(is_), dtype=np.float64)
+    rc = _load().oracle_dC_lut_at(_dp(x64), _dp(dy64), _dp(lut), lut.shape[1], _ip(is_), _ip(os_), _ip(ks), len(is_),
+                                  _dp(out), B, I, O, lut.shape[0] - 1)
+    if rc != 0:
+        raise ValueError("oracle_dC_lut_at failed")
+    return out

@@ -148,3 +148,23 @@ int oracle_backward_lut(const double *x, const double *C, const double *dy, cons
     }
     return 0;
 }
+
+/* Sampled coefficient gradients: out[s] = dC[is[s], os[s], ks[s]] of the interpolated layer,
+ * one requested element at a time (for spot checks of full-size results). */
+int oracle_dC_lut_at(const double *x, const double *dy, const double *lut, int64_t n,
+                     const int64_t *is, const int64_t *os, const int64_t *ks, int64_t count, double *out,
+                     int64_t B, int64_t I, int64_t O, int d)
+{
+    if (d < 0 || d > LUT_ORACLE_MAX_DEGREE || n < 2) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t s = 0; s < count; ++s) {
+        double T[LUT_ORACLE_MAX_DEGREE + 1];
+        double acc = 0.0;
+        for (int64_t b = 0; b < B; ++b) {
+            oracle_lut_eval(lut, d, n, tanh(x[b * I + is[s]]), 0, T, NULL, NULL, NULL);
+            acc += T[ks[s]] * dy[b * O + os[s]];
+        }
+        out[s] = acc;
+    }
+    return 0;
+}

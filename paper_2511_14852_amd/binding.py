@@ -26,6 +26,7 @@ EXPORTS = (
     "chebykan_workspace_bytes", "chebykan_forward", "chebykan_backward",
     "chebykan_status_string", "chebykan_set_kernel_family", "chebykan_version",
     "chebykan_calibrate_mfma", "chebykan_calibrate_copy",
+    "chebykan_lut_build", "chebykan_forward_lut", "chebykan_backward_lut",
 )
 
 _lib: Optional[ctypes.CDLL] = None
@@ -61,6 +62,12 @@ def load() -> ctypes.CDLL:
         lib.chebykan_set_kernel_family.restype = ci
         lib.chebykan_version.argtypes = []
         lib.chebykan_version.restype = ci
+        lib.chebykan_lut_build.argtypes = [vp, ci, ci]
+        lib.chebykan_lut_build.restype = ci
+        lib.chebykan_forward_lut.argtypes = [vp, vp, vp, ci, vp, i64, ci, ci, ci, vp, sz, vp]
+        lib.chebykan_forward_lut.restype = ci
+        lib.chebykan_backward_lut.argtypes = [vp, vp, vp, vp, ci, vp, vp, i64, ci, ci, ci, vp, sz, vp]
+        lib.chebykan_backward_lut.restype = ci
         lib.chebykan_calibrate_mfma.argtypes = [vp, ci, ci, ctypes.POINTER(ctypes.c_double), vp]
         lib.chebykan_calibrate_mfma.restype = ci
         lib.chebykan_calibrate_copy.argtypes = [vp, vp, i64, vp]
@@ -184,6 +191,65 @@ def chebykan_backward(x, C, dy, dx, dC, workspace=None, stream=None) -> None:
                       B, I, O, K - 1, ws_ptr, ws_bytes, _stream_ptr(stream))
     if st != CHEBYKAN_OK:
         raise ChebykanError(st, "chebykan_backward")
+
+
+def chebykan_lut_build(degree: int, lut_size: int):
+    """The table of T_0..T_degree on lut_size uniform samples of [-1, 1] as a CPU fp32 tensor [degree+1, lut_size]."""
+    import torch
+    lut = torch.empty((degree + 1, lut_size), dtype=torch.float32)
+    st = int(load().chebykan_lut_build(lut.data_ptr(), int(degree), int(lut_size)))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_lut_build")
+    return lut
+
+
+def _check_lut(lut, K):
+    _check(lut, "lut")
+    if lut.dim() != 2 or lut.shape[0] != K:
+        raise ValueError("lut must be [degree+1, lut_size]")
+    return int(lut.shape[1])
+
+
+def chebykan_forward_lut(x, C, lut, y, workspace=None, stream=None) -> None:
+    """Table-interpolated forward: y = layer(x; C) with the basis read from lut ([degree+1, lut_size], GPU)."""
+    _check(x, "x")
+    B, I = x.shape
+    _check(C, "C")
+    if C.dim() != 3 or C.shape[0] != I:
+        raise ValueError("C must be [in, out, degree+1]")
+    O, K = int(C.shape[1]), int(C.shape[2])
+    n = _check_lut(lut, K)
+    _check(y, "y", (B, O))
+    need = chebykan_workspace_bytes(B, I, O, K - 1, CHEBYKAN_PASS_FORWARD)
+    ws_ptr, ws_bytes = _ws(workspace, need)
+    st = int(load().chebykan_forward_lut(x.data_ptr(), C.data_ptr(), lut.data_ptr(), n, y.data_ptr(), B, I, O, K - 1,
+                                         ws_ptr, ws_bytes, _stream_ptr(stream)))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_forward_lut")
+
+
+def chebykan_backward_lut(x, C, dy, lut, dx, dC, workspace=None, stream=None) -> None:
+    """Table-interpolated backward: dx and/or dC (pass None to skip one)."""
+    _check(x, "x")
+    B, I = x.shape
+    _check(C, "C")
+    if C.dim() != 3 or C.shape[0] != I:
+        raise ValueError("C must be [in, out, degree+1]")
+    O, K = int(C.shape[1]), int(C.shape[2])
+    n = _check_lut(lut, K)
+    _check(dy, "dy", (B, O))
+    if dx is not None:
+        _check(dx, "dx", (B, I))
+    if dC is not None:
+        _check(dC, "dC", (I, O, K))
+    need = chebykan_workspace_bytes(B, I, O, K - 1, CHEBYKAN_PASS_BACKWARD)
+    ws_ptr, ws_bytes = _ws(workspace, need)
+    st = int(load().chebykan_backward_lut(x.data_ptr(), C.data_ptr(), dy.data_ptr(), lut.data_ptr(), n,
+                                          None if dx is None else dx.data_ptr(),
+                                          None if dC is None else dC.data_ptr(),
+                                          B, I, O, K - 1, ws_ptr, ws_bytes, _stream_ptr(stream)))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_backward_lut")
 
 
 def alloc_workspace(batch: int, n_in: int, n_out: int, degree: int, device="cuda"):

@@ -99,4 +99,113 @@ __device__ __forceinline__ void cheb_dT(float u, float (&dT)[D > 0 ? D : 1])
     }
 }
 
+// ---------------------------------------------------------------- basis policies
+// A kernel obtains T_k and T_k' through one of two policies with the same interface.
+//
+// ExactBasis: the recurrences above (the default path).
+//
+// TableBasis: the paper's lookup-table variant (Sec. 4.2).  The caller's table
+// LUT[k][i] = T_k(-1 + i*Delta), Delta = 2/(n-1), is staged once per workgroup into LDS,
+// transposed to [i][K] so that the 2K values of a cell are adjacent.  Online (Sec. 4.2.2):
+// pos = (u+1)/2 (n-1), c = min(floor(pos), n-2), f = pos - c,
+//     T_k  ~ LUT[k][c] + f (LUT[k][c+1] - LUT[k][c])
+//     T_k' ~ (LUT[k][c+1] - LUT[k][c]) / Delta          (difference of neighbouring samples)
+// The paper keeps its table in global memory because it does not fit the on-chip memory of
+// its GPU; 160 KB of LDS per compute unit hold tables of a few thousand samples.
+struct ExactBasis {
+    static constexpr bool kTable = false;
+    struct Args {};
+    __device__ ExactBasis(const Args&, float*, int, int, int) {}
+    template <int D>
+    __device__ __forceinline__ void T(float x, float (&out)[D + 1]) const
+    {
+        cheb_T_of_x<D>(x, out);
+    }
+    // dT[k-1] = T_k', slope = 1 - tanh(x)^2
+    template <int D>
+    __device__ __forceinline__ void dT(float x, float (&out)[D > 0 ? D : 1], float& slope) const
+    {
+        const float u = normalise(x, slope);
+        cheb_dT<D>(u, out);
+    }
+    // both at once; the derivative only where `want_dt` holds
+    template <int D>
+    __device__ __forceinline__ void T_dT(float x, float (&t)[D + 1], float (&dt)[D > 0 ? D : 1], float& slope,
+                                         bool want_dt) const
+    {
+        const float u = normalise(x, slope);
+        if constexpr (D <= 8) cheb_T<D>(u, t);
+        else cheb_T_of_x<D>(x, t);
+        if (want_dt) cheb_dT<D>(u, dt);
+    }
+};
+
+struct TableBasis {
+    static constexpr bool kTable = true;
+    struct Args {
+        const float* lut;   // device, [K][n]
+        int n;              // samples per row
+    };
+    const float* tab;       // LDS, [n][K]
+    float half;             // (n-1)/2
+    float inv_delta;        // (n-1)/2
+    int last;               // n-2
+
+    // Stage the table into LDS at `dst` (n*K floats).  Every thread of the workgroup calls this;
+    // it ends with a barrier.
+    __device__ TableBasis(const Args& a, float* dst, int K, int tid, int nthreads)
+    {
+        const int total = a.n * K;
+        for (int e = tid; e < total; e += nthreads) {
+            const int k = e / a.n, i = e - k * a.n;
+            dst[i * K + k] = a.lut[e];
+        }
+        __syncthreads();
+        tab = dst;
+        half = 0.5f * (float)(a.n - 1);
+        inv_delta = half;
+        last = a.n - 2;
+    }
+
+    // cell base pointer and in-cell fraction for u in [-1, 1]
+    template <int K>
+    __device__ __forceinline__ const float* cell(float u, float& frac) const
+    {
+        const float pos = fmaf(u, half, half);
+        int c = (int)pos;                       // pos >= 0: truncation is the floor
+        c = c < last ? c : last;
+        frac = pos - (float)c;
+        return tab + c * K;
+    }
+    template <int D>
+    __device__ __forceinline__ void T(float x, float (&out)[D + 1]) const
+    {
+        float f;
+        const float* p = cell<D + 1>(normalise(x), f);
+#pragma unroll
+        for (int k = 0; k <= D; ++k) out[k] = fmaf(f, p[D + 1 + k] - p[k], p[k]);
+    }
+    template <int D>
+    __device__ __forceinline__ void dT(float x, float (&out)[D > 0 ? D : 1], float& slope) const
+    {
+        float f;
+        const float* p = cell<D + 1>(normalise(x, slope), f);
+#pragma unroll
+        for (int k = 1; k <= D; ++k) out[k - 1] = (p[D + 1 + k] - p[k]) * inv_delta;
+    }
+    template <int D>
+    __device__ __forceinline__ void T_dT(float x, float (&t)[D + 1], float (&dt)[D > 0 ? D : 1], float& slope,
+                                         bool) const
+    {
+        float f;
+        const float* p = cell<D + 1>(normalise(x, slope), f);
+#pragma unroll
+        for (int k = 0; k <= D; ++k) {
+            const float lo = p[k], diff = p[D + 1 + k] - lo;
+            t[k] = fmaf(f, diff, lo);
+            if (k >= 1) dt[k - 1] = diff * inv_delta;
+        }
+    }
+};
+
 }  // namespace chebykan

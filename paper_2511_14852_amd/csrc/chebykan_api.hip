@@ -68,6 +68,28 @@ static void generic_dC(const float* x, const float* dy, float* dC, int64_t B, in
                        O, d);
 }
 
+static void generic_forward_table(const float* x, const float* C, const float* lut, int n, float* y, int64_t B,
+                                  int I, int O, int d, hipStream_t s)
+{
+    dim3 block(64, 4), grid((unsigned)((B + 3) / 4), (unsigned)((O + 63) / 64));
+    hipLaunchKernelGGL(generic_forward_table_kernel, grid, block, 0, s, x, C, lut, n, y, B, I, O, d);
+}
+
+static void generic_dx_table(const float* x, const float* C, const float* dy, const float* lut, int n, float* dx,
+                             int64_t B, int I, int O, int d, hipStream_t s)
+{
+    dim3 block(64, 4), grid((unsigned)((B + 3) / 4), (unsigned)((I + 63) / 64));
+    hipLaunchKernelGGL(generic_dx_table_kernel, grid, block, 0, s, x, C, dy, lut, n, dx, B, I, O, d);
+}
+
+static void generic_dC_table(const float* x, const float* dy, const float* lut, int n, float* dC, int64_t B, int I,
+                             int O, int d, hipStream_t s)
+{
+    const int64_t cnt = (int64_t)I * O * (d + 1);
+    hipLaunchKernelGGL(generic_dC_table_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, x, dy, lut, n,
+                       dC, B, I, O, d);
+}
+
 }  // namespace chebykan
 
 using namespace chebykan;
@@ -140,6 +162,71 @@ chebykan_status chebykan_backward(const float* x, const float* C, const float* d
     if (dx && batch > 0) generic_dx(x, C, dy, dx, batch, in, out, degree, s);
     // batch == 0 still defines dC (all zeros): the generic kernel's empty sum gives that.
     if (dC) generic_dC(x, dy, dC, batch, in, out, degree, s);
+    return launch_status();
+}
+
+chebykan_status chebykan_lut_build(float* lut, int degree, int lut_size)
+{
+    if (!lut) return CHEBYKAN_ERR_NULL;
+    if (degree < 0 || degree > CHEBYKAN_MAX_DEGREE || lut_size < 2 || lut_size > CHEBYKAN_MAX_LUT_SIZE)
+        return CHEBYKAN_ERR_SHAPE;
+    // Samples of T_0..T_degree on the uniform grid, recurrence in double, rounded once to fp32.
+    const double step = 2.0 / (double)(lut_size - 1);
+    for (int i = 0; i < lut_size; ++i) {
+        const double xi = i == lut_size - 1 ? 1.0 : (double)i * step - 1.0;
+        double below = 1.0, here = xi;   // T_{k-1}, T_k
+        lut[i] = 1.0f;
+        if (degree >= 1) lut[(size_t)lut_size + i] = (float)xi;
+        for (int k = 2; k <= degree; ++k) {
+            const double above = 2.0 * xi * here - below;
+            lut[(size_t)k * lut_size + i] = (float)above;
+            below = here;
+            here = above;
+        }
+    }
+    return CHEBYKAN_OK;
+}
+
+chebykan_status chebykan_forward_lut(const float* x, const float* C, const float* lut, int lut_size, float* y,
+                                     int64_t batch, int in, int out, int degree, void* workspace,
+                                     size_t workspace_bytes, chebykan_stream_t stream)
+{
+    if (!C || !lut || (batch != 0 && (!x || !y))) return CHEBYKAN_ERR_NULL;
+    if (!shape_ok(batch, in, out, degree) || lut_size < 2 || lut_size > CHEBYKAN_MAX_LUT_SIZE)
+        return CHEBYKAN_ERR_SHAPE;
+    const size_t need = forward_workspace_bytes(batch, in, out, degree);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
+    const chebykan_status dev = check_device();
+    if (dev != CHEBYKAN_OK) return dev;
+    if (batch == 0) return CHEBYKAN_OK;
+    hipStream_t s = (hipStream_t)stream;
+    (void)hipGetLastError();
+    if (g_family != 1 && fast_forward_table(x, C, lut, lut_size, y, batch, in, out, degree, workspace, s))
+        return launch_status();
+    generic_forward_table(x, C, lut, lut_size, y, batch, in, out, degree, s);
+    return launch_status();
+}
+
+chebykan_status chebykan_backward_lut(const float* x, const float* C, const float* dy, const float* lut,
+                                      int lut_size, float* dx, float* dC, int64_t batch, int in, int out,
+                                      int degree, void* workspace, size_t workspace_bytes,
+                                      chebykan_stream_t stream)
+{
+    if (!C || !lut || (batch != 0 && (!x || !dy))) return CHEBYKAN_ERR_NULL;
+    if (!dx && !dC && batch != 0) return CHEBYKAN_ERR_NULL;
+    if (!shape_ok(batch, in, out, degree) || lut_size < 2 || lut_size > CHEBYKAN_MAX_LUT_SIZE)
+        return CHEBYKAN_ERR_SHAPE;
+    const size_t need = backward_workspace_bytes(batch, in, out, degree);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
+    const chebykan_status dev = check_device();
+    if (dev != CHEBYKAN_OK) return dev;
+    hipStream_t s = (hipStream_t)stream;
+    (void)hipGetLastError();
+    if (g_family != 1 && batch > 0 &&
+        fast_backward_table(x, C, dy, lut, lut_size, dx, dC, batch, in, out, degree, workspace, s))
+        return launch_status();
+    if (dx && batch > 0) generic_dx_table(x, C, dy, lut, lut_size, dx, batch, in, out, degree, s);
+    if (dC) generic_dC_table(x, dy, lut, lut_size, dC, batch, in, out, degree, s);
     return launch_status();
 }
 

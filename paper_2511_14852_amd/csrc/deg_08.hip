@@ -2,7 +2,13 @@
 #include "degree_impl.h"
 
 namespace chebykan {
-template void degree_forward<8>(const float*, const float*, float*, int, int, int, void*, hipStream_t);
-template void degree_backward<8>(const float*, const float*, const float*, float*, float*, int, int, int, void*,
-                                  hipStream_t);
+template void degree_forward<8, ExactBasis>(const float*, const float*, float*, int, int, int, void*,
+                                            const ExactBasis::Args&, hipStream_t);
+template void degree_backward<8, ExactBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
+                                             void*, const ExactBasis::Args&, hipStream_t);
+// the table-interpolated variant (paper Sec. 4.2) of the same kernels
+template void degree_forward<8, TableBasis>(const float*, const float*, float*, int, int, int, void*,
+                                            const TableBasis::Args&, hipStream_t);
+template void degree_backward<8, TableBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
+                                             void*, const TableBasis::Args&, hipStream_t);
 }  // namespace chebykan

@@ -2,7 +2,8 @@
 #include "degree_impl.h"
 
 namespace chebykan {
-template void degree_forward<15>(const float*, const float*, float*, int, int, int, void*, hipStream_t);
-template void degree_backward<15>(const float*, const float*, const float*, float*, float*, int, int, int, void*,
-                                  hipStream_t);
+template void degree_forward<15, ExactBasis>(const float*, const float*, float*, int, int, int, void*,
+                                            const ExactBasis::Args&, hipStream_t);
+template void degree_backward<15, ExactBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
+                                             void*, const ExactBasis::Args&, hipStream_t);
 }  // namespace chebykan

@@ -18,6 +18,17 @@ void allow_lds(KernelT kernel, int bytes)
                               bytes);
 }
 
+// A workgroup may use the whole 160 KiB of a compute unit when a basis table rides along.
+constexpr int MAX_LDS_BYTES = 160 * 1024;
+
+// LDS bytes the basis policy adds to a kernel's own tiles (the staged table; 0 for the recurrences).
+template <class Basis>
+inline size_t basis_lds_bytes(const typename Basis::Args& ba, int K)
+{
+    if constexpr (Basis::kTable) return (size_t)ba.n * K * sizeof(float);
+    else { (void)ba; (void)K; return 0; }
+}
+
 // Many slices of a small tensor (coefficient gradients of narrow layers): 32 slice groups.
 // Few slices of a large tensor (split forward): 4 groups, 64 consecutive elements per block.
 inline void launch_sum_slices(const float* partial, float* out, int64_t n, int slices, hipStream_t s)
@@ -31,72 +42,73 @@ inline void launch_sum_slices(const float* partial, float* out, int64_t n, int s
 }
 
 // ------------------------------------------------------------------ forward
-template <int D, int BN, int VEC>
-void launch_fwd(const float* x, const float* C, float* y, float* partial, int B, int I, int O, hipStream_t s)
+template <int D, int BN, int VEC, class Basis>
+void launch_fwd(const float* x, const float* C, float* y, float* partial, int B, int I, int O, const typename Basis::Args& ba, hipStream_t s)
 {
     using Cfg = FwdCfg<D, BN, forward_chunk_features(D), VEC>;
-    static bool once = (allow_lds(fwd_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
+    static bool once = (allow_lds(fwd_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES), true);
     (void)once;
     const FwdPlan p = plan_forward(B, I, O, D);
     const int tiles_o = (O + BN - 1) / BN;
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * tiles_o;
     float* out = p.splits > 1 ? partial : y;
-    hipLaunchKernelGGL(fwd_mfma_kernel<Cfg>, dim3((unsigned)tiles, (unsigned)p.splits), dim3(MFMA_THREADS),
-                       Cfg::LDS_BYTES, s, x, C, out, B, I, O, tiles_o, p.chunks_per_split);
+    hipLaunchKernelGGL((fwd_mfma_kernel<Cfg, Basis>), dim3((unsigned)tiles, (unsigned)p.splits), dim3(MFMA_THREADS),
+                       Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, out, B, I, O, tiles_o,
+                       p.chunks_per_split, ba);
     if (p.splits > 1) launch_sum_slices(partial, y, (int64_t)B * O, p.splits, s);
 }
 
-template <int D>
-void pick_fwd(const float* x, const float* C, float* y, float* partial, int B, int I, int O, hipStream_t s)
+template <int D, class Basis>
+void pick_fwd(const float* x, const float* C, float* y, float* partial, int B, int I, int O, const typename Basis::Args& ba, hipStream_t s)
 {
     const bool vec = aligned16(C) && ((int64_t)O * (D + 1)) % 4 == 0;
     if (O <= 64) {
-        if (vec) launch_fwd<D, 64, 4>(x, C, y, partial, B, I, O, s);
-        else launch_fwd<D, 64, 1>(x, C, y, partial, B, I, O, s);
+        if (vec) launch_fwd<D, 64, 4, Basis>(x, C, y, partial, B, I, O, ba, s);
+        else launch_fwd<D, 64, 1, Basis>(x, C, y, partial, B, I, O, ba, s);
     } else {
-        if (vec) launch_fwd<D, 128, 4>(x, C, y, partial, B, I, O, s);
-        else launch_fwd<D, 128, 1>(x, C, y, partial, B, I, O, s);
+        if (vec) launch_fwd<D, 128, 4, Basis>(x, C, y, partial, B, I, O, ba, s);
+        else launch_fwd<D, 128, 1, Basis>(x, C, y, partial, B, I, O, ba, s);
     }
 }
 
 // --------------------------------------------------------------------- dC
-template <int D, int BN, int VEC, int BIC>
+template <int D, int BN, int VEC, int BIC, class Basis>
 void launch_dC(const float* x, const float* dy, float* partial, int B, int I, int O, const DcPlan& p,
-               hipStream_t s)
+               const typename Basis::Args& ba, hipStream_t s)
 {
     using Cfg = DcCfg<D, BN, VEC, BIC>;
-    static bool once = (allow_lds(dC_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
+    static bool once = (allow_lds(dC_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES), true);
     (void)once;
     const int tiles_o = (O + BN - 1) / BN;
     const int tiles_i = (I + Cfg::BIC - 1) / Cfg::BIC;
-    hipLaunchKernelGGL(dC_mfma_kernel<Cfg>, dim3((unsigned)((int64_t)tiles_i * tiles_o * p.slices)),
-                       dim3(MFMA_THREADS), Cfg::LDS_BYTES, s, x, dy, partial, B, I, O, tiles_o, tiles_i, p.slices,
-                       p.rows_per_slice);
+    hipLaunchKernelGGL((dC_mfma_kernel<Cfg, Basis>), dim3((unsigned)((int64_t)tiles_i * tiles_o * p.slices)),
+                       dim3(MFMA_THREADS), Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, dy, partial, B, I, O,
+                       tiles_o, tiles_i, p.slices, p.rows_per_slice, ba);
 }
 
-template <int D, int BIC>
+template <int D, int BIC, class Basis>
 void pick_dC_tile(const float* x, const float* dy, float* partial, int B, int I, int O, const DcPlan& p,
-                  hipStream_t s)
+                  const typename Basis::Args& ba, hipStream_t s)
 {
     const bool vec = aligned16(dy) && O % 4 == 0;
     if (p.bn == 64) {
-        if (vec) launch_dC<D, 64, 4, BIC>(x, dy, partial, B, I, O, p, s);
-        else launch_dC<D, 64, 1, BIC>(x, dy, partial, B, I, O, p, s);
+        if (vec) launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, B, I, O, p, ba, s);
+        else launch_dC<D, 64, 1, BIC, Basis>(x, dy, partial, B, I, O, p, ba, s);
     } else {
-        if (vec) launch_dC<D, 128, 4, BIC>(x, dy, partial, B, I, O, p, s);
-        else launch_dC<D, 128, 1, BIC>(x, dy, partial, B, I, O, p, s);
+        if (vec) launch_dC<D, 128, 4, BIC, Basis>(x, dy, partial, B, I, O, p, ba, s);
+        else launch_dC<D, 128, 1, BIC, Basis>(x, dy, partial, B, I, O, p, ba, s);
     }
 }
 
-template <int D>
+template <int D, class Basis>
 void pick_dC(const float* x, const float* dy, float* dC, float* partial, int B, int I, int O, const DcPlan& p,
-             hipStream_t s)
+             const typename Basis::Args& ba, hipStream_t s)
 {
     if constexpr (D == 6) {
-        if (dc_tile_features_for(I, D) == 16) pick_dC_tile<D, 16>(x, dy, partial, B, I, O, p, s);
-        else pick_dC_tile<D, dc_tile_features(D)>(x, dy, partial, B, I, O, p, s);
+        if (dc_tile_features_for(I, D) == 16) pick_dC_tile<D, 16, Basis>(x, dy, partial, B, I, O, p, ba, s);
+        else pick_dC_tile<D, dc_tile_features(D), Basis>(x, dy, partial, B, I, O, p, ba, s);
     } else {
-        pick_dC_tile<D, dc_tile_features(D)>(x, dy, partial, B, I, O, p, s);
+        pick_dC_tile<D, dc_tile_features(D), Basis>(x, dy, partial, B, I, O, p, ba, s);
     }
     const dim3 grid((unsigned)((O + 31) / 32), (unsigned)I);
     static bool once = (allow_lds(dC_combine_kernel<D, 32>, 1024 * ((D + 1) | 1) * (int)sizeof(float)), true);
@@ -110,130 +122,136 @@ void pick_dC(const float* x, const float* dy, float* dC, float* partial, int B, 
 }
 
 // --------------------------------------------------------------------- dx
-template <int D, int NB, int VEC>
+template <int D, int NB, int VEC, class Basis>
 void launch_dx(const float* x, const float* C, const float* dy, float* dx, float* partial, int B, int I, int O,
-               const DxPlan& p, hipStream_t s)
+               const DxPlan& p, const typename Basis::Args& ba, hipStream_t s)
 {
     using Cfg = DxCfg<D, NB, VEC>;
-    static bool once = (allow_lds(dx_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
+    static bool once = (allow_lds(dx_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES), true);
     (void)once;
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * p.feature_tiles;
-    hipLaunchKernelGGL(dx_mfma_kernel<Cfg>, dim3((unsigned)tiles, (unsigned)p.split.splits), dim3(MFMA_THREADS),
-                       Cfg::LDS_BYTES, s, x, C, dy, p.split.splits > 1 ? partial : dx, B, I, O, p.feature_tiles,
-                       p.split.chunks_per_split);
+    hipLaunchKernelGGL((dx_mfma_kernel<Cfg, Basis>), dim3((unsigned)tiles, (unsigned)p.split.splits), dim3(MFMA_THREADS),
+                       Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy,
+                       p.split.splits > 1 ? partial : dx, B, I, O, p.feature_tiles, p.split.chunks_per_split, ba);
 }
 
-template <int D, int VEC>
+template <int D, int VEC, class Basis>
 void launch_dx2(const float* x, const float* C, const float* dy, float* dx, float* partial, int B, int I, int O,
-                const DxPlan& p, hipStream_t s)
+                const DxPlan& p, const typename Basis::Args& ba, hipStream_t s)
 {
     using Cfg = Dx2Cfg<D, VEC>;
     static_assert(Cfg::BO == (D <= 4 ? 32 : 16), "plan_dx assumes this chunk width");
-    static bool once = (allow_lds(dx2_mfma_kernel<Cfg>, Cfg::LDS_BYTES), true);
+    static bool once = (allow_lds(dx2_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES), true);
     (void)once;
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * p.feature_tiles;
-    hipLaunchKernelGGL(dx2_mfma_kernel<Cfg>, dim3((unsigned)tiles, (unsigned)p.split.splits), dim3(MFMA_THREADS),
-                       Cfg::LDS_BYTES, s, x, C, dy, p.split.splits > 1 ? partial : dx, B, I, O, p.feature_tiles,
-                       p.split.chunks_per_split);
+    hipLaunchKernelGGL((dx2_mfma_kernel<Cfg, Basis>), dim3((unsigned)tiles, (unsigned)p.split.splits), dim3(MFMA_THREADS),
+                       Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy,
+                       p.split.splits > 1 ? partial : dx, B, I, O, p.feature_tiles, p.split.chunks_per_split, ba);
 }
 
-template <int D>
+template <int D, class Basis>
 void pick_dx(const float* x, const float* C, const float* dy, float* dx, float* partial, int B, int I, int O,
-             hipStream_t s)
+             const typename Basis::Args& ba, hipStream_t s)
 {
     const bool vec = aligned16(C) && aligned16(dy) && O % 4 == 0;   // O%4==0 makes every slab run 16-byte aligned
     const DxPlan p = plan_dx(B, I, O, D);
     bool done = false;
     if constexpr (D <= 6) {   // the feature-per-lane kernel exists for these degrees only
         if (p.per_lane) {
-            if (vec) launch_dx2<D, 4>(x, C, dy, dx, partial, B, I, O, p, s);
-            else launch_dx2<D, 1>(x, C, dy, dx, partial, B, I, O, p, s);
+            if (vec) launch_dx2<D, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s);
+            else launch_dx2<D, 1, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s);
             done = true;
         }
     }
     if (!done) {
         switch (p.nb * 2 + (vec ? 1 : 0)) {
-            case 2: launch_dx<D, 1, 1>(x, C, dy, dx, partial, B, I, O, p, s); break;
-            case 3: launch_dx<D, 1, 4>(x, C, dy, dx, partial, B, I, O, p, s); break;
-            case 4: launch_dx<D, 2, 1>(x, C, dy, dx, partial, B, I, O, p, s); break;
-            case 5: launch_dx<D, 2, 4>(x, C, dy, dx, partial, B, I, O, p, s); break;
-            case 6: launch_dx<D, 3, 1>(x, C, dy, dx, partial, B, I, O, p, s); break;
-            case 7: launch_dx<D, 3, 4>(x, C, dy, dx, partial, B, I, O, p, s); break;
-            case 8: launch_dx<D, 4, 1>(x, C, dy, dx, partial, B, I, O, p, s); break;
-            default: launch_dx<D, 4, 4>(x, C, dy, dx, partial, B, I, O, p, s); break;
+            case 2: launch_dx<D, 1, 1, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
+            case 3: launch_dx<D, 1, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
+            case 4: launch_dx<D, 2, 1, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
+            case 5: launch_dx<D, 2, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
+            case 6: launch_dx<D, 3, 1, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
+            case 7: launch_dx<D, 3, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
+            case 8: launch_dx<D, 4, 1, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
+            default: launch_dx<D, 4, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
         }
     }
     if (p.split.splits > 1) launch_sum_slices(partial, dx, (int64_t)B * I, p.split.splits, s);
 }
 
 // ------------------------------------------------------------ narrow layers
-template <int D, int O>
-void launch_narrow_fwd(const float* x, const float* C, float* y, int B, int I, hipStream_t s)
+template <int D, int O, class Basis>
+void launch_narrow_fwd(const float* x, const float* C, float* y, int B, int I, const typename Basis::Args& ba, hipStream_t s)
 {
     const NarrowPlan p = plan_narrow(B, I, NARROW_FWD_WGS);
-    hipLaunchKernelGGL((narrow_fwd_kernel<D, O>), dim3((unsigned)p.slices), dim3(NARROW_THREADS),
-                       (size_t)I * O * (D + 1) * sizeof(float), s, x, C, y, B, I, p.G, p.rows_per_wg);
+    static bool once = (allow_lds(narrow_fwd_kernel<D, O, Basis>, MAX_LDS_BYTES), true);
+    (void)once;
+    hipLaunchKernelGGL((narrow_fwd_kernel<D, O, Basis>), dim3((unsigned)p.slices), dim3(NARROW_THREADS),
+                       narrow_fwd_lds_floats(I, O, D + 1) * sizeof(float) + basis_lds_bytes<Basis>(ba, D + 1), s, x, C,
+                       y, B, I, p.G, p.rows_per_wg, ba);
 }
 
-template <int D, int O>
+template <int D, int O, class Basis>
 void launch_narrow_bwd(const float* x, const float* C, const float* dy, float* dx, float* dC, float* partial,
-                       int B, int I, hipStream_t s)
+                       int B, int I, const typename Basis::Args& ba, hipStream_t s)
 {
     const NarrowPlan p = plan_narrow(B, I, NARROW_BWD_WGS);
     const int blocks_i = (I + p.G - 1) / p.G;
-    hipLaunchKernelGGL((narrow_bwd_kernel<D, O>), dim3((unsigned)p.slices, (unsigned)blocks_i),
-                       dim3(NARROW_THREADS), (size_t)NARROW_THREADS * O * (D + 1) * sizeof(float), s, x, C, dy,
-                       dx, dC ? partial : nullptr, B, I, p.G, p.rows_per_wg);
+    static bool once = (allow_lds(narrow_bwd_kernel<D, O, Basis>, MAX_LDS_BYTES), true);
+    (void)once;
+    hipLaunchKernelGGL((narrow_bwd_kernel<D, O, Basis>), dim3((unsigned)p.slices, (unsigned)blocks_i),
+                       dim3(NARROW_THREADS),
+                       narrow_bwd_lds_floats(O, D + 1) * sizeof(float) + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy,
+                       dx, dC ? partial : nullptr, B, I, p.G, p.rows_per_wg, ba);
     if (dC) {
         launch_sum_slices(partial, dC, (int64_t)I * O * (D + 1), p.slices, s);
     }
 }
 
-template <int D>
-void narrow_fwd_by_out(const float* x, const float* C, float* y, int B, int I, int O, hipStream_t s)
+template <int D, class Basis>
+void narrow_fwd_by_out(const float* x, const float* C, float* y, int B, int I, int O, const typename Basis::Args& ba, hipStream_t s)
 {
     switch (O) {
-        case 1: launch_narrow_fwd<D, 1>(x, C, y, B, I, s); break;
-        case 2: launch_narrow_fwd<D, 2>(x, C, y, B, I, s); break;
-        case 3: launch_narrow_fwd<D, 3>(x, C, y, B, I, s); break;
-        default: launch_narrow_fwd<D, 4>(x, C, y, B, I, s); break;
+        case 1: launch_narrow_fwd<D, 1, Basis>(x, C, y, B, I, ba, s); break;
+        case 2: launch_narrow_fwd<D, 2, Basis>(x, C, y, B, I, ba, s); break;
+        case 3: launch_narrow_fwd<D, 3, Basis>(x, C, y, B, I, ba, s); break;
+        default: launch_narrow_fwd<D, 4, Basis>(x, C, y, B, I, ba, s); break;
     }
 }
 
-template <int D>
+template <int D, class Basis>
 void narrow_bwd_by_out(const float* x, const float* C, const float* dy, float* dx, float* dC, float* partial, int B,
-                       int I, int O, hipStream_t s)
+                       int I, int O, const typename Basis::Args& ba, hipStream_t s)
 {
     switch (O) {
-        case 1: launch_narrow_bwd<D, 1>(x, C, dy, dx, dC, partial, B, I, s); break;
-        case 2: launch_narrow_bwd<D, 2>(x, C, dy, dx, dC, partial, B, I, s); break;
-        case 3: launch_narrow_bwd<D, 3>(x, C, dy, dx, dC, partial, B, I, s); break;
-        default: launch_narrow_bwd<D, 4>(x, C, dy, dx, dC, partial, B, I, s); break;
+        case 1: launch_narrow_bwd<D, 1, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s); break;
+        case 2: launch_narrow_bwd<D, 2, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s); break;
+        case 3: launch_narrow_bwd<D, 3, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s); break;
+        default: launch_narrow_bwd<D, 4, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s); break;
     }
 }
 
 // ------------------------------------------------------- per-degree entry points
 // `ws` is the caller's workspace (partial outputs of a split forward contraction; partial
 // coefficient gradients of the batch slices).
-template <int D>
-void degree_forward(const float* x, const float* C, float* y, int B, int I, int O, void* ws, hipStream_t s)
+template <int D, class Basis>
+void degree_forward(const float* x, const float* C, float* y, int B, int I, int O, void* ws, const typename Basis::Args& ba, hipStream_t s)
 {
-    if (use_narrow(B, I, O, D)) narrow_fwd_by_out<D>(x, C, y, B, I, O, s);
-    else pick_fwd<D>(x, C, y, static_cast<float*>(ws), B, I, O, s);
+    if (use_narrow(B, I, O, D)) narrow_fwd_by_out<D, Basis>(x, C, y, B, I, O, ba, s);
+    else pick_fwd<D, Basis>(x, C, y, static_cast<float*>(ws), B, I, O, ba, s);
 }
 
-template <int D>
+template <int D, class Basis>
 void degree_backward(const float* x, const float* C, const float* dy, float* dx, float* dC, int B, int I, int O,
-                     void* ws, hipStream_t s)
+                     void* ws, const typename Basis::Args& ba, hipStream_t s)
 {
     float* partial = static_cast<float*>(ws);
     if (use_narrow(B, I, O, D)) {
-        narrow_bwd_by_out<D>(x, C, dy, dx, dC, partial, B, I, O, s);
+        narrow_bwd_by_out<D, Basis>(x, C, dy, dx, dC, partial, B, I, O, ba, s);
         return;
     }
     // the dx partials are summed before the dC kernel reuses the workspace (same stream)
-    if (dx) pick_dx<D>(x, C, dy, dx, partial, B, I, O, s);
-    if (dC) pick_dC<D>(x, dy, dC, partial, B, I, O, plan_dC(B, I, O, D), s);
+    if (dx) pick_dx<D, Basis>(x, C, dy, dx, partial, B, I, O, ba, s);
+    if (dC) pick_dC<D, Basis>(x, dy, dC, partial, B, I, O, plan_dC(B, I, O, D), ba, s);
 }
 
 }  // namespace chebykan

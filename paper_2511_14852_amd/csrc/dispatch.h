@@ -19,4 +19,11 @@ bool fast_forward(const float* x, const float* C, float* y, int64_t B, int I, in
 bool fast_backward(const float* x, const float* C, const float* dy, float* dx, float* dC, int64_t B, int I,
                    int O, int d, void* ws, hipStream_t s);
 
+// Table-interpolated variant; lut is a device pointer to [d+1][n] samples.  False when the degree
+// has no table kernels or the table does not fit beside the tiles in LDS.
+bool fast_forward_table(const float* x, const float* C, const float* lut, int n, float* y, int64_t B, int I, int O,
+                        int d, void* ws, hipStream_t s);
+bool fast_backward_table(const float* x, const float* C, const float* dy, const float* lut, int n, float* dx,
+                         float* dC, int64_t B, int I, int O, int d, void* ws, hipStream_t s);
+
 }  // namespace chebykan

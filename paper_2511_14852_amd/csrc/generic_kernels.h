@@ -111,4 +111,92 @@ generic_dC_kernel(const float* __restrict__ x, const float* __restrict__ dy, flo
     dC[e] = total + (mid + part);
 }
 
+// ------------------------------------------------------------------------------------------
+// Table-interpolated variant (paper Sec. 4.2) for any degree and any table size: the table
+// LUT[k][i] stays in global memory (it is read through the caches), one thread per output
+// element as above.  cell index c = min(floor((u+1)/2 (n-1)), n-2), fraction f = pos - c.
+__device__ __forceinline__ int table_cell(float u, int n, float& f)
+{
+    const float half = 0.5f * (float)(n - 1);
+    const float pos = fmaf(u, half, half);
+    int c = (int)pos;
+    c = c < n - 2 ? c : n - 2;
+    f = pos - (float)c;
+    return c;
+}
+
+__global__ void __launch_bounds__(256)
+generic_forward_table_kernel(const float* __restrict__ x, const float* __restrict__ C,
+                             const float* __restrict__ lut, int n, float* __restrict__ y, int64_t B, int I, int O,
+                             int degree)
+{
+    const int o = blockIdx.y * 64 + threadIdx.x;
+    const int64_t b = (int64_t)blockIdx.x * 4 + threadIdx.y;
+    if (o >= O || b >= B) return;
+    const int K = degree + 1;
+    const float* xr = x + b * I;
+    float total = 0.0f, part = 0.0f;
+    for (int i = 0; i < I; ++i) {
+        float f;
+        const int c = table_cell(normalise(xr[i]), n, f);
+        const float* cf = C + ((int64_t)i * O + o) * K;
+        float acc = 0.0f;
+        for (int k = 0; k < K; ++k) {
+            const float lo = lut[(int64_t)k * n + c], hi = lut[(int64_t)k * n + c + 1];
+            acc = fmaf(cf[k], fmaf(f, hi - lo, lo), acc);
+        }
+        part += acc;
+        if ((i % GENERIC_FOLD) == GENERIC_FOLD - 1) { total += part; part = 0.0f; }
+    }
+    y[b * O + o] = total + part;
+}
+
+__global__ void __launch_bounds__(256)
+generic_dx_table_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
+                        const float* __restrict__ lut, int n, float* __restrict__ dx, int64_t B, int I, int O,
+                        int degree)
+{
+    const int i = blockIdx.y * 64 + threadIdx.x;
+    const int64_t b = (int64_t)blockIdx.x * 4 + threadIdx.y;
+    if (i >= I || b >= B) return;
+    const int K = degree + 1;
+    float slope, f;
+    const int c = table_cell(normalise(x[b * I + i], slope), n, f);
+    const float inv_delta = 0.5f * (float)(n - 1);
+    const float* g = dy + b * O;
+    float total = 0.0f, part = 0.0f;
+    for (int o = 0; o < O; ++o) {
+        const float* cf = C + ((int64_t)i * O + o) * K;
+        float inner = 0.0f;
+        for (int k = 1; k < K; ++k)
+            inner = fmaf(cf[k], (lut[(int64_t)k * n + c + 1] - lut[(int64_t)k * n + c]) * inv_delta, inner);
+        part = fmaf(g[o], inner, part);
+        if ((o % GENERIC_FOLD) == GENERIC_FOLD - 1) { total += part; part = 0.0f; }
+    }
+    dx[b * I + i] = slope * (total + part);
+}
+
+__global__ void __launch_bounds__(256)
+generic_dC_table_kernel(const float* __restrict__ x, const float* __restrict__ dy, const float* __restrict__ lut,
+                        int n, float* __restrict__ dC, int64_t B, int I, int O, int degree)
+{
+    const int K = degree + 1;
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (int64_t)I * O * K) return;
+    const int k = (int)(e % K);
+    const int o = (int)((e / K) % O);
+    const int i = (int)(e / ((int64_t)K * O));
+    const float* row = lut + (int64_t)k * n;
+    float total = 0.0f, mid = 0.0f, part = 0.0f;
+    for (int64_t b = 0; b < B; ++b) {
+        float f;
+        const int c = table_cell(normalise(x[b * I + i]), n, f);
+        const float lo = row[c];
+        part = fmaf(fmaf(f, row[c + 1] - lo, lo), dy[b * O + o], part);
+        if ((b % 64) == 63) { mid += part; part = 0.0f; }
+        if ((b % 4096) == 4095) { total += mid; mid = 0.0f; }
+    }
+    dC[e] = total + (mid + part);
+}
+
 }  // namespace chebykan

@@ -2,23 +2,33 @@
 // runtime degree to the per-degree entry points (each compiled in its own deg_NN.hip).
 #include <hip/hip_runtime.h>
 
+#include "basis.h"
 #include "dispatch.h"
 #include "plans.h"
 
 namespace chebykan {
 
-template <int D>
-void degree_forward(const float* x, const float* C, float* y, int B, int I, int O, void* ws, hipStream_t s);
-template <int D>
+template <int D, class Basis>
+void degree_forward(const float* x, const float* C, float* y, int B, int I, int O, void* ws,
+                    const typename Basis::Args& ba, hipStream_t s);
+template <int D, class Basis>
 void degree_backward(const float* x, const float* C, const float* dy, float* dx, float* dC, int B, int I, int O,
-                     void* ws, hipStream_t s);
+                     void* ws, const typename Basis::Args& ba, hipStream_t s);
 
-#define CHEBYKAN_DECLARE_DEGREE(n)                                                                              \
-    extern template void degree_forward<n>(const float*, const float*, float*, int, int, int, void*, hipStream_t); \
-    extern template void degree_backward<n>(const float*, const float*, const float*, float*, float*, int, int,   \
-                                            int, void*, hipStream_t);
+#define CHEBYKAN_DECLARE_DEGREE(n)                                                                               \
+    extern template void degree_forward<n, ExactBasis>(const float*, const float*, float*, int, int, int, void*,  \
+                                                       const ExactBasis::Args&, hipStream_t);                     \
+    extern template void degree_backward<n, ExactBasis>(const float*, const float*, const float*, float*, float*, \
+                                                        int, int, int, void*, const ExactBasis::Args&, hipStream_t);
 CHEBYKAN_FOR_EACH_DEGREE(CHEBYKAN_DECLARE_DEGREE)
 #undef CHEBYKAN_DECLARE_DEGREE
+#define CHEBYKAN_DECLARE_TABLE_DEGREE(n)                                                                          \
+    extern template void degree_forward<n, TableBasis>(const float*, const float*, float*, int, int, int, void*,  \
+                                                       const TableBasis::Args&, hipStream_t);                     \
+    extern template void degree_backward<n, TableBasis>(const float*, const float*, const float*, float*, float*, \
+                                                        int, int, int, void*, const TableBasis::Args&, hipStream_t);
+CHEBYKAN_FOR_EACH_TABLE_DEGREE(CHEBYKAN_DECLARE_TABLE_DEGREE)
+#undef CHEBYKAN_DECLARE_TABLE_DEGREE
 
 size_t forward_workspace_bytes(int64_t B, int I, int O, int d)
 {
@@ -43,7 +53,7 @@ bool fast_forward(const float* x, const float* C, float* y, int64_t B, int I, in
     if (!shape_fits(B, I, O, d)) return false;
     if (forward_workspace_bytes(B, I, O, d) > 0 && !ws) return false;
     switch (d) {
-#define CHEBYKAN_FORWARD_CASE(n) case n: degree_forward<n>(x, C, y, (int)B, I, O, ws, s); return true;
+#define CHEBYKAN_FORWARD_CASE(n) case n: degree_forward<n, ExactBasis>(x, C, y, (int)B, I, O, ws, ExactBasis::Args{}, s); return true;
         CHEBYKAN_FOR_EACH_DEGREE(CHEBYKAN_FORWARD_CASE)
 #undef CHEBYKAN_FORWARD_CASE
     }
@@ -55,8 +65,43 @@ bool fast_backward(const float* x, const float* C, const float* dy, float* dx, f
 {
     if (!shape_fits(B, I, O, d) || (backward_workspace_bytes(B, I, O, d) > 0 && !ws)) return false;
     switch (d) {
-#define CHEBYKAN_BACKWARD_CASE(n) case n: degree_backward<n>(x, C, dy, dx, dC, (int)B, I, O, ws, s); return true;
+#define CHEBYKAN_BACKWARD_CASE(n) case n: degree_backward<n, ExactBasis>(x, C, dy, dx, dC, (int)B, I, O, ws, ExactBasis::Args{}, s); return true;
         CHEBYKAN_FOR_EACH_DEGREE(CHEBYKAN_BACKWARD_CASE)
+#undef CHEBYKAN_BACKWARD_CASE
+    }
+    return false;
+}
+
+// ---- table-interpolated variant: same plans and workspace, basis read from an LDS copy of the table
+bool table_fits(int d, int n)
+{
+    return table_degree_specialised(d) && n >= 2 && (int64_t)n * (d + 1) * (int64_t)sizeof(float) <= TABLE_LDS_BYTES;
+}
+
+bool fast_forward_table(const float* x, const float* C, const float* lut, int n, float* y, int64_t B, int I, int O,
+                        int d, void* ws, hipStream_t s)
+{
+    if (!shape_fits(B, I, O, d) || !table_fits(d, n)) return false;
+    if (forward_workspace_bytes(B, I, O, d) > 0 && !ws) return false;
+    const TableBasis::Args ba{lut, n};
+    switch (d) {
+#define CHEBYKAN_FORWARD_CASE(k) case k: degree_forward<k, TableBasis>(x, C, y, (int)B, I, O, ws, ba, s); return true;
+        CHEBYKAN_FOR_EACH_TABLE_DEGREE(CHEBYKAN_FORWARD_CASE)
+#undef CHEBYKAN_FORWARD_CASE
+    }
+    return false;
+}
+
+bool fast_backward_table(const float* x, const float* C, const float* dy, const float* lut, int n, float* dx,
+                         float* dC, int64_t B, int I, int O, int d, void* ws, hipStream_t s)
+{
+    if (!shape_fits(B, I, O, d) || !table_fits(d, n)) return false;
+    if (backward_workspace_bytes(B, I, O, d) > 0 && !ws) return false;
+    const TableBasis::Args ba{lut, n};
+    switch (d) {
+#define CHEBYKAN_BACKWARD_CASE(k) \
+    case k: degree_backward<k, TableBasis>(x, C, dy, dx, dC, (int)B, I, O, ws, ba, s); return true;
+        CHEBYKAN_FOR_EACH_TABLE_DEGREE(CHEBYKAN_BACKWARD_CASE)
 #undef CHEBYKAN_BACKWARD_CASE
     }
     return false;

@@ -94,15 +94,16 @@ struct FwdCfg {
 // through bounds-checked buffer views (zeros beyond the tensor), so this body has no
 // branches and the vector-ALU, LDS-write and load instructions can be scheduled between
 // MFMA issues of the same wave.
-template <class Cfg>
+template <class Cfg, class Basis = ExactBasis>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float* __restrict__ y,
-                int B, int I, int O, int n_tiles_o, int chunks_per_split)
+                int B, int I, int O, int n_tiles_o, int chunks_per_split, typename Basis::Args bargs)
 {
     constexpr int D = Cfg::D, K = Cfg::K, KP = Cfg::KP, BN = Cfg::BN, BI = Cfg::BI, VEC = Cfg::VEC;
     constexpr int SA = Cfg::SA, SS = Cfg::SS, TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
     extern __shared__ __align__(16) float lds[];
     CHEBYKAN_PROBE(0);
+    const Basis basis(bargs, lds + Cfg::LDS_BYTES / 4, Cfg::K, (int)threadIdx.x, MFMA_THREADS);
 
     const int t = threadIdx.x;
     const int tile_o = blockIdx.x % n_tiles_o;
@@ -159,7 +160,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
 #pragma unroll
         for (int j = 0; j < Cfg::XPT; ++j) {
             float T[D + 1];
-            cheb_T_of_x<D>(xreg[j], T);
+            basis.template T<D>(xreg[j], T);
             float* dst = sA + xr_row * SA + (xr_f0 + j) * K;
 #pragma unroll
             for (int k = 0; k < K; ++k) dst[k] = T[k];
@@ -307,15 +308,16 @@ struct DcCfg {
 // of atomics).  grid.x = tiles_ik * tiles_o * n_slices.  Same chunk pipeline as the
 // forward kernel: loads through buffer views based at the slice (rows past the slice
 // read as zero dy, so they add nothing), producer work between MFMA issues.
-template <class Cfg>
+template <class Cfg, class Basis = ExactBasis>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ partial,
-               int B, int I, int O, int n_tiles_o, int n_tiles_i, int n_slices, int rows_per_slice)
+               int B, int I, int O, int n_tiles_o, int n_tiles_i, int n_slices, int rows_per_slice, typename Basis::Args bargs)
 {
     constexpr int D = Cfg::D, K = Cfg::K, BN = Cfg::BN, VEC = Cfg::VEC, BB = Cfg::BB, BIC = Cfg::BIC;
     constexpr int SMA = Cfg::SMA, SNB = Cfg::SNB, TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
     extern __shared__ __align__(16) float lds[];
     CHEBYKAN_PROBE(0);
+    const Basis basis(bargs, lds + Cfg::LDS_BYTES / 4, Cfg::K, (int)threadIdx.x, MFMA_THREADS);
 
     const int t = threadIdx.x;
     // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.
@@ -385,7 +387,7 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
         for (int j = 0; j < Cfg::XPT; ++j) {
             const int bl = xe[j] / BIC, il = xe[j] % BIC;
             float T[D + 1];
-            cheb_T_of_x<D>(xreg[j], T);
+            basis.template T<D>(xreg[j], T);
             // SMA = BMR (mod 32): consecutive elements land K words apart across row ends too
             float* dst = sA + bl * SMA + il * K;
 #pragma unroll
@@ -565,15 +567,16 @@ struct DxCfg {
 // workgroup owns all outputs o for its (b,i) tile.  Each of the four waves takes 32 rows
 // and all NB column blocks; NB is chosen on the host so that the feature count wastes
 // as few columns as possible.  grid.x = ceil(B/128) * ceil(I/BIX).
-template <class Cfg>
+template <class Cfg, class Basis = ExactBasis>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
-               float* __restrict__ dx, int B, int I, int O, int n_tiles_i, int chunks_per_split)
+               float* __restrict__ dx, int B, int I, int O, int n_tiles_i, int chunks_per_split, typename Basis::Args bargs)
 {
     constexpr int D = Cfg::D, K = Cfg::K, VEC = Cfg::VEC, BIX = Cfg::BIX, BO = Cfg::BO, NB = Cfg::NB;
     constexpr int SAX = Cfg::SAX, SSX = Cfg::SSX, SG = Cfg::SG;
     extern __shared__ __align__(16) float lds[];
     CHEBYKAN_PROBE(0);
+    const Basis basis(bargs, lds + Cfg::LDS_BYTES / 4, Cfg::K, (int)threadIdx.x, MFMA_THREADS);
 
     const int t = threadIdx.x;
     const int tile_i = blockIdx.x % n_tiles_i;
@@ -727,9 +730,8 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
         const int b = b0 + m, i = i0 + il;
         if (e < Cfg::BM * BIX && b < B && i < I) {
             float slope;
-            const float u = normalise(x[(int64_t)b * I + i], slope);
             float dT[D];
-            cheb_dT<D>(u, dT);
+            basis.template dT<D>(x[(int64_t)b * I + i], dT, slope);
             const float* g = lds + m * SG + il * D;
             float sum = 0.0f;
 #pragma unroll
@@ -774,15 +776,16 @@ struct Dx2Cfg {
 };
 
 // grid.x = ceil(B/128) * ceil(I/32), feature tile fastest.
-template <class Cfg>
+template <class Cfg, class Basis = ExactBasis>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
-                float* __restrict__ dx, int B, int I, int O, int n_tiles_i, int chunks_per_split)
+                float* __restrict__ dx, int B, int I, int O, int n_tiles_i, int chunks_per_split, typename Basis::Args bargs)
 {
     constexpr int D = Cfg::D, K = Cfg::K, VEC = Cfg::VEC, BF = Cfg::BF, BO = Cfg::BO;
     constexpr int SAX = Cfg::SAX, SSX = Cfg::SSX;
     extern __shared__ __align__(16) float lds[];
     CHEBYKAN_PROBE(0);
+    const Basis basis(bargs, lds + Cfg::LDS_BYTES / 4, Cfg::K, (int)threadIdx.x, MFMA_THREADS);
 
     const int t = threadIdx.x;
     const int tile_i = blockIdx.x % n_tiles_i;
@@ -872,9 +875,8 @@ dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             float slope;
-            const float u = normalise(xval[r], slope);
             float dT[D];
-            cheb_dT<D>(u, dT);
+            basis.template dT<D>(xval[r], dT, slope);
             float sum = 0.0f;
 #pragma unroll
             for (int j = 0; j < D; ++j) sum = fmaf(acc[j][r], dT[j], sum);

@@ -63,16 +63,21 @@ __device__ __forceinline__ float group_sum(float v, int G)
 // consecutive rows starting at first + (it * 256/G + rg) * NARROW_RB.  G = lanes per row
 // (power of two, 8..64); lane g of a group takes input features g, g+G, ...
 
+// LDS floats of the two kernels' own data (a basis table, if any, follows them)
+__host__ __device__ constexpr size_t narrow_fwd_lds_floats(int I, int O, int K) { return ((size_t)I * O * K + 3) & ~(size_t)3; }
+__host__ __device__ constexpr size_t narrow_bwd_lds_floats(int O, int K) { return (size_t)NARROW_THREADS * O * K; }
+
 // grid.x workgroups.  Dynamic LDS: I*O*(D+1) floats, coefficients as [k][o][i].
 // The x values of the next step are requested before the current step is computed.
-template <int D, int O>
+template <int D, int O, class Basis = ExactBasis>
 __global__ void __launch_bounds__(NARROW_THREADS)
 narrow_fwd_kernel(const float* __restrict__ x, const float* __restrict__ C, float* __restrict__ y,
-                  int B, int I, int G, int rows_per_wg)
+                  int B, int I, int G, int rows_per_wg, typename Basis::Args bargs)
 {
     constexpr int K = D + 1, RB = NARROW_RB;
     extern __shared__ __align__(16) float lds[];
     const int t = threadIdx.x;
+    const Basis basis(bargs, lds + narrow_fwd_lds_floats(I, O, K), K, t, NARROW_THREADS);
     const int g = t % G, rg = t / G, RPW = NARROW_THREADS / G;
     const int64_t first = (int64_t)blockIdx.x * rows_per_wg;
     int64_t last = first + rows_per_wg;
@@ -121,7 +126,7 @@ narrow_fwd_kernel(const float* __restrict__ x, const float* __restrict__ C, floa
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
                 float T[K];
-                cheb_T_of_x<D>(xv[r], T);
+                basis.template T<D>(xv[r], T);
 #pragma unroll
                 for (int o = 0; o < O; ++o) {
                     float s = 0.0f;
@@ -146,14 +151,16 @@ narrow_fwd_kernel(const float* __restrict__ x, const float* __restrict__ C, floa
 
 // grid = (row slices, ceil(I/G) feature groups).  Writes dx (if non-null) and
 // partial[slice][i][o][k] (if non-null).  Dynamic LDS: 256*O*(D+1) floats.
-template <int D, int O>
+template <int D, int O, class Basis = ExactBasis>
 __global__ void __launch_bounds__(NARROW_THREADS)
 narrow_bwd_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
-                  float* __restrict__ dx, float* __restrict__ partial, int B, int I, int G, int rows_per_wg)
+                  float* __restrict__ dx, float* __restrict__ partial, int B, int I, int G, int rows_per_wg,
+                  typename Basis::Args bargs)
 {
     constexpr int K = D + 1, RB = NARROW_RB;
     extern __shared__ __align__(16) float lds[];
     const int t = threadIdx.x;
+    const Basis basis(bargs, lds + narrow_bwd_lds_floats(O, K), K, t, NARROW_THREADS);
     const int g = t % G, rg = t / G, RPW = NARROW_THREADS / G;
     const int i = blockIdx.y * G + g;
     const bool i_ok = i < I;
@@ -199,18 +206,16 @@ narrow_bwd_kernel(const float* __restrict__ x, const float* __restrict__ C, cons
 #pragma unroll
         for (int r = 0; r < RB; ++r) {
             float slope;
-            const float u = normalise(xv[r], slope);
             float T[K];
-            if constexpr (D <= 8) cheb_T<D>(u, T);
-            else cheb_T_of_x<D>(xv[r], T);
+            float dT[D > 0 ? D : 1];
+            const bool want_dx = dx && i_ok && row0 + r < last;
+            basis.template T_dT<D>(xv[r], T, dT, slope, want_dx);
 #pragma unroll
             for (int o = 0; o < O; ++o)
 #pragma unroll
                 for (int k = 0; k < K; ++k) acc[o][k] = fmaf(T[k], gv[r][o], acc[o][k]);
             if constexpr (D >= 1) {
-                if (dx && i_ok && row0 + r < last) {
-                    float dT[D];
-                    cheb_dT<D>(u, dT);
+                if (want_dx) {
                     float s = 0.0f;
 #pragma unroll
                     for (int o = 0; o < O; ++o) {

@@ -1,7 +1,8 @@
 // Host driver for the CPU emulation build of the library: reads raw fp32 inputs,
 // calls the C ABI (whose launches now run on OS threads), writes raw outputs.
-//   emu_driver <dir> <B> <I> <O> <degree> <family>
-// <dir> holds x.bin, C.bin, dy.bin; y.bin, dx.bin, dC.bin are written there.
+//   emu_driver <dir> <B> <I> <O> <degree> <family> [lut_size]
+// <dir> holds x.bin, C.bin, dy.bin (and lut.bin when lut_size is given: the table-interpolated
+// entry points are called then); y.bin, dx.bin, dC.bin are written there.
 #include <stdio.h>
 #include <stdlib.h>
 #include <math.h>
@@ -28,7 +29,8 @@ static void write_bin(const std::string& path, const float* p, size_t n)
 
 int main(int argc, char** argv)
 {
-    if (argc != 7) { fprintf(stderr, "usage: emu_driver dir B I O degree family\n"); return 2; }
+    if (argc != 7 && argc != 8) { fprintf(stderr, "usage: emu_driver dir B I O degree family [lut_size]\n"); return 2; }
+    const int lut_size = argc == 8 ? atoi(argv[7]) : 0;
     const std::string dir = argv[1];
     const long B = atol(argv[2]);
     const int I = atoi(argv[3]), O = atoi(argv[4]), d = atoi(argv[5]), family = atoi(argv[6]);
@@ -49,9 +51,14 @@ int main(int argc, char** argv)
     const size_t wn = wf > wb ? wf : wb;
     float* ws = wn ? (float*)malloc(wn) : nullptr;
     for (size_t i = 0; i < wn / 4; ++i) ws[i] = NAN;
-    int rc = chebykan_forward(x.data(), C.data(), y, B, I, O, d, ws, wn, nullptr);
+    std::vector<float> lut;
+    if (lut_size > 0) lut = read_bin(dir + "/lut.bin", K * (size_t)lut_size);
+    int rc = lut_size > 0 ? chebykan_forward_lut(x.data(), C.data(), lut.data(), lut_size, y, B, I, O, d, ws, wn, nullptr)
+                          : chebykan_forward(x.data(), C.data(), y, B, I, O, d, ws, wn, nullptr);
     if (rc != CHEBYKAN_OK) { fprintf(stderr, "forward: %s\n", chebykan_status_string((chebykan_status)rc)); return 1; }
-    rc = chebykan_backward(x.data(), C.data(), dy.data(), dx, dC, B, I, O, d, ws, wn, nullptr);
+    rc = lut_size > 0 ? chebykan_backward_lut(x.data(), C.data(), dy.data(), lut.data(), lut_size, dx, dC, B, I, O, d, ws,
+                                              wn, nullptr)
+                      : chebykan_backward(x.data(), C.data(), dy.data(), dx, dC, B, I, O, d, ws, wn, nullptr);
     if (rc != CHEBYKAN_OK) { fprintf(stderr, "backward: %s\n", chebykan_status_string((chebykan_status)rc)); return 1; }
     write_bin(dir + "/y.bin", y, (size_t)B * O);
     write_bin(dir + "/dx.bin", dx, (size_t)B * I);

@@ -5,6 +5,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2511_14852_amd import binding
@@ -107,3 +108,18 @@ def test_no_device_is_reported_not_faked():
         pytest.skip("a GPU is present")
     P = 4096
     assert binding.raw_forward(P, P, P, 4, 4, 4, 2) == binding.CHEBYKAN_ERR_DEVICE
+
+
+def test_host_table_builder_matches_the_oracle_table():
+    """chebykan_lut_build runs on the host: its fp32 table against the oracle's fp64 construction."""
+    import oracle
+    for degree, n in [(0, 2), (1, 5), (6, 1025), (8, 2049), (24, 257)]:
+        lut = binding.chebykan_lut_build(degree, n).numpy()
+        want = oracle.lut_build(degree, n)
+        assert lut.shape == want.shape
+        assert np.array_equal(lut, want.astype(np.float32))
+    lib = binding.load()
+    assert lib.chebykan_lut_build(None, 3, 9) == binding.CHEBYKAN_ERR_NULL
+    buf = np.zeros(16, dtype=np.float32)
+    assert lib.chebykan_lut_build(buf.ctypes.data, 3, 1) == binding.CHEBYKAN_ERR_SHAPE
+    assert lib.chebykan_lut_build(buf.ctypes.data, -1, 4) == binding.CHEBYKAN_ERR_SHAPE

@@ -15,6 +15,7 @@ import numpy as np
 import pytest
 
 import oracle
+from lut_checks import dx_error
 from paper_2511_14852_amd import workloads as wl
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -50,7 +51,7 @@ def emu_driver():
     return exe
 
 
-def _run(exe, B, I, O, d, family, seed=1):
+def _run(exe, B, I, O, d, family, seed=1, lut_size=0):
     x = wl.make_x(B, I, seed)
     C = wl.make_coeff(I, O, d, seed + 1)
     dy = wl.make_dy(B, O, seed + 2)
@@ -59,14 +60,22 @@ def _run(exe, B, I, O, d, family, seed=1):
         x.tofile(os.path.join(td, "x.bin"))
         C.tofile(os.path.join(td, "C.bin"))
         dy.tofile(os.path.join(td, "dy.bin"))
-        r = subprocess.run([exe, td, str(B), str(I), str(O), str(d), str(family)], capture_output=True, text=True,
-                           timeout=600)
+        args = [exe, td, str(B), str(I), str(O), str(d), str(family)]
+        if lut_size:
+            lut = oracle.lut_build(d, lut_size).astype(np.float32)
+            lut.tofile(os.path.join(td, "lut.bin"))
+            args.append(str(lut_size))
+        r = subprocess.run(args, capture_output=True, text=True, timeout=600)
         assert r.returncode == 0, (r.stdout[-1000:], r.stderr[-4000:])
         y = np.fromfile(os.path.join(td, "y.bin"), dtype=np.float32).reshape(B, O)
         dx = np.fromfile(os.path.join(td, "dx.bin"), dtype=np.float32).reshape(B, I)
         dC = np.fromfile(os.path.join(td, "dC.bin"), dtype=np.float32).reshape(I, O, d + 1)
     finally:
         shutil.rmtree(td, ignore_errors=True)
+    if lut_size:
+        _, dC_ref = oracle.backward_lut(x, C, dy, lut, need_dx=False)
+        return (oracle.rel_err(y, oracle.forward_lut(x, C, lut)), dx_error(dx, x, C, dy, lut),
+                oracle.rel_err(dC, dC_ref))
     dx_ref, dC_ref = oracle.backward(x, C, dy)
     return (oracle.rel_err(y, oracle.forward(x, C)), oracle.rel_err(dx, dx_ref), oracle.rel_err(dC, dC_ref))
 
@@ -111,4 +120,24 @@ def test_mfma_family_on_cpu_emulation(emu_driver, case):
 
 def test_generic_family_on_cpu_emulation(emu_driver):
     errs = _run(emu_driver, 37, 11, 9, 7, family=1)
+    assert all(np.isfinite(e) and e <= 1e-5 for e in errs), errs
+
+
+# (B, I, O, degree, table size): the table-interpolated form of each kernel family, a table too
+# large for staging (any-degree kernels with the table in global memory) and the smallest table
+LUT_CASES = [
+    (130, 9, 64, 4, 65),
+    (140, 40, 72, 6, 129),
+    (129, 5, 257, 8, 33),
+    (300, 64, 1, 6, 65),
+    (100, 8, 2, 3, 17),
+    (64, 300, 72, 2, 2),
+    (40, 6, 20, 6, 4097),
+]
+
+
+@pytest.mark.parametrize("case", LUT_CASES, ids=lambda c: "B%d_I%d_O%d_d%d_n%d" % c)
+def test_table_variant_on_cpu_emulation(emu_driver, case):
+    B, I, O, d, n = case
+    errs = _run(emu_driver, B, I, O, d, family=2, lut_size=n)
     assert all(np.isfinite(e) and e <= 1e-5 for e in errs), errs

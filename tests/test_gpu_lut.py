@@ -1,0 +1,202 @@
+"""GPU parity of the table-interpolated variant (paper Sec. 4.2) against its fp64 oracle.
+
+Both sides interpolate the SAME fp32 table (built by the oracle, rounded once).  Bars:
+ - y and dC: max |gpu - oracle| / RMS(oracle) <= 1e-5 (the interpolant is continuous, so the cell
+   an implementation picks next to a knot does not matter);
+ - dx uses the difference quotient of the chosen cell, which jumps at the knots.  The GPU takes the
+   cell in fp32, the oracle in fp64: elements whose position lies within 2e-3 cells of a knot may
+   legitimately use either neighbour and are accepted against either; all others meet 1e-5;
+ - against the EXACT layer the variant is an approximation: <= 1e-3 for y and dC with 1025 samples
+   (degree <= 8); dx is first-order in the step and only reported against its bound.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from lut_checks import dx_error
+from paper_2511_14852_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def make_table(degree, n):
+    """fp32 table from the oracle's fp64 construction (never from the GPU library)."""
+    return oracle.lut_build(degree, n).astype(np.float32)
+
+
+def gpu_layer_lut(x, C, lut, dy=None, family=0, need_dx=True, need_dC=True):
+    B, I = x.shape
+    _, O, K = C.shape
+    prev = binding.chebykan_set_kernel_family(family)
+    try:
+        xd, Cd, ld = _dev(x), _dev(C), _dev(lut)
+        ws = binding.alloc_workspace(B, I, O, K - 1)
+        y = torch.full((B, O), float("nan"), device="cuda")
+        binding.chebykan_forward_lut(xd, Cd, ld, y, ws)
+        out = [y.cpu().numpy()]
+        if dy is not None:
+            dyd = _dev(dy)
+            dx = torch.full((B, I), float("nan"), device="cuda") if need_dx else None
+            dC = torch.full((I, O, K), float("nan"), device="cuda") if need_dC else None
+            binding.chebykan_backward_lut(xd, Cd, dyd, ld, dx, dC, ws)
+            out += [None if dx is None else dx.cpu().numpy(), None if dC is None else dC.cpu().numpy()]
+        torch.cuda.synchronize()
+    finally:
+        binding.chebykan_set_kernel_family(prev)
+    return out
+
+
+def check_dx(dx, x, C, dy, lut, label):
+    worst = dx_error(dx, x, C, dy, lut)
+    assert worst <= TOL, (label, "dx", worst)
+    return worst
+
+
+def check_all(x, C, dy, lut, family, label):
+    y, dx, dC = gpu_layer_lut(x, C, lut, dy, family)
+    ey = oracle.rel_err(y, oracle.forward_lut(x, C, lut))
+    _, dC_ref = oracle.backward_lut(x, C, dy, lut, need_dx=False)
+    eC = oracle.rel_err(dC, dC_ref)
+    ex = check_dx(dx, x, C, dy, lut, label)
+    print("%s family=%d errs y %.2e dx %.2e dC %.2e" % (label, family, ey, ex, eC), flush=True)
+    assert np.isfinite(ey) and ey <= TOL, (label, "y", ey)
+    assert np.isfinite(eC) and eC <= TOL, (label, "dC", eC)
+
+
+def _inputs(B, I, O, d, seed, x_mean=0.0, x_std=1.0):
+    return (wl.make_x(B, I, seed, x_mean, x_std), wl.make_coeff(I, O, d, seed + 1), wl.make_dy(B, O, seed + 2))
+
+
+# (B, I, O, degree, table size): every kernel family of the exact path, ragged tiles, several table sizes,
+# a table too large for on-chip staging (4097 at degree 6) and degrees without table kernels (1, 15)
+SHAPES = [
+    (256, 64, 64, 4, 1025),
+    (300, 70, 150, 8, 513),
+    (513, 33, 129, 3, 2049),
+    (260, 257, 65, 5, 257),
+    (1000, 8, 64, 6, 1025),
+    (777, 64, 1, 6, 1025),
+    (129, 130, 257, 6, 33),
+    (37, 5, 3, 2, 1025),
+    (130, 20, 70, 7, 1025),
+    (200, 5, 40, 6, 4097),
+    (64, 24, 40, 15, 257),
+    (50, 17, 9, 1, 65),
+    (100, 20, 2, 3, 129),
+    (50, 300, 4, 5, 1025),
+    (128, 40, 256, 8, 2049),
+    (1200, 70, 40, 8, 1025),
+    (129, 7, 520, 8, 1025),
+    (140, 21, 64, 3, 2),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "B%d_I%d_O%d_d%d_n%d" % s)
+@pytest.mark.parametrize("family", [0, 1], ids=["auto", "generic"])
+def test_small_shapes_elementwise(shape, family):
+    B, I, O, d, n = shape
+    x, C, dy = _inputs(B, I, O, d, seed=3000 + B + I + O + d)
+    check_all(x, C, dy, make_table(d, n), family, "lut %s" % (shape,))
+
+
+def test_saturating_inputs_use_the_last_cell():
+    B, I, O, d, n = 200, 16, 24, 6, 1025
+    x, C, dy = _inputs(B, I, O, d, seed=91, x_mean=-2.0, x_std=1.5)
+    x[0, :8] = [12.0, -12.0, 30.0, -30.0, 9.5, -9.5, 0.0, -0.0]
+    check_all(x, C, dy, make_table(d, n), 0, "saturating")
+
+
+def test_skip_one_gradient_and_reproducibility():
+    B, I, O, d, n = 300, 40, 72, 6, 1025
+    x, C, dy = _inputs(B, I, O, d, seed=17)
+    lut = make_table(d, n)
+    y, dx, dC = gpu_layer_lut(x, C, lut, dy)
+    _, dx_only, none_dC = gpu_layer_lut(x, C, lut, dy, need_dC=False)
+    _, none_dx, dC_only = gpu_layer_lut(x, C, lut, dy, need_dx=False)
+    assert none_dC is None and none_dx is None
+    assert np.array_equal(dx, dx_only) and np.array_equal(dC, dC_only)
+    y2, dx2, dC2 = gpu_layer_lut(x, C, lut, dy)
+    assert np.array_equal(y, y2) and np.array_equal(dx, dx2) and np.array_equal(dC, dC2)
+
+
+def test_argument_errors_and_empty_batch():
+    d, n = 4, 129
+    lut = _dev(make_table(d, n))
+    C = _dev(wl.make_coeff(8, 8, d, 1))
+    x = torch.zeros((4, 8), device="cuda")
+    y = torch.zeros((4, 8), device="cuda")
+    lib = binding.load()
+    st = lib.chebykan_forward_lut(x.data_ptr(), C.data_ptr(), None, n, y.data_ptr(), 4, 8, 8, d, None, 0, None)
+    assert st == binding.CHEBYKAN_ERR_NULL
+    st = lib.chebykan_forward_lut(x.data_ptr(), C.data_ptr(), lut.data_ptr(), 1, y.data_ptr(), 4, 8, 8, d, None, 0, None)
+    assert st == binding.CHEBYKAN_ERR_SHAPE
+    st = lib.chebykan_forward_lut(None, C.data_ptr(), lut.data_ptr(), n, None, 0, 8, 8, d, None, 0, None)
+    assert st == binding.CHEBYKAN_OK
+    dC = torch.full((8, 8, d + 1), float("nan"), device="cuda")
+    st = lib.chebykan_backward_lut(None, C.data_ptr(), None, lut.data_ptr(), n, None, dC.data_ptr(), 0, 8, 8, d,
+                                   None, 0, None)
+    torch.cuda.synchronize()
+    assert st == binding.CHEBYKAN_OK and bool((dC == 0).all())
+
+
+@pytest.mark.parametrize("degree", [3, 6, 8])
+def test_error_against_the_exact_layer(degree):
+    """With 1025 samples y and dC stay within 1e-3 of the exact layer; dx within its first-order bound."""
+    B, I, O, n = 512, 64, 48, 1025
+    x, C, dy = _inputs(B, I, O, degree, seed=55)
+    y, dx, dC = gpu_layer_lut(x, C, make_table(degree, n), dy)
+    y_ref = oracle.forward(x, C)
+    dx_ref, dC_ref = oracle.backward(x, C, dy)
+    ey, ex, eC = oracle.rel_err(y, y_ref), oracle.rel_err(dx, dx_ref), oracle.rel_err(dC, dC_ref)
+    print("degree %d, %d samples, against the exact layer: y %.2e dx %.2e dC %.2e" % (degree, n, ey, ex, eC),
+          flush=True)
+    assert ey <= 1e-3 and eC <= 1e-3
+    # per-term derivative error <= step * k^2(k^2-1)/3; loose whole-layer bound from it
+    step = 2.0 / (n - 1)
+    assert ex <= step * degree ** 2 * (degree ** 2 - 1) / 3.0
+
+
+def test_tabular_stack_sampled():
+    """The benchmark's table-variant workload: full-size stack, sampled outputs layer by layer."""
+    w = wl.WORKLOADS["c2"]
+    n = 1025
+    x0, Cs, dy_last = wl.workload_inputs(w)
+    lut = make_table(w.degree, n)
+    ld = _dev(lut)
+    rng = np.random.default_rng(7)
+    B = w.batch
+    xs = [_dev(x0)]
+    Cd = [_dev(c) for c in Cs]
+    ws = [binding.alloc_workspace(B, i, o, w.degree) for (i, o) in w.layers]
+    for l, (i, o) in enumerate(w.layers):
+        y = torch.empty((B, o), device="cuda")
+        binding.chebykan_forward_lut(xs[l], Cd[l], ld, y, ws[l])
+        xs.append(y)
+    dy = _dev(dy_last)
+    rows = np.sort(rng.choice(B, size=48, replace=False))
+    for l in reversed(range(len(w.layers))):
+        i_dim, o_dim = w.layers[l]
+        dx = torch.empty((B, i_dim), device="cuda")
+        dC = torch.empty_like(Cd[l])
+        binding.chebykan_backward_lut(xs[l], Cd[l], dy, ld, dx, dC, ws[l])
+        torch.cuda.synchronize()
+        x_l, dy_l = xs[l].cpu().numpy(), dy.cpu().numpy()
+        # forward and dx are independent per row: the oracle runs on the sampled rows only
+        y_ref = oracle.forward_lut(x_l[rows], Cs[l], lut)
+        ey = np.max(np.abs(xs[l + 1].cpu().numpy()[rows] - y_ref)) / np.sqrt(np.mean(y_ref ** 2))
+        ex = check_dx(dx.cpu().numpy()[rows], x_l[rows], Cs[l], dy_l[rows], lut, "c2 layer %d" % l)
+        cnt = 24
+        is_, os_, ks = rng.integers(0, i_dim, cnt), rng.integers(0, o_dim, cnt), rng.integers(0, w.degree + 1, cnt)
+        dC_ref = oracle.dC_lut_at(x_l, dy_l, lut, is_, os_, ks)
+        dC_full_rms = float(np.sqrt(np.mean(dC.cpu().numpy().astype(np.float64) ** 2)))
+        eC = np.max(np.abs(dC.cpu().numpy()[is_, os_, ks] - dC_ref)) / dC_full_rms
+        print("c2 table variant layer %d: y %.2e dx %.2e dC %.2e" % (l, ey, ex, eC), flush=True)
+        assert ey <= TOL and eC <= TOL
+        dy = dx

@@ -213,3 +213,12 @@ def test_converges_to_the_exact_layer():
             assert 3 < prev[1] / edx < 5.5                                  # first order: 4x per 4x samples
         prev = (ey, edx, edC)
     assert prev[0] < 2e-5 and prev[2] < 2e-5 and prev[1] < 5e-3
+
+
+def test_sampled_dC_matches_the_full_computation():
+    x, C, dy = _layer(41, 70, 6, 5, 4)
+    lut = oracle.lut_build(4, 65)
+    _, dC = oracle.backward_lut(x, C, dy, lut, need_dx=False)
+    is_, os_, ks = [0, 5, 3, 2], [4, 0, 2, 2], [0, 4, 1, 3]
+    got = oracle.dC_lut_at(x, dy, lut, is_, os_, ks)
+    assert np.allclose(got, dC[is_, os_, ks], rtol=1e-13, atol=1e-13)
