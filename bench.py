@@ -32,12 +32,12 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
 # WRITE_SIZE runs scaled by the same counters on a 256 MiB copy (profiles/<workload>_counters.md).
 # Keyed by (workload, call, layer); a call that is not listed reports traffic = null.
 MEASURED_TRAFFIC_BYTES = {
-    ("c2", "dC", 1): 132.2e6 + 14.8e6,
+    ("c2", "dC", 1): 48.4e6 + 14.8e6,      # slice kernel + combine
     ("c2", "dx", 1): 80.6e6,
     ("c2", "fwd", 1): 26.8e6,
-    ("c5", "dC", 0): 900.1e6 + 188.8e6,
-    ("c5", "fwd", 0): 753.5e6,
-    ("c5", "dx", 0): 1781.8e6,
+    ("c5", "dC", 0): 900.5e6 + 188.8e6,
+    ("c5", "fwd", 0): 754.4e6,
+    ("c5", "dx", 0): 1762.9e6,
 }
 
 
