@@ -13,7 +13,8 @@ from typing import Optional, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, "chebykan_oracle.c"), os.path.join(_HERE, "chebykan_lut_oracle.c")]
+_SRCS = [os.path.join(_HERE, "chebykan_oracle.c"), os.path.join(_HERE, "chebykan_lut_oracle.c"),
+         os.path.join(_HERE, "kan_bases_oracle.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib: Optional[ctypes.CDLL] = None
 
@@ -67,6 +68,12 @@ def _load() -> ctypes.CDLL:
         lib.oracle_forward_lut.restype = ctypes.c_int
         lib.oracle_backward_lut.argtypes = [dp, dp, dp, dp, i64, i8p, dp, dp, dp, i64, i64, i64, ctypes.c_int]
         lib.oracle_backward_lut.restype = ctypes.c_int
+        lib.oracle_basis_eval.argtypes = [ctypes.c_int, ctypes.c_double, ctypes.c_int, dp, dp]
+        lib.oracle_basis_eval.restype = ctypes.c_int
+        lib.oracle_forward_basis.argtypes = [ctypes.c_int, dp, dp, dp, i64, i64, i64, ctypes.c_int]
+        lib.oracle_forward_basis.restype = ctypes.c_int
+        lib.oracle_backward_basis.argtypes = [ctypes.c_int, dp, dp, dp, dp, dp, i64, i64, i64, ctypes.c_int]
+        lib.oracle_backward_basis.restype = ctypes.c_int
         lib.oracle_dC_lut_at.argtypes = [dp, dp, dp, i64, ip, ip, ip, i64, dp, i64, i64, i64, ctypes.c_int]
         lib.oracle_dC_lut_at.restype = ctypes.c_int
         _lib = lib
@@ -269,3 +276,35 @@ def dC_lut_at(x, dy, lut, is_, os_, ks) -> np.ndarray:
     if rc != 0:
         raise ValueError("oracle_dC_lut_at failed")
     return out
+
+
+# ------------------------------------------------------------- other bases
+BASIS_CHEBYSHEV, BASIS_LEGENDRE, BASIS_HERMITE, BASIS_FOURIER = 0, 1, 2, 3
+
+
+def basis_eval(kind: int, x: float, degree: int):
+    """(B_0..B_d, dB_0/dx..dB_d/dx) of one basis family at the raw input x."""
+    Bv = np.empty(degree + 1)
+    dB = np.empty(degree + 1)
+    if _load().oracle_basis_eval(int(kind), float(x), int(degree), _dp(Bv), _dp(dB)) != 0:
+        raise ValueError("basis kind/degree not supported")
+    return Bv, dB
+
+
+def forward_basis(kind: int, x, C) -> np.ndarray:
+    B, I, O, d = _check_shapes(x, C)
+    x64, C64 = _f64(x), _f64(C)
+    y = np.empty((B, O), dtype=np.float64)
+    if _load().oracle_forward_basis(int(kind), _dp(x64), _dp(C64), _dp(y), B, I, O, d) != 0:
+        raise ValueError("basis kind/degree not supported")
+    return y
+
+
+def backward_basis(kind: int, x, C, dy, need_dx: bool = True, need_dC: bool = True):
+    B, I, O, d = _check_shapes(x, C, dy)
+    x64, C64, dy64 = _f64(x), _f64(C), _f64(dy)
+    dx = np.empty((B, I), dtype=np.float64) if need_dx else None
+    dC = np.empty((I, O, d + 1), dtype=np.float64) if need_dC else None
+    if _load().oracle_backward_basis(int(kind), _dp(x64), _dp(C64), _dp(dy64), _dp(dx), _dp(dC), B, I, O, d) != 0:
+        raise ValueError("basis kind/degree not supported")
+    return dx, dC
