@@ -52,8 +52,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--family", type=int, default=0, help="kernel family override (0 auto)")
-    ap.add_argument("--basis", default="exact", choices=["exact", "lut"],
-                    help="exact = recurrences (default); lut = the paper's table-interpolated variant (Sec. 4.2)")
+    ap.add_argument("--basis", default="exact", choices=["exact", "lut", "legendre", "hermite", "fourier"],
+                    help="exact = Chebyshev recurrences (default); lut = the paper's table-interpolated variant "
+                         "(Sec. 4.2); legendre / hermite / fourier = the other bases of Sec. 2.3 on the same kernels")
     ap.add_argument("--lut-size", type=int, default=1025, help="table samples for --basis lut")
     ap.add_argument("--probe", type=int, default=0,
                     help="counter-collection mode for rocprofv3 --pmc: run this many steps of the split calls plus "
@@ -64,8 +65,9 @@ def parse_args():
 class Stack:
     """Device buffers and the launch sequence of one workload."""
 
-    def __init__(self, w, rotate, torch, binding, wl, lut=None):
+    def __init__(self, w, rotate, torch, binding, wl, lut=None, kind=0):
         self.w, self.torch, self.binding = w, torch, binding
+        self.kind = kind        # 0 Chebyshev, 1 Legendre, 2 Hermite, 3 Fourier
         self.lut = lut          # device table [degree+1, samples] or None for the exact basis
         B = w.batch
         self.B = B
@@ -88,14 +90,18 @@ class Stack:
 
     def _fwd(self, xin, l, s):
         b = self.binding
-        if self.lut is None:
+        if self.kind:
+            b.chebykan_forward_basis(self.kind, xin, self.C[l], self.y[l], self.ws[l], s)
+        elif self.lut is None:
             b.chebykan_forward(xin, self.C[l], self.y[l], self.ws[l], s)
         else:
             b.chebykan_forward_lut(xin, self.C[l], self.lut, self.y[l], self.ws[l], s)
 
     def _bwd(self, xin, l, dy, dx, dC, s):
         b = self.binding
-        if self.lut is None:
+        if self.kind:
+            b.chebykan_backward_basis(self.kind, xin, self.C[l], dy, dx, dC, self.ws[l], s)
+        elif self.lut is None:
             b.chebykan_backward(xin, self.C[l], dy, dx, dC, self.ws[l], s)
         else:
             b.chebykan_backward_lut(xin, self.C[l], dy, self.lut, dx, dC, self.ws[l], s)
@@ -166,7 +172,7 @@ def measured_peaks(torch, binding, stream):
             "note": "register-only v_mfma_f32_32x32x2_f32 loop on 512 workgroups; 256 MiB device copy"}
 
 
-def cpu_baseline(w, wl, target_seconds, lut_size=0):
+def cpu_baseline(w, wl, target_seconds, lut_size=0, kind=0):
     """Time the fp64 oracle on the host cores over a bounded row sample of the workload."""
     import oracle
     threads = oracle.num_threads()
@@ -177,10 +183,18 @@ def cpu_baseline(w, wl, target_seconds, lut_size=0):
         t0 = time.perf_counter()
         xs = [x0.astype(np.float64)]
         for C in Cs:
-            xs.append(oracle.forward(xs[-1], C) if lut is None else oracle.forward_lut(xs[-1], C, lut))
+            if kind:
+                xs.append(oracle.forward_basis(kind, xs[-1], C))
+            else:
+                xs.append(oracle.forward(xs[-1], C) if lut is None else oracle.forward_lut(xs[-1], C, lut))
         dy = dy_last.astype(np.float64)
         for l in reversed(range(len(Cs))):
-            dx, _ = oracle.backward(xs[l], Cs[l], dy) if lut is None else oracle.backward_lut(xs[l], Cs[l], dy, lut)
+            if kind:
+                dx, _ = oracle.backward_basis(kind, xs[l], Cs[l], dy)
+            elif lut is None:
+                dx, _ = oracle.backward(xs[l], Cs[l], dy)
+            else:
+                dx, _ = oracle.backward_lut(xs[l], Cs[l], dy, lut)
             dy = dx
         return time.perf_counter() - t0
 
@@ -212,7 +226,10 @@ def main():
     lut = None
     if args.basis == "lut":
         lut = binding.chebykan_lut_build(w.degree, args.lut_size).cuda()
-    st = Stack(w, max(1, args.rotate), torch, binding, wl, lut)
+    kind = {"legendre": 1, "hermite": 2, "fourier": 3}.get(args.basis, 0)
+    if kind == 3 and w.degree % 2:
+        raise SystemExit("the Fourier basis needs an even degree; workload %s has degree %d" % (w.name, w.degree))
+    st = Stack(w, max(1, args.rotate), torch, binding, wl, lut, kind)
     B = w.batch
 
     if args.probe > 0:
@@ -268,7 +285,7 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(dom["gbs"] / PEAK_HBM_GBS, 4)}
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((w.name, dom["call"], dom["layer"])) if lut is None else None
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((w.name, dom["call"], dom["layer"])) if lut is None and not kind else None
     roof["algorithmic_bytes"] = by
     roof["kernel"] = "%s layer %d (%d->%d)" % (dom["call"], dom["layer"], I, O)
     roof["us"] = dom["us"]
@@ -281,7 +298,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %s, batch %d, widths %s, degree %d%s" % (
             w.name, w.note, B, "->".join(map(str, w.widths)), w.degree,
-            "" if lut is None else ", table-interpolated basis with %d samples" % args.lut_size),
+            (", %s basis" % args.basis if kind else "") if lut is None
+            else ", table-interpolated basis with %d samples" % args.lut_size),
             "input_sets_rotated": len(st.x0_sets), "basis": args.basis},
         "tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
         "algorithmic_gbs": total_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -292,7 +310,7 @@ def main():
     }
     line["measured_peaks"] = measured_peaks(torch, binding, st.stream)
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(w, wl, args.cpu_seconds, args.lut_size if lut is not None else 0)
+        line["cpu_baseline"] = cpu_baseline(w, wl, args.cpu_seconds, args.lut_size if lut is not None else 0, kind)
     print(json.dumps(line), flush=True)
 
 

@@ -138,6 +138,40 @@ chebykan_status chebykan_backward_lut(const float *x, const float *C, const floa
                                       int64_t batch, int in, int out, int degree,
                                       void *workspace, size_t workspace_bytes, chebykan_stream_t stream);
 
+/*
+ * Other KAN bases on the same layer skeleton (paper Sec. 2.3: every variant expands
+ * each input into K = degree+1 basis functions by a short recurrence and contracts
+ * them with C; Sec. 6.3 reports the method on Fourier, Legendre and Hermite KANs).
+ * The paper prints no formulas for these bases; the textbook ones are used:
+ *
+ *   CHEBYKAN_BASIS_CHEBYSHEV  T_k(tanh x)                     (= chebykan_forward/backward)
+ *   CHEBYKAN_BASIS_LEGENDRE   P_k(tanh x), (k+1)P_{k+1} = (2k+1)u P_k - k P_{k-1}
+ *   CHEBYKAN_BASIS_HERMITE    H_k(tanh x), physicists': H_{k+1} = 2u H_k - 2k H_{k-1}
+ *   CHEBYKAN_BASIS_FOURIER    B_0 = 1, B_{2m-1} = cos(m x), B_{2m} = sin(m x) of the raw
+ *                             input, m = 1..degree/2; degree must be even
+ *
+ *   y[b,o] = sum_i sum_k C[i,o,k] B_k(x[b,i]),  dC[i,o,k] = sum_b B_k(x[b,i]) dy[b,o],
+ *   dx[b,i] = sum_o dy[b,o] sum_k C[i,o,k] dB_k/dx(x[b,i])
+ *
+ * Tensors, layouts, workspace (chebykan_workspace_bytes of the same shape),
+ * ownership, overwrite semantics, reproducibility and errors are those of
+ * chebykan_forward / chebykan_backward; an unknown basis or an odd Fourier degree
+ * gives CHEBYKAN_ERR_SHAPE.  Degrees 3, 4, 5, 6, 8 (Fourier: 4, 6, 8) run on the
+ * matrix-core kernels, every other degree up to CHEBYKAN_MAX_DEGREE on the
+ * any-degree kernels.
+ */
+#define CHEBYKAN_BASIS_CHEBYSHEV 0
+#define CHEBYKAN_BASIS_LEGENDRE 1
+#define CHEBYKAN_BASIS_HERMITE 2
+#define CHEBYKAN_BASIS_FOURIER 3
+chebykan_status chebykan_forward_basis(int basis, const float *x, const float *C, float *y,
+                                       int64_t batch, int in, int out, int degree,
+                                       void *workspace, size_t workspace_bytes, chebykan_stream_t stream);
+chebykan_status chebykan_backward_basis(int basis, const float *x, const float *C, const float *dy,
+                                        float *dx, float *dC,
+                                        int64_t batch, int in, int out, int degree,
+                                        void *workspace, size_t workspace_bytes, chebykan_stream_t stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *chebykan_status_string(chebykan_status status);
 

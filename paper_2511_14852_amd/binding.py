@@ -27,6 +27,7 @@ EXPORTS = (
     "chebykan_status_string", "chebykan_set_kernel_family", "chebykan_version",
     "chebykan_calibrate_mfma", "chebykan_calibrate_copy",
     "chebykan_lut_build", "chebykan_forward_lut", "chebykan_backward_lut",
+    "chebykan_forward_basis", "chebykan_backward_basis",
 )
 
 _lib: Optional[ctypes.CDLL] = None
@@ -62,6 +63,10 @@ def load() -> ctypes.CDLL:
         lib.chebykan_set_kernel_family.restype = ci
         lib.chebykan_version.argtypes = []
         lib.chebykan_version.restype = ci
+        lib.chebykan_forward_basis.argtypes = [ci, vp, vp, vp, i64, ci, ci, ci, vp, sz, vp]
+        lib.chebykan_forward_basis.restype = ci
+        lib.chebykan_backward_basis.argtypes = [ci, vp, vp, vp, vp, vp, i64, ci, ci, ci, vp, sz, vp]
+        lib.chebykan_backward_basis.restype = ci
         lib.chebykan_lut_build.argtypes = [vp, ci, ci]
         lib.chebykan_lut_build.restype = ci
         lib.chebykan_forward_lut.argtypes = [vp, vp, vp, ci, vp, i64, ci, ci, ci, vp, sz, vp]
@@ -250,6 +255,49 @@ def chebykan_backward_lut(x, C, dy, lut, dx, dC, workspace=None, stream=None) ->
                                           B, I, O, K - 1, ws_ptr, ws_bytes, _stream_ptr(stream)))
     if st != CHEBYKAN_OK:
         raise ChebykanError(st, "chebykan_backward_lut")
+
+
+BASIS_CHEBYSHEV, BASIS_LEGENDRE, BASIS_HERMITE, BASIS_FOURIER = 0, 1, 2, 3
+
+
+def chebykan_forward_basis(basis: int, x, C, y, workspace=None, stream=None) -> None:
+    """Forward of the layer on another basis family (BASIS_* constants)."""
+    _check(x, "x")
+    B, I = x.shape
+    _check(C, "C")
+    if C.dim() != 3 or C.shape[0] != I:
+        raise ValueError("C must be [in, out, degree+1]")
+    O, K = int(C.shape[1]), int(C.shape[2])
+    _check(y, "y", (B, O))
+    need = chebykan_workspace_bytes(B, I, O, K - 1, CHEBYKAN_PASS_FORWARD)
+    ws_ptr, ws_bytes = _ws(workspace, need)
+    st = int(load().chebykan_forward_basis(int(basis), x.data_ptr(), C.data_ptr(), y.data_ptr(), B, I, O, K - 1,
+                                           ws_ptr, ws_bytes, _stream_ptr(stream)))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_forward_basis")
+
+
+def chebykan_backward_basis(basis: int, x, C, dy, dx, dC, workspace=None, stream=None) -> None:
+    """dx and/or dC of the layer on another basis family (pass None to skip one)."""
+    _check(x, "x")
+    B, I = x.shape
+    _check(C, "C")
+    if C.dim() != 3 or C.shape[0] != I:
+        raise ValueError("C must be [in, out, degree+1]")
+    O, K = int(C.shape[1]), int(C.shape[2])
+    _check(dy, "dy", (B, O))
+    if dx is not None:
+        _check(dx, "dx", (B, I))
+    if dC is not None:
+        _check(dC, "dC", (I, O, K))
+    need = chebykan_workspace_bytes(B, I, O, K - 1, CHEBYKAN_PASS_BACKWARD)
+    ws_ptr, ws_bytes = _ws(workspace, need)
+    st = int(load().chebykan_backward_basis(int(basis), x.data_ptr(), C.data_ptr(), dy.data_ptr(),
+                                            None if dx is None else dx.data_ptr(),
+                                            None if dC is None else dC.data_ptr(),
+                                            B, I, O, K - 1, ws_ptr, ws_bytes, _stream_ptr(stream)))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_backward_basis")
 
 
 def alloc_workspace(batch: int, n_in: int, n_out: int, degree: int, device="cuda"):

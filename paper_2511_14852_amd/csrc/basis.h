@@ -140,6 +140,121 @@ struct ExactBasis {
     }
 };
 
+// Other KAN bases on the same skeleton (paper Sec. 2.3: alpha_k B_{k+1} = beta_k(x) B_k - gamma_k B_{k-1};
+// Sec. 6.3 reports the method on Fourier, Legendre and Hermite KANs).  The paper prints no
+// formulas for them; the textbook recurrences are used.  In every family B_0 = 1, so the input
+// gradient skips k = 0 exactly as for Chebyshev.  `slope` is the factor the kernels multiply the
+// k-sum with: 1 - tanh(x)^2 for the polynomial families (dT is then dB_k/du), 1 for Fourier
+// (dT is dB_k/dx).
+struct LegendreBasis {   // (k+1) P_{k+1} = (2k+1) u P_k - k P_{k-1};  P'_{k+1} = P'_{k-1} + (2k+1) P_k;  u = tanh x
+    static constexpr bool kTable = false;
+    struct Args {};
+    __device__ LegendreBasis(const Args&, float*, int, int, int) {}
+    template <int D>
+    __device__ __forceinline__ void T(float x, float (&out)[D + 1]) const
+    {
+        const float u = normalise(x);
+        out[0] = 1.0f;
+        if constexpr (D >= 1) out[1] = u;
+#pragma unroll
+        for (int k = 1; k < D; ++k)
+            out[k + 1] = fmaf((float)(2 * k + 1) / (float)(k + 1) * u, out[k], -(float)k / (float)(k + 1) * out[k - 1]);
+    }
+    template <int D>
+    __device__ __forceinline__ void T_dT(float x, float (&t)[D + 1], float (&dt)[D > 0 ? D : 1], float& slope,
+                                         bool) const
+    {
+        const float u = normalise(x, slope);
+        t[0] = 1.0f;
+        if constexpr (D >= 1) { t[1] = u; dt[0] = 1.0f; }
+#pragma unroll
+        for (int k = 1; k < D; ++k) {
+            t[k + 1] = fmaf((float)(2 * k + 1) / (float)(k + 1) * u, t[k], -(float)k / (float)(k + 1) * t[k - 1]);
+            dt[k] = fmaf((float)(2 * k + 1), t[k], k >= 2 ? dt[k - 2] : 0.0f);   // P'_{k+1}; P'_0 = 0
+        }
+    }
+    template <int D>
+    __device__ __forceinline__ void dT(float x, float (&out)[D > 0 ? D : 1], float& slope) const
+    {
+        float t[D + 1];
+        T_dT<D>(x, t, out, slope, true);
+    }
+};
+
+struct HermiteBasis {    // physicists': H_{k+1} = 2 u H_k - 2k H_{k-1};  H'_k = 2k H_{k-1};  u = tanh x
+    static constexpr bool kTable = false;
+    struct Args {};
+    __device__ HermiteBasis(const Args&, float*, int, int, int) {}
+    template <int D>
+    __device__ __forceinline__ void T(float x, float (&out)[D + 1]) const
+    {
+        const float two_u = 2.0f * normalise(x);
+        out[0] = 1.0f;
+        if constexpr (D >= 1) out[1] = two_u;
+#pragma unroll
+        for (int k = 1; k < D; ++k) out[k + 1] = fmaf(two_u, out[k], -(float)(2 * k) * out[k - 1]);
+    }
+    template <int D>
+    __device__ __forceinline__ void T_dT(float x, float (&t)[D + 1], float (&dt)[D > 0 ? D : 1], float& slope,
+                                         bool) const
+    {
+        const float two_u = 2.0f * normalise(x, slope);
+        t[0] = 1.0f;
+        if constexpr (D >= 1) t[1] = two_u;
+#pragma unroll
+        for (int k = 1; k < D; ++k) t[k + 1] = fmaf(two_u, t[k], -(float)(2 * k) * t[k - 1]);
+#pragma unroll
+        for (int k = 1; k <= D; ++k) dt[k - 1] = (float)(2 * k) * t[k - 1];
+    }
+    template <int D>
+    __device__ __forceinline__ void dT(float x, float (&out)[D > 0 ? D : 1], float& slope) const
+    {
+        float t[D + 1];
+        T_dT<D>(x, t, out, slope, true);
+    }
+};
+
+struct FourierBasis {    // B_0 = 1, B_{2m-1} = cos(m x), B_{2m} = sin(m x) on the raw input; D = 2G
+    static constexpr bool kTable = false;
+    struct Args {};
+    __device__ FourierBasis(const Args&, float*, int, int, int) {}
+    // cos(m x), sin(m x) for m = 1..G from cos x, sin x by the angle-addition recurrence (Sec. 2.3)
+    template <int D>
+    __device__ __forceinline__ void T(float x, float (&out)[D + 1]) const
+    {
+        static_assert(D % 2 == 0, "Fourier basis: the degree counts cos/sin pairs");
+        const float c1 = cosf(x), s1 = sinf(x);
+        float c = c1, s = s1;
+        out[0] = 1.0f;
+#pragma unroll
+        for (int m = 1; m <= D / 2; ++m) {
+            out[2 * m - 1] = c;
+            out[2 * m] = s;
+            const float cn = fmaf(c, c1, -s * s1), sn = fmaf(s, c1, c * s1);
+            c = cn;
+            s = sn;
+        }
+    }
+    template <int D>
+    __device__ __forceinline__ void T_dT(float x, float (&t)[D + 1], float (&dt)[D > 0 ? D : 1], float& slope,
+                                         bool) const
+    {
+        T<D>(x, t);
+        slope = 1.0f;
+#pragma unroll
+        for (int m = 1; m <= D / 2; ++m) {
+            dt[2 * m - 2] = -(float)m * t[2 * m];       // d cos(m x)/dx
+            dt[2 * m - 1] = (float)m * t[2 * m - 1];    // d sin(m x)/dx
+        }
+    }
+    template <int D>
+    __device__ __forceinline__ void dT(float x, float (&out)[D > 0 ? D : 1], float& slope) const
+    {
+        float t[D + 1];
+        T_dT<D>(x, t, out, slope, true);
+    }
+};
+
 struct TableBasis {
     static constexpr bool kTable = true;
     struct Args {

@@ -230,4 +230,62 @@ chebykan_status chebykan_backward_lut(const float* x, const float* C, const floa
     return launch_status();
 }
 
+static bool basis_ok(int basis, int degree)
+{
+    if (basis < CHEBYKAN_BASIS_CHEBYSHEV || basis > CHEBYKAN_BASIS_FOURIER) return false;
+    return basis != CHEBYKAN_BASIS_FOURIER || degree % 2 == 0;
+}
+
+chebykan_status chebykan_forward_basis(int basis, const float* x, const float* C, float* y, int64_t batch, int in,
+                                       int out, int degree, void* workspace, size_t workspace_bytes,
+                                       chebykan_stream_t stream)
+{
+    if (basis == CHEBYKAN_BASIS_CHEBYSHEV)
+        return chebykan_forward(x, C, y, batch, in, out, degree, workspace, workspace_bytes, stream);
+    if (!C || (batch != 0 && (!x || !y))) return CHEBYKAN_ERR_NULL;
+    if (!shape_ok(batch, in, out, degree) || !basis_ok(basis, degree)) return CHEBYKAN_ERR_SHAPE;
+    const size_t need = forward_workspace_bytes(batch, in, out, degree);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
+    const chebykan_status dev = check_device();
+    if (dev != CHEBYKAN_OK) return dev;
+    if (batch == 0) return CHEBYKAN_OK;
+    hipStream_t s = (hipStream_t)stream;
+    (void)hipGetLastError();
+    if (g_family != 1 && fast_forward_family(basis, x, C, y, batch, in, out, degree, workspace, s))
+        return launch_status();
+    dim3 block(64, 4), grid((unsigned)((batch + 3) / 4), (unsigned)((out + 63) / 64));
+    hipLaunchKernelGGL(generic_forward_family_kernel, grid, block, 0, s, basis, x, C, y, batch, in, out, degree);
+    return launch_status();
+}
+
+chebykan_status chebykan_backward_basis(int basis, const float* x, const float* C, const float* dy, float* dx,
+                                        float* dC, int64_t batch, int in, int out, int degree, void* workspace,
+                                        size_t workspace_bytes, chebykan_stream_t stream)
+{
+    if (basis == CHEBYKAN_BASIS_CHEBYSHEV)
+        return chebykan_backward(x, C, dy, dx, dC, batch, in, out, degree, workspace, workspace_bytes, stream);
+    if (!C || (batch != 0 && (!x || !dy))) return CHEBYKAN_ERR_NULL;
+    if (!dx && !dC && batch != 0) return CHEBYKAN_ERR_NULL;
+    if (!shape_ok(batch, in, out, degree) || !basis_ok(basis, degree)) return CHEBYKAN_ERR_SHAPE;
+    const size_t need = backward_workspace_bytes(batch, in, out, degree);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
+    const chebykan_status dev = check_device();
+    if (dev != CHEBYKAN_OK) return dev;
+    hipStream_t s = (hipStream_t)stream;
+    (void)hipGetLastError();
+    if (g_family != 1 && batch > 0 &&
+        fast_backward_family(basis, x, C, dy, dx, dC, batch, in, out, degree, workspace, s))
+        return launch_status();
+    if (dx && batch > 0) {
+        dim3 block(64, 4), grid((unsigned)((batch + 3) / 4), (unsigned)((in + 63) / 64));
+        hipLaunchKernelGGL(generic_dx_family_kernel, grid, block, 0, s, basis, x, C, dy, dx, batch, in, out, degree);
+    }
+    if (dC) {
+        const int64_t cnt = (int64_t)in * out * (degree + 1);
+        hipLaunchKernelGGL(generic_dC_family_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, basis, x, dy,
+                           dC, batch, in, out, degree);
+    }
+    return launch_status();
+}
+
 }  // extern "C"

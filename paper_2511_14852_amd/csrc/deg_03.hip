@@ -11,4 +11,13 @@ template void degree_forward<3, TableBasis>(const float*, const float*, float*, 
                                             const TableBasis::Args&, hipStream_t);
 template void degree_backward<3, TableBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
                                              void*, const TableBasis::Args&, hipStream_t);
+// other bases on the same kernels (paper Sec. 2.3)
+template void degree_forward<3, LegendreBasis>(const float*, const float*, float*, int, int, int, void*,
+                                            const LegendreBasis::Args&, hipStream_t);
+template void degree_backward<3, LegendreBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
+                                             void*, const LegendreBasis::Args&, hipStream_t);
+template void degree_forward<3, HermiteBasis>(const float*, const float*, float*, int, int, int, void*,
+                                            const HermiteBasis::Args&, hipStream_t);
+template void degree_backward<3, HermiteBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
+                                             void*, const HermiteBasis::Args&, hipStream_t);
 }  // namespace chebykan

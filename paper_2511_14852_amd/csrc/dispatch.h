@@ -26,4 +26,10 @@ bool fast_forward_table(const float* x, const float* C, const float* lut, int n,
 bool fast_backward_table(const float* x, const float* C, const float* dy, const float* lut, int n, float* dx,
                          float* dC, int64_t B, int I, int O, int d, void* ws, hipStream_t s);
 
+// Other bases (kind 1 Legendre, 2 Hermite, 3 Fourier).  False when the degree has no kernels for the family.
+bool fast_forward_family(int kind, const float* x, const float* C, float* y, int64_t B, int I, int O, int d,
+                         void* ws, hipStream_t s);
+bool fast_backward_family(int kind, const float* x, const float* C, const float* dy, float* dx, float* dC,
+                          int64_t B, int I, int O, int d, void* ws, hipStream_t s);
+
 }  // namespace chebykan

@@ -199,4 +199,109 @@ generic_dC_table_kernel(const float* __restrict__ x, const float* __restrict__ d
     dC[e] = total + (mid + part);
 }
 
+// ------------------------------------------------------------------------------------------
+// Other bases (kind 1 Legendre, 2 Hermite, 3 Fourier; see the policies in basis.h) at any
+// degree up to 32: one thread per output element, the basis of one input evaluated into a
+// small per-thread array.  bv[k] = B_k, db[k] = dB_k/du (dB_k/dx for Fourier), slope = du/dx.
+__device__ inline void family_eval(int kind, float x, int d, float* bv, float* db, float& slope)
+{
+    bv[0] = 1.0f;
+    db[0] = 0.0f;
+    if (kind == 3) {
+        slope = 1.0f;
+        const float c1 = cosf(x), s1 = sinf(x);
+        float c = c1, s = s1;
+        for (int m = 1; m <= d / 2; ++m) {
+            bv[2 * m - 1] = c;
+            bv[2 * m] = s;
+            db[2 * m - 1] = -(float)m * s;
+            db[2 * m] = (float)m * c;
+            const float cn = fmaf(c, c1, -s * s1), sn = fmaf(s, c1, c * s1);
+            c = cn;
+            s = sn;
+        }
+        return;
+    }
+    const float u = normalise(x, slope);
+    if (d >= 1) {
+        bv[1] = kind == 2 ? 2.0f * u : u;
+        db[1] = kind == 2 ? 2.0f : 1.0f;
+    }
+    for (int k = 1; k < d; ++k) {
+        if (kind == 2) {
+            bv[k + 1] = fmaf(2.0f * u, bv[k], -(float)(2 * k) * bv[k - 1]);
+            db[k + 1] = (float)(2 * k + 2) * bv[k];
+        } else {
+            bv[k + 1] = ((float)(2 * k + 1) * u * bv[k] - (float)k * bv[k - 1]) / (float)(k + 1);
+            db[k + 1] = fmaf((float)(2 * k + 1), bv[k], db[k - 1]);
+        }
+    }
+}
+
+constexpr int FAMILY_MAX_K = 33;
+
+__global__ void __launch_bounds__(256)
+generic_forward_family_kernel(int kind, const float* __restrict__ x, const float* __restrict__ C,
+                              float* __restrict__ y, int64_t B, int I, int O, int degree)
+{
+    const int o = blockIdx.y * 64 + threadIdx.x;
+    const int64_t b = (int64_t)blockIdx.x * 4 + threadIdx.y;
+    if (o >= O || b >= B) return;
+    const int K = degree + 1;
+    float bv[FAMILY_MAX_K], db[FAMILY_MAX_K], slope;
+    float total = 0.0f, part = 0.0f;
+    for (int i = 0; i < I; ++i) {
+        family_eval(kind, x[b * I + i], degree, bv, db, slope);
+        const float* cf = C + ((int64_t)i * O + o) * K;
+        float acc = 0.0f;
+        for (int k = 0; k < K; ++k) acc = fmaf(cf[k], bv[k], acc);
+        part += acc;
+        if ((i % GENERIC_FOLD) == GENERIC_FOLD - 1) { total += part; part = 0.0f; }
+    }
+    y[b * O + o] = total + part;
+}
+
+__global__ void __launch_bounds__(256)
+generic_dx_family_kernel(int kind, const float* __restrict__ x, const float* __restrict__ C,
+                         const float* __restrict__ dy, float* __restrict__ dx, int64_t B, int I, int O, int degree)
+{
+    const int i = blockIdx.y * 64 + threadIdx.x;
+    const int64_t b = (int64_t)blockIdx.x * 4 + threadIdx.y;
+    if (i >= I || b >= B) return;
+    const int K = degree + 1;
+    float bv[FAMILY_MAX_K], db[FAMILY_MAX_K], slope;
+    family_eval(kind, x[b * I + i], degree, bv, db, slope);
+    const float* g = dy + b * O;
+    float total = 0.0f, part = 0.0f;
+    for (int o = 0; o < O; ++o) {
+        const float* cf = C + ((int64_t)i * O + o) * K;
+        float inner = 0.0f;
+        for (int k = 1; k < K; ++k) inner = fmaf(cf[k], db[k], inner);
+        part = fmaf(g[o], inner, part);
+        if ((o % GENERIC_FOLD) == GENERIC_FOLD - 1) { total += part; part = 0.0f; }
+    }
+    dx[b * I + i] = slope * (total + part);
+}
+
+__global__ void __launch_bounds__(256)
+generic_dC_family_kernel(int kind, const float* __restrict__ x, const float* __restrict__ dy,
+                         float* __restrict__ dC, int64_t B, int I, int O, int degree)
+{
+    const int K = degree + 1;
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (int64_t)I * O * K) return;
+    const int k = (int)(e % K);
+    const int o = (int)((e / K) % O);
+    const int i = (int)(e / ((int64_t)K * O));
+    float bv[FAMILY_MAX_K], db[FAMILY_MAX_K], slope;
+    float total = 0.0f, mid = 0.0f, part = 0.0f;
+    for (int64_t b = 0; b < B; ++b) {
+        family_eval(kind, x[b * I + i], degree, bv, db, slope);
+        part = fmaf(bv[k], dy[b * O + o], part);
+        if ((b % 64) == 63) { mid += part; part = 0.0f; }
+        if ((b % 4096) == 4095) { total += mid; mid = 0.0f; }
+    }
+    dC[e] = total + (mid + part);
+}
+
 }  // namespace chebykan

@@ -2,6 +2,8 @@
 // runtime degree to the per-degree entry points (each compiled in its own deg_NN.hip).
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "basis.h"
 #include "dispatch.h"
 #include "plans.h"
@@ -29,6 +31,19 @@ CHEBYKAN_FOR_EACH_DEGREE(CHEBYKAN_DECLARE_DEGREE)
                                                         int, int, int, void*, const TableBasis::Args&, hipStream_t);
 CHEBYKAN_FOR_EACH_TABLE_DEGREE(CHEBYKAN_DECLARE_TABLE_DEGREE)
 #undef CHEBYKAN_DECLARE_TABLE_DEGREE
+
+#define CHEBYKAN_DECLARE_FAMILY(n, Basis)                                                                      \
+    extern template void degree_forward<n, Basis>(const float*, const float*, float*, int, int, int, void*,   \
+                                                  const Basis::Args&, hipStream_t);                            \
+    extern template void degree_backward<n, Basis>(const float*, const float*, const float*, float*, float*,  \
+                                                   int, int, int, void*, const Basis::Args&, hipStream_t);
+#define CHEBYKAN_DECLARE_POLY(n) CHEBYKAN_DECLARE_FAMILY(n, LegendreBasis) CHEBYKAN_DECLARE_FAMILY(n, HermiteBasis)
+#define CHEBYKAN_DECLARE_FOURIER(n) CHEBYKAN_DECLARE_FAMILY(n, FourierBasis)
+CHEBYKAN_FOR_EACH_FAMILY_DEGREE(CHEBYKAN_DECLARE_POLY)
+CHEBYKAN_FOR_EACH_FOURIER_DEGREE(CHEBYKAN_DECLARE_FOURIER)
+#undef CHEBYKAN_DECLARE_POLY
+#undef CHEBYKAN_DECLARE_FOURIER
+#undef CHEBYKAN_DECLARE_FAMILY
 
 size_t forward_workspace_bytes(int64_t B, int I, int O, int d)
 {
@@ -103,6 +118,71 @@ bool fast_backward_table(const float* x, const float* C, const float* dy, const 
     case k: degree_backward<k, TableBasis>(x, C, dy, dx, dC, (int)B, I, O, ws, ba, s); return true;
         CHEBYKAN_FOR_EACH_TABLE_DEGREE(CHEBYKAN_BACKWARD_CASE)
 #undef CHEBYKAN_BACKWARD_CASE
+    }
+    return false;
+}
+
+// ---- other bases: same plans and workspace, another basis policy
+template <class Basis>
+static bool family_forward(const float* x, const float* C, float* y, int64_t B, int I, int O, int d, void* ws,
+                           hipStream_t s)
+{
+    const typename Basis::Args ba{};
+    switch (d) {
+#define CHEBYKAN_CASE(k) case k: degree_forward<k, Basis>(x, C, y, (int)B, I, O, ws, ba, s); return true;
+        CHEBYKAN_FOR_EACH_FOURIER_DEGREE(CHEBYKAN_CASE)
+#undef CHEBYKAN_CASE
+    }
+    if constexpr (!std::is_same<Basis, FourierBasis>::value) {
+        switch (d) {
+            case 3: degree_forward<3, Basis>(x, C, y, (int)B, I, O, ws, ba, s); return true;
+            case 5: degree_forward<5, Basis>(x, C, y, (int)B, I, O, ws, ba, s); return true;
+        }
+    }
+    return false;
+}
+
+template <class Basis>
+static bool family_backward(const float* x, const float* C, const float* dy, float* dx, float* dC, int64_t B,
+                            int I, int O, int d, void* ws, hipStream_t s)
+{
+    const typename Basis::Args ba{};
+    switch (d) {
+#define CHEBYKAN_CASE(k) case k: degree_backward<k, Basis>(x, C, dy, dx, dC, (int)B, I, O, ws, ba, s); return true;
+        CHEBYKAN_FOR_EACH_FOURIER_DEGREE(CHEBYKAN_CASE)
+#undef CHEBYKAN_CASE
+    }
+    if constexpr (!std::is_same<Basis, FourierBasis>::value) {
+        switch (d) {
+            case 3: degree_backward<3, Basis>(x, C, dy, dx, dC, (int)B, I, O, ws, ba, s); return true;
+            case 5: degree_backward<5, Basis>(x, C, dy, dx, dC, (int)B, I, O, ws, ba, s); return true;
+        }
+    }
+    return false;
+}
+
+bool fast_forward_family(int kind, const float* x, const float* C, float* y, int64_t B, int I, int O, int d,
+                         void* ws, hipStream_t s)
+{
+    if (!shape_fits(B, I, O, d)) return false;
+    if (forward_workspace_bytes(B, I, O, d) > 0 && !ws) return false;
+    switch (kind) {
+        case 1: return family_forward<LegendreBasis>(x, C, y, B, I, O, d, ws, s);
+        case 2: return family_forward<HermiteBasis>(x, C, y, B, I, O, d, ws, s);
+        case 3: return family_forward<FourierBasis>(x, C, y, B, I, O, d, ws, s);
+    }
+    return false;
+}
+
+bool fast_backward_family(int kind, const float* x, const float* C, const float* dy, float* dx, float* dC,
+                          int64_t B, int I, int O, int d, void* ws, hipStream_t s)
+{
+    if (!shape_fits(B, I, O, d)) return false;
+    if (backward_workspace_bytes(B, I, O, d) > 0 && !ws) return false;
+    switch (kind) {
+        case 1: return family_backward<LegendreBasis>(x, C, dy, dx, dC, B, I, O, d, ws, s);
+        case 2: return family_backward<HermiteBasis>(x, C, dy, dx, dC, B, I, O, d, ws, s);
+        case 3: return family_backward<FourierBasis>(x, C, dy, dx, dC, B, I, O, d, ws, s);
     }
     return false;
 }

@@ -1,8 +1,9 @@
 // Host driver for the CPU emulation build of the library: reads raw fp32 inputs,
 // calls the C ABI (whose launches now run on OS threads), writes raw outputs.
-//   emu_driver <dir> <B> <I> <O> <degree> <family> [lut_size]
+//   emu_driver <dir> <B> <I> <O> <degree> <family> [lut_size [basis]]
 // <dir> holds x.bin, C.bin, dy.bin (and lut.bin when lut_size is given: the table-interpolated
-// entry points are called then); y.bin, dx.bin, dC.bin are written there.
+// entry points are called then; basis 1..3 with lut_size 0 calls the Legendre / Hermite / Fourier entry
+// points); y.bin, dx.bin, dC.bin are written there.
 #include <stdio.h>
 #include <stdlib.h>
 #include <math.h>
@@ -29,8 +30,9 @@ static void write_bin(const std::string& path, const float* p, size_t n)
 
 int main(int argc, char** argv)
 {
-    if (argc != 7 && argc != 8) { fprintf(stderr, "usage: emu_driver dir B I O degree family [lut_size]\n"); return 2; }
-    const int lut_size = argc == 8 ? atoi(argv[7]) : 0;
+    if (argc < 7 || argc > 9) { fprintf(stderr, "usage: emu_driver dir B I O degree family [lut_size [basis]]\n"); return 2; }
+    const int lut_size = argc >= 8 ? atoi(argv[7]) : 0;
+    const int basis = argc >= 9 ? atoi(argv[8]) : 0;
     const std::string dir = argv[1];
     const long B = atol(argv[2]);
     const int I = atoi(argv[3]), O = atoi(argv[4]), d = atoi(argv[5]), family = atoi(argv[6]);
@@ -54,11 +56,11 @@ int main(int argc, char** argv)
     std::vector<float> lut;
     if (lut_size > 0) lut = read_bin(dir + "/lut.bin", K * (size_t)lut_size);
     int rc = lut_size > 0 ? chebykan_forward_lut(x.data(), C.data(), lut.data(), lut_size, y, B, I, O, d, ws, wn, nullptr)
-                          : chebykan_forward(x.data(), C.data(), y, B, I, O, d, ws, wn, nullptr);
+                          : chebykan_forward_basis(basis, x.data(), C.data(), y, B, I, O, d, ws, wn, nullptr);
     if (rc != CHEBYKAN_OK) { fprintf(stderr, "forward: %s\n", chebykan_status_string((chebykan_status)rc)); return 1; }
     rc = lut_size > 0 ? chebykan_backward_lut(x.data(), C.data(), dy.data(), lut.data(), lut_size, dx, dC, B, I, O, d, ws,
                                               wn, nullptr)
-                      : chebykan_backward(x.data(), C.data(), dy.data(), dx, dC, B, I, O, d, ws, wn, nullptr);
+                      : chebykan_backward_basis(basis, x.data(), C.data(), dy.data(), dx, dC, B, I, O, d, ws, wn, nullptr);
     if (rc != CHEBYKAN_OK) { fprintf(stderr, "backward: %s\n", chebykan_status_string((chebykan_status)rc)); return 1; }
     write_bin(dir + "/y.bin", y, (size_t)B * O);
     write_bin(dir + "/dx.bin", dx, (size_t)B * I);

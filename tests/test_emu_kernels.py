@@ -51,7 +51,7 @@ def emu_driver():
     return exe
 
 
-def _run(exe, B, I, O, d, family, seed=1, lut_size=0):
+def _run(exe, B, I, O, d, family, seed=1, lut_size=0, basis=0):
     x = wl.make_x(B, I, seed)
     C = wl.make_coeff(I, O, d, seed + 1)
     dy = wl.make_dy(B, O, seed + 2)
@@ -65,6 +65,8 @@ def _run(exe, B, I, O, d, family, seed=1, lut_size=0):
             lut = oracle.lut_build(d, lut_size).astype(np.float32)
             lut.tofile(os.path.join(td, "lut.bin"))
             args.append(str(lut_size))
+        elif basis:
+            args += ["0", str(basis)]
         r = subprocess.run(args, capture_output=True, text=True, timeout=600)
         assert r.returncode == 0, (r.stdout[-1000:], r.stderr[-4000:])
         y = np.fromfile(os.path.join(td, "y.bin"), dtype=np.float32).reshape(B, O)
@@ -75,6 +77,10 @@ def _run(exe, B, I, O, d, family, seed=1, lut_size=0):
     if lut_size:
         _, dC_ref = oracle.backward_lut(x, C, dy, lut, need_dx=False)
         return (oracle.rel_err(y, oracle.forward_lut(x, C, lut)), dx_error(dx, x, C, dy, lut),
+                oracle.rel_err(dC, dC_ref))
+    if basis:
+        dx_ref, dC_ref = oracle.backward_basis(basis, x, C, dy)
+        return (oracle.rel_err(y, oracle.forward_basis(basis, x, C)), oracle.rel_err(dx, dx_ref),
                 oracle.rel_err(dC, dC_ref))
     dx_ref, dC_ref = oracle.backward(x, C, dy)
     return (oracle.rel_err(y, oracle.forward(x, C)), oracle.rel_err(dx, dx_ref), oracle.rel_err(dC, dC_ref))
@@ -140,4 +146,21 @@ LUT_CASES = [
 def test_table_variant_on_cpu_emulation(emu_driver, case):
     B, I, O, d, n = case
     errs = _run(emu_driver, B, I, O, d, family=2, lut_size=n)
+    assert all(np.isfinite(e) and e <= 1e-5 for e in errs), errs
+
+
+# (B, I, O, degree, basis): Legendre (1), Hermite (2), Fourier (3) on the matrix-core, streaming and any-degree kernels
+BASIS_CASES = [
+    (130, 9, 64, 4, 1),
+    (140, 40, 72, 6, 2),
+    (129, 5, 130, 8, 3),
+    (300, 64, 1, 6, 3),
+    (60, 11, 9, 7, 2),
+]
+
+
+@pytest.mark.parametrize("case", BASIS_CASES, ids=lambda c: "B%d_I%d_O%d_d%d_basis%d" % c)
+def test_other_bases_on_cpu_emulation(emu_driver, case):
+    B, I, O, d, basis = case
+    errs = _run(emu_driver, B, I, O, d, family=2, basis=basis)
     assert all(np.isfinite(e) and e <= 1e-5 for e in errs), errs
