@@ -56,6 +56,9 @@ def parse_args():
                     help="exact = Chebyshev recurrences (default); lut = the paper's table-interpolated variant "
                          "(Sec. 4.2); legendre / hermite / fourier = the other bases of Sec. 2.3 on the same kernels")
     ap.add_argument("--lut-size", type=int, default=1025, help="table samples for --basis lut")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the steps (one per rotated input set) in a HIP graph and time its replays; the "
+                         "first replay is checked against the eager result")
     ap.add_argument("--probe", type=int, default=0,
                     help="counter-collection mode for rocprofv3 --pmc: run this many steps of the split calls plus "
                          "one plain 256 MiB device copy (the calibration kernel of known size), then exit")
@@ -248,11 +251,38 @@ def main():
     for k in range(args.warmup):
         st.step_fused_calls(k)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        st.step_fused_calls(k)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    if args.graph:
+        # one graph holds one step per rotated input set; K steps = K / sets replays (K is rounded up to that)
+        sets = len(st.x0_sets)
+        st.step_fused_calls(0)
+        torch.cuda.synchronize()
+        eager = [t.clone() for t in (st.y[-1], st.dx[0], st.dC[0])]
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=st.stream):
+            for k in range(sets):
+                st.step_fused_calls(k)
+        graph.replay()
+        torch.cuda.synchronize()
+        st.step_fused_calls(sets - 1)          # eager result of the set the graph ended on
+        torch.cuda.synchronize()
+        last = [t.clone() for t in (st.y[-1], st.dx[0], st.dC[0])]
+        replays = (args.steps + sets - 1) // sets
+        args.steps = replays * sets
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        for a, b_ in zip(last, (st.y[-1], st.dx[0], st.dC[0])):
+            if not torch.equal(a, b_):
+                raise RuntimeError("graph replay differs from the eager step")
+        del eager
+    else:
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            st.step_fused_calls(k)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
     # ---- per-call durations: the same steps again with events on the launch stream
@@ -300,7 +330,8 @@ def main():
             w.name, w.note, B, "->".join(map(str, w.widths)), w.degree,
             (", %s basis" % args.basis if kind else "") if lut is None
             else ", table-interpolated basis with %d samples" % args.lut_size),
-            "input_sets_rotated": len(st.x0_sets), "basis": args.basis},
+            "input_sets_rotated": len(st.x0_sets), "basis": args.basis,
+            "launch": "hip graph replay" if args.graph else "eager"},
         "tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
         "algorithmic_gbs": total_bytes / (ms_per_step * 1e-3) / 1e9,
         "mfma_frac": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS,

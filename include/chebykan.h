@@ -172,6 +172,36 @@ chebykan_status chebykan_backward_basis(int basis, const float *x, const float *
                                         int64_t batch, int in, int out, int degree,
                                         void *workspace, size_t workspace_bytes, chebykan_stream_t stream);
 
+/*
+ * Whole stacks in one call (the paper evaluates three-layer Chebyshev-KAN stacks,
+ * Sec. 6.1 Table 2): layer l maps widths[l] -> widths[l+1] inputs, all layers share
+ * `degree`, and the layers are chained directly, act[l+1] = layer_l(act[l]).
+ *
+ * All array arguments are HOST arrays of DEVICE pointers (n_layers or n_layers+1
+ * entries) that the call reads before it returns:
+ *   C[l]    coefficients of layer l                 [widths[l], widths[l+1], degree+1]
+ *   act[l]  activations: act[0] is the input x (read only), act[l+1] receives the
+ *           output of layer l; chebykan_stack_backward reads act[0..n_layers-1]
+ *   grad[l] gradient with respect to act[l]: grad[n_layers] is the incoming dy (read
+ *           only), grad[l] for l < n_layers is written; grad[0] may be NULL when the
+ *           gradient with respect to the stack's input is not wanted
+ *   dC[l]   coefficient gradients, same shape as C[l]; an entry may be NULL (skipped)
+ * The workspace must hold chebykan_stack_workspace_bytes(...) bytes (the largest
+ * per-layer requirement; the layers run one after the other on `stream`).
+ * 1 <= n_layers <= CHEBYKAN_MAX_LAYERS.  Everything else - overwrite semantics,
+ * reproducibility, validation order and error codes - is as for the single-layer
+ * calls; on any error nothing has been enqueued.
+ */
+#define CHEBYKAN_MAX_LAYERS 64
+size_t chebykan_stack_workspace_bytes(int64_t batch, int n_layers, const int *widths, int degree);
+chebykan_status chebykan_stack_forward(int n_layers, const int *widths, int degree, int64_t batch,
+                                       const float *const *C, float *const *act,
+                                       void *workspace, size_t workspace_bytes, chebykan_stream_t stream);
+chebykan_status chebykan_stack_backward(int n_layers, const int *widths, int degree, int64_t batch,
+                                        const float *const *C, const float *const *act,
+                                        float *const *grad, float *const *dC,
+                                        void *workspace, size_t workspace_bytes, chebykan_stream_t stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *chebykan_status_string(chebykan_status status);
 

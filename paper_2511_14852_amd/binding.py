@@ -28,6 +28,7 @@ EXPORTS = (
     "chebykan_calibrate_mfma", "chebykan_calibrate_copy",
     "chebykan_lut_build", "chebykan_forward_lut", "chebykan_backward_lut",
     "chebykan_forward_basis", "chebykan_backward_basis",
+    "chebykan_stack_workspace_bytes", "chebykan_stack_forward", "chebykan_stack_backward",
 )
 
 _lib: Optional[ctypes.CDLL] = None
@@ -63,6 +64,14 @@ def load() -> ctypes.CDLL:
         lib.chebykan_set_kernel_family.restype = ci
         lib.chebykan_version.argtypes = []
         lib.chebykan_version.restype = ci
+        ip = ctypes.POINTER(ctypes.c_int)
+        pp = ctypes.POINTER(ctypes.c_void_p)
+        lib.chebykan_stack_workspace_bytes.argtypes = [i64, ci, ip, ci]
+        lib.chebykan_stack_workspace_bytes.restype = sz
+        lib.chebykan_stack_forward.argtypes = [ci, ip, ci, i64, pp, pp, vp, sz, vp]
+        lib.chebykan_stack_forward.restype = ci
+        lib.chebykan_stack_backward.argtypes = [ci, ip, ci, i64, pp, pp, pp, pp, vp, sz, vp]
+        lib.chebykan_stack_backward.restype = ci
         lib.chebykan_forward_basis.argtypes = [ci, vp, vp, vp, i64, ci, ci, ci, vp, sz, vp]
         lib.chebykan_forward_basis.restype = ci
         lib.chebykan_backward_basis.argtypes = [ci, vp, vp, vp, vp, vp, i64, ci, ci, ci, vp, sz, vp]
@@ -298,6 +307,73 @@ def chebykan_backward_basis(basis: int, x, C, dy, dx, dC, workspace=None, stream
                                             B, I, O, K - 1, ws_ptr, ws_bytes, _stream_ptr(stream)))
     if st != CHEBYKAN_OK:
         raise ChebykanError(st, "chebykan_backward_basis")
+
+
+def _int_array(values):
+    return (ctypes.c_int * len(values))(*[int(v) for v in values])
+
+
+def _ptr_array(tensors):
+    return (ctypes.c_void_p * len(tensors))(*[None if t is None else t.data_ptr() for t in tensors])
+
+
+def chebykan_stack_workspace_bytes(batch: int, widths, degree: int) -> int:
+    return int(load().chebykan_stack_workspace_bytes(int(batch), len(widths) - 1, _int_array(widths), int(degree)))
+
+
+def _stack_shapes(Cs, acts):
+    widths = [int(Cs[0].shape[0])] + [int(c.shape[1]) for c in Cs]
+    K = int(Cs[0].shape[2])
+    B = int(acts[0].shape[0])
+    for l, c in enumerate(Cs):
+        _check(c, "C[%d]" % l, (widths[l], widths[l + 1], K))
+    return widths, K - 1, B
+
+
+def chebykan_stack_forward(Cs, acts, workspace=None, stream=None) -> None:
+    """Forward through a stack: acts[0] is the input, acts[l+1] receives the output of layer l."""
+    widths, degree, B = _stack_shapes(Cs, acts)
+    if len(acts) != len(Cs) + 1:
+        raise ValueError("acts needs one more entry than Cs")
+    for l, a in enumerate(acts):
+        _check(a, "act[%d]" % l, (B, widths[l]))
+    need = chebykan_stack_workspace_bytes(B, widths, degree)
+    ws_ptr, ws_bytes = _ws(workspace, need)
+    st = int(load().chebykan_stack_forward(len(Cs), _int_array(widths), degree, B, _ptr_array(Cs), _ptr_array(acts),
+                                           ws_ptr, ws_bytes, _stream_ptr(stream)))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_stack_forward")
+
+
+def chebykan_stack_backward(Cs, acts, grads, dCs, workspace=None, stream=None) -> None:
+    """Backward through a stack: grads[-1] is the incoming dy; grads[l] (l < n) and dCs[l] are written.
+
+    acts holds the inputs of every layer (n entries, or n+1 with the unused last output);
+    grads[0] and any dCs[l] may be None (skipped)."""
+    widths, degree, B = _stack_shapes(Cs, acts)
+    n = len(Cs)
+    if len(grads) != n + 1 or len(dCs) != n or len(acts) < n:
+        raise ValueError("grads needs n+1 entries, dCs n, acts at least n")
+    for l in range(n):
+        _check(acts[l], "act[%d]" % l, (B, widths[l]))
+        if dCs[l] is not None:
+            _check(dCs[l], "dC[%d]" % l, tuple(Cs[l].shape))
+    for l, g in enumerate(grads):
+        if g is not None:
+            _check(g, "grad[%d]" % l, (B, widths[l]))
+    need = chebykan_stack_workspace_bytes(B, widths, degree)
+    ws_ptr, ws_bytes = _ws(workspace, need)
+    st = int(load().chebykan_stack_backward(n, _int_array(widths), degree, B, _ptr_array(Cs),
+                                            _ptr_array(list(acts[:n])), _ptr_array(grads), _ptr_array(dCs),
+                                            ws_ptr, ws_bytes, _stream_ptr(stream)))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_stack_backward")
+
+
+def alloc_stack_workspace(batch: int, widths, degree: int, device="cuda"):
+    import torch
+    need = chebykan_stack_workspace_bytes(batch, widths, degree)
+    return torch.empty(need, dtype=torch.uint8, device=device) if need else None
 
 
 def alloc_workspace(batch: int, n_in: int, n_out: int, degree: int, device="cuda"):

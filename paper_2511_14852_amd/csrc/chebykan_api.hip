@@ -230,6 +230,73 @@ chebykan_status chebykan_backward_lut(const float* x, const float* C, const floa
     return launch_status();
 }
 
+static bool stack_ok(int n_layers, const int* widths, int degree, int64_t batch)
+{
+    if (n_layers < 1 || n_layers > CHEBYKAN_MAX_LAYERS || !widths) return false;
+    for (int l = 0; l < n_layers; ++l)
+        if (!shape_ok(batch, widths[l], widths[l + 1], degree)) return false;
+    return true;
+}
+
+size_t chebykan_stack_workspace_bytes(int64_t batch, int n_layers, const int* widths, int degree)
+{
+    if (!widths || n_layers < 1 || n_layers > CHEBYKAN_MAX_LAYERS) return 0;
+    size_t need = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const size_t f = chebykan_workspace_bytes(batch, widths[l], widths[l + 1], degree, CHEBYKAN_PASS_FORWARD);
+        const size_t b = chebykan_workspace_bytes(batch, widths[l], widths[l + 1], degree, CHEBYKAN_PASS_BACKWARD);
+        if (f > need) need = f;
+        if (b > need) need = b;
+    }
+    return need;
+}
+
+chebykan_status chebykan_stack_forward(int n_layers, const int* widths, int degree, int64_t batch,
+                                       const float* const* C, float* const* act, void* workspace,
+                                       size_t workspace_bytes, chebykan_stream_t stream)
+{
+    if (!widths || !C || !act) return CHEBYKAN_ERR_NULL;
+    if (n_layers < 1 || n_layers > CHEBYKAN_MAX_LAYERS) return CHEBYKAN_ERR_SHAPE;
+    for (int l = 0; l < n_layers; ++l)
+        if (!C[l] || (batch != 0 && (!act[l] || !act[l + 1]))) return CHEBYKAN_ERR_NULL;
+    if (!stack_ok(n_layers, widths, degree, batch)) return CHEBYKAN_ERR_SHAPE;
+    const size_t need = chebykan_stack_workspace_bytes(batch, n_layers, widths, degree);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
+    const chebykan_status dev = check_device();
+    if (dev != CHEBYKAN_OK) return dev;
+    // every argument is validated: the per-layer calls below can only fail at launch
+    for (int l = 0; l < n_layers; ++l) {
+        const chebykan_status st = chebykan_forward(act[l], C[l], act[l + 1], batch, widths[l], widths[l + 1], degree,
+                                                    workspace, workspace_bytes, stream);
+        if (st != CHEBYKAN_OK) return st;
+    }
+    return CHEBYKAN_OK;
+}
+
+chebykan_status chebykan_stack_backward(int n_layers, const int* widths, int degree, int64_t batch,
+                                        const float* const* C, const float* const* act, float* const* grad,
+                                        float* const* dC, void* workspace, size_t workspace_bytes,
+                                        chebykan_stream_t stream)
+{
+    if (!widths || !C || !act || !grad || !dC) return CHEBYKAN_ERR_NULL;
+    if (n_layers < 1 || n_layers > CHEBYKAN_MAX_LAYERS) return CHEBYKAN_ERR_SHAPE;
+    for (int l = 0; l < n_layers; ++l) {
+        if (!C[l] || (batch != 0 && (!act[l] || !grad[l + 1]))) return CHEBYKAN_ERR_NULL;
+        if (l == 0 && !grad[0] && !dC[0] && batch != 0) return CHEBYKAN_ERR_NULL;   // layer 0 would have nothing to do
+    }
+    if (!stack_ok(n_layers, widths, degree, batch)) return CHEBYKAN_ERR_SHAPE;
+    const size_t need = chebykan_stack_workspace_bytes(batch, n_layers, widths, degree);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
+    const chebykan_status dev = check_device();
+    if (dev != CHEBYKAN_OK) return dev;
+    for (int l = n_layers - 1; l >= 0; --l) {
+        const chebykan_status st = chebykan_backward(act[l], C[l], grad[l + 1], grad[l], dC[l], batch, widths[l],
+                                                     widths[l + 1], degree, workspace, workspace_bytes, stream);
+        if (st != CHEBYKAN_OK) return st;
+    }
+    return CHEBYKAN_OK;
+}
+
 static bool basis_ok(int basis, int degree)
 {
     if (basis < CHEBYKAN_BASIS_CHEBYSHEV || basis > CHEBYKAN_BASIS_FOURIER) return false;

@@ -1,0 +1,95 @@
+"""Stack-level entry points and the autograd wrapper against the fp64 oracle (GPU)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_14852_amd import binding, workloads as wl
+from paper_2511_14852_amd.autograd import ChebyKANStack, ChebyKANStackFunction
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+def _oracle_stack(x0, Cs, dy_last):
+    """Layer by layer in fp64 on the oracle's own activations."""
+    xs = [x0.astype(np.float64)]
+    for C in Cs:
+        xs.append(oracle.forward(xs[-1], C))
+    grads, dCs = [None] * len(Cs) + [dy_last.astype(np.float64)], []
+    for l in reversed(range(len(Cs))):
+        dx, dC = oracle.backward(xs[l], Cs[l], grads[l + 1])
+        grads[l] = dx
+        dCs.insert(0, dC)
+    return xs, grads, dCs
+
+
+@pytest.mark.parametrize("widths,degree,B", [((8, 64, 64, 1), 6, 700), ((20, 33, 9), 5, 300), ((64, 64), 4, 256),
+                                              ((12, 40, 24, 16, 5), 3, 130)])
+def test_stack_calls_against_the_oracle(widths, degree, B):
+    x0 = wl.make_x(B, widths[0], 11)
+    Cs = [wl.make_coeff(i, o, degree, 20 + l) for l, (i, o) in enumerate(zip(widths[:-1], widths[1:]))]
+    dy = wl.make_dy(B, widths[-1], 13)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    Cd = [dev(c) for c in Cs]
+    acts = [dev(x0)] + [torch.full((B, w), float("nan"), device="cuda") for w in widths[1:]]
+    ws = binding.alloc_stack_workspace(B, widths, degree)
+    binding.chebykan_stack_forward(Cd, acts, ws)
+    grads = [torch.full((B, w), float("nan"), device="cuda") for w in widths[:-1]] + [dev(dy)]
+    dCd = [torch.full_like(c, float("nan")) for c in Cd]
+    binding.chebykan_stack_backward(Cd, acts, grads, dCd, ws)
+    torch.cuda.synchronize()
+    xs, g_ref, dC_ref = _oracle_stack(x0, Cs, dy)
+    # end-to-end comparison: errors of earlier layers propagate, so the bar is per layer times the depth
+    depth = len(Cs)
+    for l in range(depth):
+        assert oracle.rel_err(acts[l + 1].cpu().numpy(), xs[l + 1]) <= TOL * (l + 1)
+        assert oracle.rel_err(grads[l].cpu().numpy(), g_ref[l]) <= TOL * (2 * depth - l)
+        assert oracle.rel_err(dCd[l].cpu().numpy(), dC_ref[l]) <= TOL * (2 * depth - l)
+    # the stack call is the chained single-layer calls, bit for bit
+    y = acts[0]
+    for l, c in enumerate(Cd):
+        out = torch.empty((B, widths[l + 1]), device="cuda")
+        binding.chebykan_forward(y, c, out, binding.alloc_workspace(B, widths[l], widths[l + 1], degree))
+        y = out
+    torch.cuda.synchronize()
+    assert torch.equal(y, acts[-1])
+
+
+def test_stack_skips_and_errors():
+    widths, degree, B = (8, 16, 4), 4, 64
+    Cd = [torch.from_numpy(wl.make_coeff(i, o, degree, 5)).cuda() for i, o in zip(widths[:-1], widths[1:])]
+    acts = [torch.randn(B, widths[0], device="cuda")] + [torch.empty(B, w, device="cuda") for w in widths[1:]]
+    binding.chebykan_stack_forward(Cd, acts, binding.alloc_stack_workspace(B, widths, degree))
+    grads = [None, torch.empty(B, widths[1], device="cuda"), torch.randn(B, widths[2], device="cuda")]
+    dCs = [torch.empty_like(Cd[0]), None]
+    binding.chebykan_stack_backward(Cd, acts, grads, dCs, binding.alloc_stack_workspace(B, widths, degree))
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(dCs[0]).all())
+    with pytest.raises(binding.ChebykanError):       # first layer with neither output
+        binding.chebykan_stack_backward(Cd, acts, grads, [None, None], binding.alloc_stack_workspace(B, widths, degree))
+    lib = binding.load()
+    assert lib.chebykan_stack_forward(0, None, degree, B, None, None, None, 0, None) == binding.CHEBYKAN_ERR_NULL
+
+
+def test_autograd_wrapper_matches_the_oracle_gradients():
+    widths, degree, B = (10, 48, 24, 3), 5, 200
+    torch.manual_seed(0)
+    model = ChebyKANStack(widths, degree)
+    x = torch.randn(B, widths[0], device="cuda", requires_grad=True)
+    y = model(x)
+    w = torch.randn_like(y)
+    (y * w).sum().backward()
+    Cs = [p.detach().cpu().numpy() for p in model.coeffs]
+    xs, g_ref, dC_ref = _oracle_stack(x.detach().cpu().numpy(), Cs, w.cpu().numpy())
+    assert oracle.rel_err(y.detach().cpu().numpy(), xs[-1]) <= 3 * TOL
+    assert oracle.rel_err(x.grad.cpu().numpy(), g_ref[0]) <= 6 * TOL
+    for p, ref in zip(model.coeffs, dC_ref):
+        assert oracle.rel_err(p.grad.cpu().numpy(), ref) <= 6 * TOL
+    # no gradient for the input requested: dx of the first layer is skipped
+    x2 = x.detach().clone()
+    for p in model.coeffs:
+        p.grad = None
+    (ChebyKANStackFunction.apply(x2, *model.coeffs) * w).sum().backward()
+    for p, ref in zip(model.coeffs, dC_ref):
+        assert oracle.rel_err(p.grad.cpu().numpy(), ref) <= 6 * TOL
