@@ -291,3 +291,19 @@ def test_full_size_workload_sampled(name):
         _sampled_layer_check(xs[l], Cs[l], dys[l], y, dx, dC, rng, "%s layer %d %s" % (name, l, w.layers[l]))
         if l > 0:
             dys[l - 1] = dx
+
+
+def test_calibration_entry_points():
+    """The roofline calibration kernels: the copy copies, the MFMA loop reports its flop count and finishes."""
+    src = torch.randn(1 << 20, device="cuda")
+    dst = torch.zeros_like(src)
+    assert binding.chebykan_calibrate_copy(dst, src) == src.numel() * 4
+    sink = torch.full((8 * 256,), float("nan"), device="cuda")
+    flops = binding.chebykan_calibrate_mfma(sink, 8, 10)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    assert flops == 8 * 4 * 10 * 32 * 4096.0
+    assert bool(torch.isfinite(sink).all())
+    lib = binding.load()
+    assert lib.chebykan_calibrate_copy(dst.data_ptr(), src.data_ptr(), 3, None) == binding.CHEBYKAN_ERR_SHAPE
+    assert lib.chebykan_calibrate_mfma(None, 8, 10, None, None) == binding.CHEBYKAN_ERR_NULL
