@@ -90,6 +90,7 @@ class Stack:
         self.dC = [torch.empty_like(c) for c in self.C]
         self.ws = [binding.alloc_workspace(B, i, o, self.d) for (i, o) in self.layers]
         self.stream = torch.cuda.Stream()
+        self.stack_ws = binding.alloc_stack_workspace(B, list(w.widths), self.d)
 
     def _fwd(self, xin, l, s):
         b = self.binding
@@ -127,14 +128,18 @@ class Stack:
         return out
 
     def step_fused_calls(self, step):
-        """One step as a user would issue it: one forward and one backward call per layer."""
+        """One step as a user would issue it: the stack's forward call (the library runs a narrow stack in
+        one kernel, any other stack layer by layer), then one backward call per layer."""
         b, n = self.binding, len(self.layers)
         x0 = self.x0_sets[step % len(self.x0_sets)]
         dyl = self.dy_sets[step % len(self.dy_sets)]
         s = self.stream
-        for l in range(n):
-            xin = x0 if l == 0 else self.y[l - 1]
-            self._fwd(xin, l, s)
+        if self.lut is None and not self.kind:
+            b.chebykan_stack_forward(self.C, [x0] + self.y, self.stack_ws, s)
+        else:
+            for l in range(n):
+                xin = x0 if l == 0 else self.y[l - 1]
+                self._fwd(xin, l, s)
         for l in reversed(range(n)):
             xin = x0 if l == 0 else self.y[l - 1]
             dy = dyl if l == n - 1 else self.dx[l + 1]

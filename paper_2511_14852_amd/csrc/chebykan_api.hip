@@ -264,6 +264,11 @@ chebykan_status chebykan_stack_forward(int n_layers, const int* widths, int degr
     if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
     const chebykan_status dev = check_device();
     if (dev != CHEBYKAN_OK) return dev;
+    if (batch == 0) return CHEBYKAN_OK;
+    // narrow stacks run all layers in one kernel, each workgroup keeping its rows' activations in LDS
+    (void)hipGetLastError();
+    if (g_family != 1 && fast_chain_forward(n_layers, widths, degree, batch, C, act, (hipStream_t)stream))
+        return launch_status();
     // every argument is validated: the per-layer calls below can only fail at launch
     for (int l = 0; l < n_layers; ++l) {
         const chebykan_status st = chebykan_forward(act[l], C[l], act[l + 1], batch, widths[l], widths[l + 1], degree,

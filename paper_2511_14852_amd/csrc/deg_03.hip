@@ -20,4 +20,6 @@ template void degree_forward<3, HermiteBasis>(const float*, const float*, float*
                                             const HermiteBasis::Args&, hipStream_t);
 template void degree_backward<3, HermiteBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
                                              void*, const HermiteBasis::Args&, hipStream_t);
+// forward of a narrow stack in one launch
+template void degree_chain_forward<3>(const ChainArgs&, int, hipStream_t);
 }  // namespace chebykan

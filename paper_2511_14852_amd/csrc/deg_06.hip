@@ -24,4 +24,6 @@ template void degree_forward<6, FourierBasis>(const float*, const float*, float*
                                             const FourierBasis::Args&, hipStream_t);
 template void degree_backward<6, FourierBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
                                              void*, const FourierBasis::Args&, hipStream_t);
+// forward of a narrow stack in one launch
+template void degree_chain_forward<6>(const ChainArgs&, int, hipStream_t);
 }  // namespace chebykan

@@ -4,6 +4,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include "chain_kernels.h"
 #include "mfma_kernels.h"
 #include "narrow_kernels.h"
 #include "plans.h"
@@ -228,6 +229,17 @@ void narrow_bwd_by_out(const float* x, const float* C, const float* dy, float* d
         case 3: launch_narrow_bwd<D, 3, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s); break;
         default: launch_narrow_bwd<D, 4, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s); break;
     }
+}
+
+// ------------------------------------------------------------ fused narrow stack
+// Forward of a whole stack in one launch; the caller has checked chain_eligible().
+template <int D>
+void degree_chain_forward(const ChainArgs& a, int B, hipStream_t s)
+{
+    static bool once = (allow_lds(fwd_chain_kernel<D>, chain_lds_bytes<D>()), true);
+    (void)once;
+    hipLaunchKernelGGL(fwd_chain_kernel<D>, dim3((unsigned)((B + 127) / 128)), dim3(MFMA_THREADS),
+                       (size_t)chain_lds_bytes<D>(), s, a, B);
 }
 
 // ------------------------------------------------------- per-degree entry points

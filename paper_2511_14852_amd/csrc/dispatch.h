@@ -26,6 +26,11 @@ bool fast_forward_table(const float* x, const float* C, const float* lut, int n,
 bool fast_backward_table(const float* x, const float* C, const float* dy, const float* lut, int n, float* dx,
                          float* dC, int64_t B, int I, int O, int d, void* ws, hipStream_t s);
 
+// Forward of a whole narrow stack in one launch (act[0] input, act[l+1] output of layer l).  False when
+// the stack is not eligible (then nothing is enqueued and the caller runs the layers one by one).
+bool fast_chain_forward(int n_layers, const int* widths, int d, int64_t B, const float* const* C, float* const* act,
+                        hipStream_t s);
+
 // Other bases (kind 1 Legendre, 2 Hermite, 3 Fourier).  False when the degree has no kernels for the family.
 bool fast_forward_family(int kind, const float* x, const float* C, float* y, int64_t B, int I, int O, int d,
                          void* ws, hipStream_t s);

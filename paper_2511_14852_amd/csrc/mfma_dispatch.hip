@@ -5,6 +5,7 @@
 #include <type_traits>
 
 #include "basis.h"
+#include "chain_kernels.h"
 #include "dispatch.h"
 #include "plans.h"
 
@@ -44,6 +45,12 @@ CHEBYKAN_FOR_EACH_FOURIER_DEGREE(CHEBYKAN_DECLARE_FOURIER)
 #undef CHEBYKAN_DECLARE_POLY
 #undef CHEBYKAN_DECLARE_FOURIER
 #undef CHEBYKAN_DECLARE_FAMILY
+
+template <int D>
+void degree_chain_forward(const ChainArgs& a, int B, hipStream_t s);
+#define CHEBYKAN_DECLARE_CHAIN(n) extern template void degree_chain_forward<n>(const ChainArgs&, int, hipStream_t);
+CHEBYKAN_FOR_EACH_CHAIN_DEGREE(CHEBYKAN_DECLARE_CHAIN)
+#undef CHEBYKAN_DECLARE_CHAIN
 
 size_t forward_workspace_bytes(int64_t B, int I, int O, int d)
 {
@@ -118,6 +125,41 @@ bool fast_backward_table(const float* x, const float* C, const float* dy, const 
     case k: degree_backward<k, TableBasis>(x, C, dy, dx, dC, (int)B, I, O, ws, ba, s); return true;
         CHEBYKAN_FOR_EACH_TABLE_DEGREE(CHEBYKAN_BACKWARD_CASE)
 #undef CHEBYKAN_BACKWARD_CASE
+    }
+    return false;
+}
+
+// ---- forward of a narrow stack in one launch
+// Eligible: at least two layers, every width after the input at most 64 (a 128-row tile of one
+// layer's output is the next layer's whole input tile), enough rows to fill the GPU with one
+// workgroup per 128 rows, vector loads possible for every matrix-core layer; a last layer of
+// 1..4 outputs is finished on the vector ALUs.
+bool chain_eligible(int n_layers, const int* widths, int d, int64_t B, const float* const* C)
+{
+    if ((tune_flags() & 256) || !chain_degree(d) || n_layers < 2 || n_layers > CHAIN_MAX_LAYERS) return false;
+    if ((B < 128 * 256 && !(tune_flags() & 512)) || B > 0x7fffffff) return false;   // bit 9: any batch (tests)
+    if ((int64_t)B * (widths[0] > CHAIN_WIDTH ? widths[0] : CHAIN_WIDTH) >= ((int64_t)1 << 30)) return false;
+    for (int l = 0; l < n_layers; ++l) {
+        const int O = widths[l + 1];
+        if (O > CHAIN_WIDTH || widths[l] > 65535) return false;
+        const bool narrow_last = l == n_layers - 1 && O <= 4;
+        if (!narrow_last && (!aligned16(C[l]) || ((int64_t)O * (d + 1)) % 4 != 0)) return false;
+    }
+    return true;
+}
+
+bool fast_chain_forward(int n_layers, const int* widths, int d, int64_t B, const float* const* C, float* const* act,
+                        hipStream_t s)
+{
+    if (!chain_eligible(n_layers, widths, d, B, C)) return false;
+    ChainArgs a;
+    a.n_layers = n_layers;
+    for (int l = 0; l < n_layers; ++l) a.C[l] = C[l];
+    for (int l = 0; l <= n_layers; ++l) { a.act[l] = act[l]; a.width[l] = widths[l]; }
+    switch (d) {
+#define CHEBYKAN_CHAIN_CASE(k) case k: degree_chain_forward<k>(a, (int)B, s); return true;
+        CHEBYKAN_FOR_EACH_CHAIN_DEGREE(CHEBYKAN_CHAIN_CASE)
+#undef CHEBYKAN_CHAIN_CASE
     }
     return false;
 }

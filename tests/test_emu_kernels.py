@@ -32,7 +32,8 @@ def emu_driver():
     os.makedirs(out_dir, exist_ok=True)
     exe = os.path.join(out_dir, "emu_driver")
     hip_srcs = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
-    srcs = hip_srcs + [os.path.join(EMU, "emu_state.cpp"), os.path.join(EMU, "emu_driver.cpp")]
+    srcs = hip_srcs + [os.path.join(EMU, "emu_state.cpp"), os.path.join(EMU, "emu_driver.cpp"),
+                       os.path.join(EMU, "emu_stack_driver.cpp")]
     deps = srcs + [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(EMU, "shim", "hip", "hip_runtime.h")]
     if not os.path.exists(exe) or os.path.getmtime(exe) < max(os.path.getmtime(p) for p in deps):
         from concurrent.futures import ThreadPoolExecutor
@@ -46,8 +47,13 @@ def emu_driver():
 
         with ThreadPoolExecutor(max_workers=8) as pool:
             objs = list(pool.map(compile_one, srcs))
-        subprocess.run([CLANG, "-fsanitize=address", *objs, "-o", exe + ".tmp", "-lpthread"], check=True, cwd=EMU)
-        os.replace(exe + ".tmp", exe)
+        drivers = {"emu_driver": "emu_driver.cpp.o", "emu_stack_driver": "emu_stack_driver.cpp.o"}
+        shared = [o for o in objs if os.path.basename(o) not in drivers.values()]
+        for name, obj in drivers.items():
+            out = os.path.join(out_dir, name)
+            subprocess.run([CLANG, "-fsanitize=address", *shared, os.path.join(out_dir, obj), "-o", out + ".tmp",
+                            "-lpthread"], check=True, cwd=EMU)
+            os.replace(out + ".tmp", out)
     return exe
 
 
@@ -164,3 +170,38 @@ def test_other_bases_on_cpu_emulation(emu_driver, case):
     B, I, O, d, basis = case
     errs = _run(emu_driver, B, I, O, d, family=2, basis=basis)
     assert all(np.isfinite(e) and e <= 1e-5 for e in errs), errs
+
+
+# (B, widths, degree): forward of a narrow stack in one kernel (forced at these small batches): ragged
+# last row tile, narrow and matrix-core last layers, a hidden width below 64
+STACK_CASES = [
+    (200, (8, 64, 64, 1), 6),
+    (150, (9, 16, 48, 3), 4),
+    (129, (5, 64, 12), 3),
+]
+
+
+@pytest.mark.parametrize("case", STACK_CASES, ids=lambda c: "B%d_%s_d%d" % (c[0], "x".join(map(str, c[1])), c[2]))
+def test_fused_stack_forward_on_cpu_emulation(emu_driver, case):
+    B, widths, d = case
+    exe = os.path.join(os.path.dirname(emu_driver), "emu_stack_driver")
+    x = wl.make_x(B, widths[0], 77)
+    Cs = [wl.make_coeff(i, o, d, 80 + l) for l, (i, o) in enumerate(zip(widths[:-1], widths[1:]))]
+    td = tempfile.mkdtemp(prefix="emu_")
+    try:
+        x.tofile(os.path.join(td, "x.bin"))
+        for l, c in enumerate(Cs):
+            c.tofile(os.path.join(td, "C%d.bin" % l))
+        env = dict(os.environ, CHEBYKAN_TUNE="512")
+        r = subprocess.run([exe, td, str(B), str(d), str(len(Cs)), *map(str, widths)], capture_output=True, text=True,
+                           timeout=600, env=env)
+        assert r.returncode == 0, (r.stdout[-1000:], r.stderr[-4000:])
+        ys = [np.fromfile(os.path.join(td, "y%d.bin" % l), dtype=np.float32).reshape(B, widths[l + 1])
+              for l in range(len(Cs))]
+    finally:
+        shutil.rmtree(td, ignore_errors=True)
+    xin = x
+    for l, c in enumerate(Cs):             # per layer, on the kernel's own fp32 layer input
+        err = oracle.rel_err(ys[l], oracle.forward(xin, c))
+        assert np.isfinite(err) and err <= 1e-5, (l, err)
+        xin = ys[l]

@@ -24,8 +24,12 @@ def _oracle_stack(x0, Cs, dy_last):
     return xs, grads, dCs
 
 
+# the last four are large and narrow enough for the single-launch forward (all hidden widths <= 64,
+# >= 32768 rows): ragged last row tile, a narrow and a matrix-core last layer, every fused degree
 @pytest.mark.parametrize("widths,degree,B", [((8, 64, 64, 1), 6, 700), ((20, 33, 9), 5, 300), ((64, 64), 4, 256),
-                                              ((12, 40, 24, 16, 5), 3, 130)])
+                                              ((12, 40, 24, 16, 5), 3, 130),
+                                              ((8, 64, 64, 1), 6, 32768 + 77), ((70, 64, 32), 5, 32768),
+                                              ((9, 16, 48, 3), 4, 33000), ((5, 64, 64, 64, 12), 3, 32800)])
 def test_stack_calls_against_the_oracle(widths, degree, B):
     x0 = wl.make_x(B, widths[0], 11)
     Cs = [wl.make_coeff(i, o, degree, 20 + l) for l, (i, o) in enumerate(zip(widths[:-1], widths[1:]))]
@@ -39,21 +43,26 @@ def test_stack_calls_against_the_oracle(widths, degree, B):
     dCd = [torch.full_like(c, float("nan")) for c in Cd]
     binding.chebykan_stack_backward(Cd, acts, grads, dCd, ws)
     torch.cuda.synchronize()
-    xs, g_ref, dC_ref = _oracle_stack(x0, Cs, dy)
-    # end-to-end comparison: errors of earlier layers propagate, so the bar is per layer times the depth
-    depth = len(Cs)
-    for l in range(depth):
-        assert oracle.rel_err(acts[l + 1].cpu().numpy(), xs[l + 1]) <= TOL * (l + 1)
-        assert oracle.rel_err(grads[l].cpu().numpy(), g_ref[l]) <= TOL * (2 * depth - l)
-        assert oracle.rel_err(dCd[l].cpu().numpy(), dC_ref[l]) <= TOL * (2 * depth - l)
-    # the stack call is the chained single-layer calls, bit for bit
+    # per layer, on the GPU's own fp32 layer inputs (an end-to-end comparison would measure how the
+    # network amplifies rounding differences of earlier layers, not the kernels)
+    for l in range(len(Cs)):
+        x_l, g_l = acts[l].cpu().numpy(), grads[l + 1].cpu().numpy()
+        assert oracle.rel_err(acts[l + 1].cpu().numpy(), oracle.forward(x_l, Cs[l])) <= TOL
+        dx_ref, dC_ref = oracle.backward(x_l, Cs[l], g_l)
+        assert oracle.rel_err(grads[l].cpu().numpy(), dx_ref) <= TOL
+        assert oracle.rel_err(dCd[l].cpu().numpy(), dC_ref) <= TOL
+    # against the chained single-layer calls: bit for bit when the stack call issues the same launches,
+    # within rounding when it runs the layers in one kernel (other chunking of the contraction)
     y = acts[0]
     for l, c in enumerate(Cd):
         out = torch.empty((B, widths[l + 1]), device="cuda")
         binding.chebykan_forward(y, c, out, binding.alloc_workspace(B, widths[l], widths[l + 1], degree))
         y = out
     torch.cuda.synchronize()
-    assert torch.equal(y, acts[-1])
+    if B < 32768:
+        assert torch.equal(y, acts[-1])
+    else:
+        assert oracle.rel_err(acts[-1].cpu().numpy(), y.cpu().numpy().astype(np.float64)) <= TOL
 
 
 def test_stack_skips_and_errors():
