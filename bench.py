@@ -130,16 +130,23 @@ class Stack:
     def step_fused_calls(self, step):
         """One step as a user would issue it: the stack's forward call (the library runs a narrow stack in
         one kernel, any other stack layer by layer), then one backward call per layer."""
-        b, n = self.binding, len(self.layers)
+        self.step_forward(step)
+        self.step_backward(step)
+
+    def step_forward(self, step):
+        b, n, s = self.binding, len(self.layers), self.stream
         x0 = self.x0_sets[step % len(self.x0_sets)]
-        dyl = self.dy_sets[step % len(self.dy_sets)]
-        s = self.stream
         if self.lut is None and not self.kind:
             b.chebykan_stack_forward(self.C, [x0] + self.y, self.stack_ws, s)
         else:
             for l in range(n):
                 xin = x0 if l == 0 else self.y[l - 1]
                 self._fwd(xin, l, s)
+
+    def step_backward(self, step):
+        n, s = len(self.layers), self.stream
+        x0 = self.x0_sets[step % len(self.x0_sets)]
+        dyl = self.dy_sets[step % len(self.dy_sets)]
         for l in reversed(range(n)):
             xin = x0 if l == 0 else self.y[l - 1]
             dy = dyl if l == n - 1 else self.dx[l + 1]
@@ -290,6 +297,21 @@ def main():
         wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
+    # ---- whole steps with events: median / min per step, forward and backward apart
+    nst = min(args.steps, 50)
+    sev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(nst)]
+    for k in range(nst):
+        sev[k][0].record(st.stream)
+        st.step_forward(k)
+        sev[k][1].record(st.stream)
+        st.step_backward(k)
+        sev[k][2].record(st.stream)
+    torch.cuda.synchronize()
+    fwd_ms = np.array([sev[k][0].elapsed_time(sev[k][1]) for k in range(nst)])
+    bwd_ms = np.array([sev[k][1].elapsed_time(sev[k][2]) for k in range(nst)])
+    step_stats = {"steps": nst, "step_ms_median": float(np.median(fwd_ms + bwd_ms)), "step_ms_min": float(np.min(fwd_ms + bwd_ms)),
+                  "forward_ms_median": float(np.median(fwd_ms)), "backward_ms_median": float(np.median(bwd_ms))}
+
     # ---- per-call durations: the same steps again with events on the launch stream
     n_calls = len(st.calls(0))
     ksteps = min(args.steps, 50)
@@ -342,6 +364,7 @@ def main():
         "mfma_frac": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS,
         "hbm_frac": total_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "roofline": roof,
+        "event_timed": step_stats,
         "calls": per_call,
     }
     line["measured_peaks"] = measured_peaks(torch, binding, st.stream)
