@@ -6,6 +6,7 @@
 
 #include "chain_kernels.h"
 #include "mfma_kernels.h"
+#include "narrow_in_kernels.h"
 #include "narrow_kernels.h"
 #include "plans.h"
 
@@ -73,6 +74,20 @@ void pick_fwd(const float* x, const float* C, float* y, float* partial, int B, i
 }
 
 // --------------------------------------------------------------------- dC
+template <int D>
+void launch_dC_combine(const float* partial, float* dC, int I, int O, int slices, hipStream_t s)
+{
+    const dim3 grid((unsigned)((O + 31) / 32), (unsigned)I);
+    static bool once = (allow_lds(dC_combine_kernel<D, 32>, 1024 * ((D + 1) | 1) * (int)sizeof(float)), true);
+    (void)once;
+    if (slices > 32)
+        hipLaunchKernelGGL((dC_combine_kernel<D, 32>), grid, dim3(1024), 1024 * ((D + 1) | 1) * sizeof(float), s,
+                           partial, dC, I, O, slices);
+    else
+        hipLaunchKernelGGL((dC_combine_kernel<D, 8>), grid, dim3(256), 256 * ((D + 1) | 1) * sizeof(float), s,
+                           partial, dC, I, O, slices);
+}
+
 template <int D, int BN, int VEC, int BIC, class Basis>
 void launch_dC(const float* x, const float* dy, float* partial, int B, int I, int O, const DcPlan& p,
                const typename Basis::Args& ba, hipStream_t s)
@@ -111,15 +126,7 @@ void pick_dC(const float* x, const float* dy, float* dC, float* partial, int B, 
     } else {
         pick_dC_tile<D, dc_tile_features(D), Basis>(x, dy, partial, B, I, O, p, ba, s);
     }
-    const dim3 grid((unsigned)((O + 31) / 32), (unsigned)I);
-    static bool once = (allow_lds(dC_combine_kernel<D, 32>, 1024 * ((D + 1) | 1) * (int)sizeof(float)), true);
-    (void)once;
-    if (p.slices > 32)
-        hipLaunchKernelGGL((dC_combine_kernel<D, 32>), grid, dim3(1024), 1024 * ((D + 1) | 1) * sizeof(float), s,
-                           partial, dC, I, O, p.slices);
-    else
-        hipLaunchKernelGGL((dC_combine_kernel<D, 8>), grid, dim3(256), 256 * ((D + 1) | 1) * sizeof(float), s,
-                           partial, dC, I, O, p.slices);
+    launch_dC_combine<D>(partial, dC, I, O, p.slices, s);
 }
 
 // --------------------------------------------------------------------- dx
@@ -259,6 +266,17 @@ void degree_backward(const float* x, const float* C, const float* dy, float* dx,
     float* partial = static_cast<float*>(ws);
     if (use_narrow(B, I, O, D)) {
         narrow_bwd_by_out<D, Basis>(x, C, dy, dx, dC, partial, B, I, O, ba, s);
+        return;
+    }
+    if (dx && dC && use_narrow_in(B, I, O, D)) {   // few inputs, both gradients wanted: one kernel for both
+        const NarrowInPlan p = plan_narrow_in(B);
+        static bool once = (allow_lds(bwd_narrow_in_kernel<D, Basis>, Basis::kTable ? MAX_LDS_BYTES : NIN_LDS_BYTES),
+                            true);
+        (void)once;
+        hipLaunchKernelGGL((bwd_narrow_in_kernel<D, Basis>), dim3((unsigned)p.slices), dim3(MFMA_THREADS),
+                           NIN_LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy, dx, dC ? partial : nullptr, B,
+                           I, O, p.rows_per_slice, ba);
+        if (dC) launch_dC_combine<D>(partial, dC, I, O, p.slices, s);
         return;
     }
     // the dx partials are summed before the dC kernel reuses the workspace (same stream)

@@ -67,7 +67,12 @@ size_t backward_workspace_bytes(int64_t B, int I, int O, int d)
     const size_t for_dC = (size_t)plan_dC(B, I, O, d).slices * coeffs;
     const DxPlan dxp = plan_dx(B, I, O, d);
     const size_t for_dx = dxp.split.splits > 1 ? (size_t)dxp.split.splits * (size_t)B * (size_t)I * sizeof(float) : 0;
-    return for_dC > for_dx ? for_dC : for_dx;   // used one after the other on the same stream
+    size_t need = for_dC > for_dx ? for_dC : for_dx;   // used one after the other on the same stream
+    if (use_narrow_in(B, I, O, d)) {                     // the one-kernel path (both gradients requested)
+        const size_t both = (size_t)plan_narrow_in(B).slices * coeffs;
+        if (both > need) need = both;
+    }
+    return need;
 }
 
 bool fast_forward(const float* x, const float* C, float* y, int64_t B, int I, int O, int d, void* ws, hipStream_t s)

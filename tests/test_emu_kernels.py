@@ -120,6 +120,10 @@ CASES = [
     # small batches whose input-gradient contraction is split over the outputs (both dx kernels)
     (33, 6, 130, 24),
     (64, 40, 200, 5),
+    # very few inputs: both gradients from the one-tile kernel (full 64-row tile, ragged tile, several slices)
+    (200, 8, 64, 6),
+    (100, 5, 40, 8),
+    (300, 16, 33, 3),
 ]
 
 
