@@ -147,6 +147,10 @@ class Stack:
         n, s = len(self.layers), self.stream
         x0 = self.x0_sets[step % len(self.x0_sets)]
         dyl = self.dy_sets[step % len(self.dy_sets)]
+        if self.lut is None and not self.kind:
+            # the stack call: per-layer gradient kernels, then every slice sum in one launch
+            self.binding.chebykan_stack_backward(self.C, [x0] + self.y[:-1], self.dx + [dyl], self.dC, self.stack_ws, s)
+            return
         for l in reversed(range(n)):
             xin = x0 if l == 0 else self.y[l - 1]
             dy = dyl if l == n - 1 else self.dx[l + 1]

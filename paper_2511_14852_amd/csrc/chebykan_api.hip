@@ -248,6 +248,11 @@ size_t chebykan_stack_workspace_bytes(int64_t batch, int n_layers, const int* wi
         if (f > need) need = f;
         if (b > need) need = b;
     }
+    // the backward pass keeps every layer's partial sums until its single combine launch
+    if (stack_ok(n_layers, widths, degree, batch)) {
+        const size_t all = stack_backward_workspace_bytes(n_layers, widths, degree, batch);
+        if (all > need) need = all;
+    }
     return need;
 }
 
@@ -294,6 +299,11 @@ chebykan_status chebykan_stack_backward(int n_layers, const int* widths, int deg
     if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
     const chebykan_status dev = check_device();
     if (dev != CHEBYKAN_OK) return dev;
+    if (batch > 0 && g_family != 1) {
+        (void)hipGetLastError();
+        if (fast_stack_backward(n_layers, widths, degree, batch, C, act, grad, dC, workspace, (hipStream_t)stream))
+            return launch_status();
+    }
     for (int l = n_layers - 1; l >= 0; --l) {
         const chebykan_status st = chebykan_backward(act[l], C[l], grad[l + 1], grad[l], dC[l], batch, widths[l],
                                                      widths[l + 1], degree, workspace, workspace_bytes, stream);

@@ -22,4 +22,5 @@ template void degree_backward<3, HermiteBasis>(const float*, const float*, const
                                              void*, const HermiteBasis::Args&, hipStream_t);
 // forward of a narrow stack in one launch
 template void degree_chain_forward<3>(const ChainArgs&, int, hipStream_t);
+template void degree_stack_combine<3>(CombineArgs&, hipStream_t);
 }  // namespace chebykan

@@ -26,4 +26,5 @@ template void degree_backward<4, FourierBasis>(const float*, const float*, const
                                              void*, const FourierBasis::Args&, hipStream_t);
 // forward of a narrow stack in one launch
 template void degree_chain_forward<4>(const ChainArgs&, int, hipStream_t);
+template void degree_stack_combine<4>(CombineArgs&, hipStream_t);
 }  // namespace chebykan

@@ -24,4 +24,5 @@ template void degree_forward<8, FourierBasis>(const float*, const float*, float*
                                             const FourierBasis::Args&, hipStream_t);
 template void degree_backward<8, FourierBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
                                              void*, const FourierBasis::Args&, hipStream_t);
+template void degree_stack_combine<8>(CombineArgs&, hipStream_t);
 }  // namespace chebykan

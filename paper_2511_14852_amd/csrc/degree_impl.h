@@ -31,6 +31,10 @@ inline size_t basis_lds_bytes(const typename Basis::Args& ba, int K)
     else { (void)ba; (void)K; return 0; }
 }
 
+// When a stack's backward pass is running, the per-layer launch code records each layer's slice sum
+// here instead of launching it; the stack code then runs all of them in one launch.  Null otherwise.
+extern thread_local CombineJob* g_deferred_combine;
+
 // Many slices of a small tensor (coefficient gradients of narrow layers): 32 slice groups.
 // Few slices of a large tensor (split forward): 4 groups, 64 consecutive elements per block.
 inline void launch_sum_slices(const float* partial, float* out, int64_t n, int slices, hipStream_t s)
@@ -77,6 +81,11 @@ void pick_fwd(const float* x, const float* C, float* y, float* partial, int B, i
 template <int D>
 void launch_dC_combine(const float* partial, float* dC, int I, int O, int slices, hipStream_t s)
 {
+    // small sums are latency-bound and gain from sharing one launch; large ones run at once
+    if (g_deferred_combine && (int64_t)((O + 31) / 32) * I <= 512) {
+        *g_deferred_combine = CombineJob{partial, dC, I, O, slices, 0, 0, 0};
+        return;
+    }
     const dim3 grid((unsigned)((O + 31) / 32), (unsigned)I);
     static bool once = (allow_lds(dC_combine_kernel<D, 32>, 1024 * ((D + 1) | 1) * (int)sizeof(float)), true);
     (void)once;
@@ -211,7 +220,8 @@ void launch_narrow_bwd(const float* x, const float* C, const float* dy, float* d
                        narrow_bwd_lds_floats(O, D + 1) * sizeof(float) + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy,
                        dx, dC ? partial : nullptr, B, I, p.G, p.rows_per_wg, ba);
     if (dC) {
-        launch_sum_slices(partial, dC, (int64_t)I * O * (D + 1), p.slices, s);
+        if (g_deferred_combine) *g_deferred_combine = CombineJob{partial, dC, I, O, p.slices, 1, (int64_t)I * O * (D + 1), 0};
+        else launch_sum_slices(partial, dC, (int64_t)I * O * (D + 1), p.slices, s);
     }
 }
 
@@ -236,6 +246,22 @@ void narrow_bwd_by_out(const float* x, const float* C, const float* dy, float* d
         case 3: launch_narrow_bwd<D, 3, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s); break;
         default: launch_narrow_bwd<D, 4, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s); break;
     }
+}
+
+// All deferred slice sums of a stack in one launch.
+template <int D>
+void degree_stack_combine(CombineArgs& a, hipStream_t s)
+{
+    int blocks = 0;
+    for (int q = 0; q < a.n_jobs; ++q) {
+        a.job[q].first_block = blocks;
+        blocks += combine_job_blocks(a.job[q]);
+    }
+    if (blocks == 0) return;
+    constexpr int lds_bytes = 1024 * ((D + 1) | 1) * (int)sizeof(float);
+    static bool once = (allow_lds(stack_combine_kernel<D>, lds_bytes), true);
+    (void)once;
+    hipLaunchKernelGGL(stack_combine_kernel<D>, dim3((unsigned)blocks), dim3(1024), lds_bytes, s, a);
 }
 
 // ------------------------------------------------------------ fused narrow stack

@@ -31,6 +31,12 @@ bool fast_backward_table(const float* x, const float* C, const float* dy, const 
 bool fast_chain_forward(int n_layers, const int* widths, int d, int64_t B, const float* const* C, float* const* act,
                         hipStream_t s);
 
+// Backward of a whole stack with every slice sum in one launch at the end; the workspace holds one region per
+// layer (stack_backward_workspace_bytes).  False when a layer has no specialised kernels (nothing enqueued).
+size_t stack_backward_workspace_bytes(int n_layers, const int* widths, int d, int64_t B);
+bool fast_stack_backward(int n_layers, const int* widths, int d, int64_t B, const float* const* C,
+                         const float* const* act, float* const* grad, float* const* dC, void* ws, hipStream_t s);
+
 // Other bases (kind 1 Legendre, 2 Hermite, 3 Fourier).  False when the degree has no kernels for the family.
 bool fast_forward_family(int kind, const float* x, const float* C, float* y, int64_t B, int I, int O, int d,
                          void* ws, hipStream_t s);

@@ -7,6 +7,7 @@
 #include "basis.h"
 #include "chain_kernels.h"
 #include "dispatch.h"
+#include "mfma_kernels.h"
 #include "plans.h"
 
 namespace chebykan {
@@ -51,6 +52,14 @@ void degree_chain_forward(const ChainArgs& a, int B, hipStream_t s);
 #define CHEBYKAN_DECLARE_CHAIN(n) extern template void degree_chain_forward<n>(const ChainArgs&, int, hipStream_t);
 CHEBYKAN_FOR_EACH_CHAIN_DEGREE(CHEBYKAN_DECLARE_CHAIN)
 #undef CHEBYKAN_DECLARE_CHAIN
+
+thread_local CombineJob* g_deferred_combine = nullptr;
+
+template <int D>
+void degree_stack_combine(CombineArgs& a, hipStream_t s);
+#define CHEBYKAN_DECLARE_COMBINE(n) extern template void degree_stack_combine<n>(CombineArgs&, hipStream_t);
+CHEBYKAN_FOR_EACH_DEGREE(CHEBYKAN_DECLARE_COMBINE)
+#undef CHEBYKAN_DECLARE_COMBINE
 
 size_t forward_workspace_bytes(int64_t B, int I, int O, int d)
 {
@@ -167,6 +176,44 @@ bool fast_chain_forward(int n_layers, const int* widths, int d, int64_t B, const
 #undef CHEBYKAN_CHAIN_CASE
     }
     return false;
+}
+
+// ---- backward of a stack: the layers' kernels one after the other, every slice sum in one launch at the end.
+// Each layer gets its own 256-byte aligned region of the workspace, because its partials now live until that
+// last launch.  False (nothing enqueued) when a layer has no specialised kernels.
+static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+size_t stack_backward_workspace_bytes(int n_layers, const int* widths, int d, int64_t B)
+{
+    size_t total = 0;
+    for (int l = 0; l < n_layers; ++l) total += align256(backward_workspace_bytes(B, widths[l], widths[l + 1], d));
+    return total;
+}
+
+bool fast_stack_backward(int n_layers, const int* widths, int d, int64_t B, const float* const* C,
+                         const float* const* act, float* const* grad, float* const* dC, void* ws, hipStream_t s)
+{
+    if ((tune_flags() & 2048) || n_layers > COMBINE_MAX_JOBS || !degree_specialised(d) || B <= 0) return false;
+    for (int l = 0; l < n_layers; ++l)
+        if (!shape_fits(B, widths[l], widths[l + 1], d)) return false;
+    CombineArgs jobs;
+    jobs.n_jobs = 0;
+    char* region = static_cast<char*>(ws);
+    for (int l = n_layers - 1; l >= 0; --l) {
+        CombineJob job{nullptr, nullptr, 0, 0, 0, 0, 0, 0};
+        g_deferred_combine = &job;
+        const bool ok = fast_backward(act[l], C[l], grad[l + 1], grad[l], dC[l], B, widths[l], widths[l + 1], d, region, s);
+        g_deferred_combine = nullptr;
+        if (!ok) return false;   // cannot happen after the checks above; nothing more is enqueued
+        if (job.partial) jobs.job[jobs.n_jobs++] = job;
+        region += align256(backward_workspace_bytes(B, widths[l], widths[l + 1], d));
+    }
+    switch (d) {
+#define CHEBYKAN_COMBINE_CASE(k) case k: degree_stack_combine<k>(jobs, s); break;
+        CHEBYKAN_FOR_EACH_DEGREE(CHEBYKAN_COMBINE_CASE)
+#undef CHEBYKAN_COMBINE_CASE
+    }
+    return true;
 }
 
 // ---- other bases: same plans and workspace, another basis policy

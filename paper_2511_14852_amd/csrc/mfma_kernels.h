@@ -488,15 +488,14 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
 // G = 32 (1024 threads) shortens the serial chain per thread when there are many slices.
 // Dynamic LDS: G * 32 * ((D+1)|1) floats.
 template <int D, int G>
-__global__ void __launch_bounds__(G * 32)
-dC_combine_kernel(const float* __restrict__ partial, float* __restrict__ dC, int I, int O, int n_slices)
+__device__ __forceinline__ void dC_combine_body(const float* __restrict__ partial, float* __restrict__ dC, int I, int O,
+                                                int n_slices, int block_x, int block_y, float* lds)
 {
     constexpr int K = D + 1, KP = K | 1;
-    extern __shared__ __align__(16) float lds[];
     const int t = threadIdx.x;
     const int ol = t & 31, sg = t >> 5;
-    const int oc = blockIdx.x * 32;
-    const int i = blockIdx.y;
+    const int oc = block_x * 32;
+    const int i = block_y;
     const int o = oc + ol;
     const int64_t IK = (int64_t)I * K;
     const int64_t slice_stride = IK * O;
@@ -530,6 +529,64 @@ dC_combine_kernel(const float* __restrict__ partial, float* __restrict__ dC, int
 #pragma unroll
         for (int q = 0; q < G; ++q) total += lds[(q * 32 + o2) * KP + k];
         dst[e] = total;
+    }
+}
+
+template <int D, int G>
+__global__ void __launch_bounds__(G * 32)
+dC_combine_kernel(const float* __restrict__ partial, float* __restrict__ dC, int I, int O, int n_slices)
+{
+    extern __shared__ __align__(16) float lds[];
+    dC_combine_body<D, G>(partial, dC, I, O, n_slices, blockIdx.x, blockIdx.y, lds);
+}
+
+// Every slice sum of a stack's backward pass in ONE launch (the per-layer sums are tiny,
+// latency-bound kernels: three launches of ~5 us each for the tabular stack).  A job is one
+// layer's sum; kind 0 is dC_combine_kernel's [slice][(i,k)][o] -> [i][o][k], kind 1 a plain
+// sum of [slice][n] planes (narrow layers).  1024 threads, 32 slice groups in both kinds.
+struct CombineJob {
+    const float* partial;
+    float* out;
+    int I, O, slices, kind;
+    int64_t n;            // kind 1: elements per plane
+    int first_block;      // filled in by the launcher
+};
+constexpr int COMBINE_MAX_JOBS = 8;
+struct CombineArgs {
+    CombineJob job[COMBINE_MAX_JOBS];
+    int n_jobs;
+};
+inline int combine_job_blocks(const CombineJob& j)
+{
+    return j.kind == 0 ? ((j.O + 31) / 32) * j.I : (int)((j.n + 31) / 32);
+}
+
+template <int D>
+__global__ void __launch_bounds__(1024) stack_combine_kernel(CombineArgs a)
+{
+    extern __shared__ __align__(16) float lds[];
+    int q = 0;
+    while (q + 1 < a.n_jobs && (int)blockIdx.x >= a.job[q + 1].first_block) ++q;
+    const CombineJob& j = a.job[q];
+    const int b = blockIdx.x - j.first_block;
+    if (j.kind == 0) {
+        const int gx = (j.O + 31) / 32;
+        dC_combine_body<D, 32>(j.partial, j.out, j.I, j.O, j.slices, b % gx, b / gx, lds);
+    } else {
+        // 32 slice groups x 32 elements; groups add every 32nd slice, then the group sums in order
+        const int el = threadIdx.x & 31, sg = threadIdx.x >> 5;
+        const int64_t e = (int64_t)b * 32 + el;
+        float s = 0.0f;
+        if (e < j.n)
+            for (int sl = sg; sl < j.slices; sl += 32) s += j.partial[(int64_t)sl * j.n + e];
+        lds[sg * 33 + el] = s;
+        __syncthreads();
+        if (sg == 0 && e < j.n) {
+            float total = 0.0f;
+#pragma unroll
+            for (int g = 0; g < 32; ++g) total += lds[g * 33 + el];
+            j.out[e] = total;
+        }
     }
 }
 

@@ -1,6 +1,7 @@
 // Host driver for the CPU emulation build: forward of a whole stack through chebykan_stack_forward.
 //   emu_stack_driver <dir> <B> <degree> <n_layers> <w0> <w1> ... <wn>
-// <dir> holds x.bin and C0.bin .. C{n-1}.bin; y0.bin .. y{n-1}.bin (the layer outputs) are written there.
+// <dir> holds x.bin, dy.bin (gradient of the last output) and C0.bin .. C{n-1}.bin; y{l}.bin (layer
+// outputs), g{l}.bin (gradient with respect to the input of layer l) and dC{l}.bin are written there.
 #include <math.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -46,10 +47,32 @@ int main(int argc, char** argv)
     float* ws = wn ? (float*)malloc(wn) : nullptr;
     const int rc = chebykan_stack_forward(n, w.data(), d, B, Cp.data(), act.data(), ws, wn, nullptr);
     if (rc != CHEBYKAN_OK) { fprintf(stderr, "stack forward: %s\n", chebykan_status_string((chebykan_status)rc)); return 1; }
-    for (int l = 1; l <= n; ++l) {
-        FILE* f = fopen((dir + "/y" + std::to_string(l - 1) + ".bin").c_str(), "wb");
-        if (!f || fwrite(act[l], sizeof(float), (size_t)B * w[l], f) != (size_t)B * w[l]) return 3;
+    auto dump = [&](const std::string& name, const float* p, size_t cnt) {
+        FILE* f = fopen((dir + "/" + name).c_str(), "wb");
+        if (!f || fwrite(p, sizeof(float), cnt, f) != cnt) { fprintf(stderr, "cannot write %s\n", name.c_str()); exit(3); }
         fclose(f);
+    };
+    // backward through the same stack
+    std::vector<float> dy = read_bin(dir + "/dy.bin", (size_t)B * w[n]);
+    std::vector<float*> grad(n + 1), dC(n);
+    grad[n] = dy.data();
+    for (int l = 0; l < n; ++l) {
+        grad[l] = (float*)malloc(sizeof(float) * B * w[l]);
+        for (size_t i = 0; i < (size_t)B * w[l]; ++i) grad[l][i] = NAN;
+        const size_t cnt = (size_t)w[l] * w[l + 1] * (d + 1);
+        dC[l] = (float*)malloc(sizeof(float) * cnt);
+        for (size_t i = 0; i < cnt; ++i) dC[l][i] = NAN;
+    }
+    const int rb = chebykan_stack_backward(n, w.data(), d, B, Cp.data(), act.data(), grad.data(), dC.data(), ws, wn, nullptr);
+    if (rb != CHEBYKAN_OK) { fprintf(stderr, "stack backward: %s\n", chebykan_status_string((chebykan_status)rb)); return 1; }
+    for (int l = 0; l < n; ++l) {
+        dump("g" + std::to_string(l) + ".bin", grad[l], (size_t)B * w[l]);
+        dump("dC" + std::to_string(l) + ".bin", dC[l], (size_t)w[l] * w[l + 1] * (d + 1));
+        free(grad[l]);
+        free(dC[l]);
+    }
+    for (int l = 1; l <= n; ++l) {
+        dump("y" + std::to_string(l - 1) + ".bin", act[l], (size_t)B * w[l]);
         free(act[l]);
     }
     for (int l = 0; l < n; ++l) free(Cp[l]);

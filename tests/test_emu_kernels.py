@@ -176,7 +176,8 @@ def test_other_bases_on_cpu_emulation(emu_driver, case):
     assert all(np.isfinite(e) and e <= 1e-5 for e in errs), errs
 
 
-# (B, widths, degree): forward of a narrow stack in one kernel (forced at these small batches): ragged
+# (B, widths, degree): stack calls - forward of a narrow stack in one kernel (forced at these small batches),
+# backward with every small slice sum in one launch: ragged
 # last row tile, narrow and matrix-core last layers, a hidden width below 64
 STACK_CASES = [
     (200, (8, 64, 64, 1), 6),
@@ -186,14 +187,16 @@ STACK_CASES = [
 
 
 @pytest.mark.parametrize("case", STACK_CASES, ids=lambda c: "B%d_%s_d%d" % (c[0], "x".join(map(str, c[1])), c[2]))
-def test_fused_stack_forward_on_cpu_emulation(emu_driver, case):
+def test_stack_calls_on_cpu_emulation(emu_driver, case):
     B, widths, d = case
     exe = os.path.join(os.path.dirname(emu_driver), "emu_stack_driver")
     x = wl.make_x(B, widths[0], 77)
+    dy = wl.make_dy(B, widths[-1], 78)
     Cs = [wl.make_coeff(i, o, d, 80 + l) for l, (i, o) in enumerate(zip(widths[:-1], widths[1:]))]
     td = tempfile.mkdtemp(prefix="emu_")
     try:
         x.tofile(os.path.join(td, "x.bin"))
+        dy.tofile(os.path.join(td, "dy.bin"))
         for l, c in enumerate(Cs):
             c.tofile(os.path.join(td, "C%d.bin" % l))
         env = dict(os.environ, CHEBYKAN_TUNE="512")
@@ -202,10 +205,18 @@ def test_fused_stack_forward_on_cpu_emulation(emu_driver, case):
         assert r.returncode == 0, (r.stdout[-1000:], r.stderr[-4000:])
         ys = [np.fromfile(os.path.join(td, "y%d.bin" % l), dtype=np.float32).reshape(B, widths[l + 1])
               for l in range(len(Cs))]
+        gs = [np.fromfile(os.path.join(td, "g%d.bin" % l), dtype=np.float32).reshape(B, widths[l])
+              for l in range(len(Cs))] + [dy]
+        dCs = [np.fromfile(os.path.join(td, "dC%d.bin" % l), dtype=np.float32).reshape(Cs[l].shape)
+               for l in range(len(Cs))]
     finally:
         shutil.rmtree(td, ignore_errors=True)
     xin = x
     for l, c in enumerate(Cs):             # per layer, on the kernel's own fp32 layer input
         err = oracle.rel_err(ys[l], oracle.forward(xin, c))
         assert np.isfinite(err) and err <= 1e-5, (l, err)
+        # backward of the layer on the kernels' own incoming gradient; the slice sums of all layers ran in one launch
+        dx_ref, dC_ref = oracle.backward(xin, c, gs[l + 1])
+        errs = (oracle.rel_err(gs[l], dx_ref), oracle.rel_err(dCs[l], dC_ref))
+        assert all(np.isfinite(e) and e <= 1e-5 for e in errs), (l, errs)
         xin = ys[l]
