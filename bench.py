@@ -35,9 +35,9 @@ MEASURED_TRAFFIC_BYTES = {
     ("c2", "dC", 1): 48.4e6 + 14.8e6,      # slice kernel + combine
     ("c2", "dx", 1): 80.6e6,
     ("c2", "fwd", 1): 26.8e6,
-    ("c5", "dC", 0): 900.5e6 + 188.8e6,
-    ("c5", "fwd", 0): 754.4e6,
-    ("c5", "dx", 0): 1762.9e6,
+    ("c5", "dC", 0): 959.4e6 + 264.3e6,
+    ("c5", "fwd", 0): 754.7e6,
+    ("c5", "dx", 0): 1760.5e6,
 }
 
 
@@ -329,7 +329,7 @@ def main():
     torch.cuda.synchronize()
     per_call = []
     for c, (tag, l, _) in enumerate(st.calls(0)):
-        ms = float(np.mean([evs[k][c][0].elapsed_time(evs[k][c][1]) for k in range(ksteps)]))
+        ms = float(np.median([evs[k][c][0].elapsed_time(evs[k][c][1]) for k in range(ksteps)]))   # robust to a stray slow launch
         I, O = w.layers[l]
         fl, by = call_work(tag, B, I, O, w.degree)
         per_call.append({"call": tag, "layer": l, "in": I, "out": O, "us": round(ms * 1e3, 2),

@@ -128,19 +128,24 @@ __device__ __forceinline__ void chain_mfma_layer(const float* __restrict__ x, co
 #pragma unroll
         for (int j = 0; j < TN; ++j) { acc[i][j] = zero16(); total[i][j] = zero16(); }
 
+    // operands are read from LDS LOOKAHEAD steps ahead of their MFMA, as in fwd_mfma_kernel
+    constexpr int LA = LOOKAHEAD < Cfg::NSTEP / 2 ? LOOKAHEAD : Cfg::NSTEP / 2;
+    float aop[Cfg::NSTEP][TM], bop[Cfg::NSTEP][TN];
+    auto read_step = [&](const float* pA, const float* pB, int s) {
+        const int ih = s / K, k = s % K;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) aop[s][i] = pA[i * 32 * SA + s];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bop[s][j] = pB[ih * SS + j * 32 * KP + k];
+    };
     auto mfma_steps = [&](const float* pA, const float* pB, int s0, int s1) {
 #pragma unroll
         for (int s = s0; s < s1; ++s) {
-            const int ih = s / K, k = s % K;
-            float a[TM], b[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = pA[i * 32 * SA + s];
-#pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = pB[ih * SS + j * 32 * KP + k];
+            if (s + LA < Cfg::NSTEP) read_step(pA, pB, s + LA);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
+                for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(aop[s][i], bop[s][j], acc[i][j]);
         }
     };
 
@@ -153,10 +158,13 @@ __device__ __forceinline__ void chain_mfma_layer(const float* __restrict__ x, co
         float* sA = lds + (c & 1) * Cfg::STAGE;
         float* sB = sA + Cfg::A_FLOATS;
         float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
+#pragma unroll
+        for (int q = 0; q < LA; ++q) read_step(sA + aBase, sB + bBase, q);
         mfma_steps(sA + aBase, sB + bBase, 0, Cfg::NSTEP / 2);
         store_chunk(nA, nA + Cfg::A_FLOATS);
         load_chunk((c + 2) * BI);
         mfma_steps(sA + aBase, sB + bBase, Cfg::NSTEP / 2, Cfg::NSTEP);
+        __builtin_amdgcn_sched_group_barrier(0x100, LA * (TM + TN), 0);
 #pragma unroll
         for (int q = 0; q < Cfg::NMFMA; ++q) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
