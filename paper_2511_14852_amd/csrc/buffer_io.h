@@ -35,7 +35,7 @@ __device__ __forceinline__ float load1(const BufferView& v, uint32_t index)
     return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(v.rsrc, (int)(index * 4u), 0, 0));
 }
 
-// four consecutive floats from a 16-byte aligned position, or zeros beyond the end
+// four consecutive floats from any 4-byte aligned position; elements beyond the end read as zero
 __device__ __forceinline__ bufx4 load4(const BufferView& v, uint32_t index)
 {
     return __builtin_bit_cast(bufx4, __builtin_amdgcn_raw_buffer_load_b128(v.rsrc, (int)(index * 4u), 0, 0));

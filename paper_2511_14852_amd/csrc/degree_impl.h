@@ -48,33 +48,53 @@ inline void launch_sum_slices(const float* partial, float* out, int64_t n, int s
 }
 
 // ------------------------------------------------------------------ forward
+// Output tiling: 128-wide tiles, except that a remainder of 1..64 columns beyond a multiple of 128
+// gets one 64-wide tile (257 outputs: 2 x 128 + 64 computed columns instead of 3 x 128).
+struct OutTiling {
+    int wide_tiles;    // 128-wide tiles from column 0
+    int tail_begin;    // first column of the 64-wide tail tile, or -1
+};
+inline OutTiling out_tiling(int O)
+{
+    const int rem = O % 128;
+    if (O > 128 && rem >= 1 && rem <= 64) return OutTiling{O / 128, (O / 128) * 128};
+    return OutTiling{(O + 127) / 128, -1};
+}
+
 template <int D, int BN, int VEC, class Basis>
-void launch_fwd(const float* x, const float* C, float* y, float* partial, int B, int I, int O, const typename Basis::Args& ba, hipStream_t s)
+void launch_fwd(const float* x, const float* C, float* out, int B, int I, int O, int tiles_o, int o_begin,
+                const FwdPlan& p, const typename Basis::Args& ba, hipStream_t s)
 {
     using Cfg = FwdCfg<D, BN, forward_chunk_features(D), VEC>;
     static bool once = (allow_lds(fwd_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES), true);
     (void)once;
-    const FwdPlan p = plan_forward(B, I, O, D);
-    const int tiles_o = (O + BN - 1) / BN;
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * tiles_o;
-    float* out = p.splits > 1 ? partial : y;
     hipLaunchKernelGGL((fwd_mfma_kernel<Cfg, Basis>), dim3((unsigned)tiles, (unsigned)p.splits), dim3(MFMA_THREADS),
-                       Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, out, B, I, O, tiles_o,
+                       Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, out, B, I, O, tiles_o, o_begin,
                        p.chunks_per_split, ba);
-    if (p.splits > 1) launch_sum_slices(partial, y, (int64_t)B * O, p.splits, s);
 }
 
 template <int D, class Basis>
 void pick_fwd(const float* x, const float* C, float* y, float* partial, int B, int I, int O, const typename Basis::Args& ba, hipStream_t s)
 {
-    const bool vec = aligned16(C) && ((int64_t)O * (D + 1)) % 4 == 0;
+    // 16-byte loads only need 4-byte aligned addresses in global memory; the LDS side of the copy stays aligned
+    const bool vec = !(tune_flags() & 16384);
+    (void)C;
+    const FwdPlan p = plan_forward(B, I, O, D);
+    float* out = p.splits > 1 ? partial : y;
     if (O <= 64) {
-        if (vec) launch_fwd<D, 64, 4, Basis>(x, C, y, partial, B, I, O, ba, s);
-        else launch_fwd<D, 64, 1, Basis>(x, C, y, partial, B, I, O, ba, s);
+        if (vec) launch_fwd<D, 64, 4, Basis>(x, C, out, B, I, O, 1, 0, p, ba, s);
+        else launch_fwd<D, 64, 1, Basis>(x, C, out, B, I, O, 1, 0, p, ba, s);
     } else {
-        if (vec) launch_fwd<D, 128, 4, Basis>(x, C, y, partial, B, I, O, ba, s);
-        else launch_fwd<D, 128, 1, Basis>(x, C, y, partial, B, I, O, ba, s);
+        const OutTiling t = out_tiling(O);
+        if (vec) launch_fwd<D, 128, 4, Basis>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s);
+        else launch_fwd<D, 128, 1, Basis>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s);
+        if (t.tail_begin >= 0) {
+            if (vec) launch_fwd<D, 64, 4, Basis>(x, C, out, B, I, O, 1, t.tail_begin, p, ba, s);
+            else launch_fwd<D, 64, 1, Basis>(x, C, out, B, I, O, 1, t.tail_begin, p, ba, s);
+        }
     }
+    if (p.splits > 1) launch_sum_slices(partial, y, (int64_t)B * O, p.splits, s);
 }
 
 // --------------------------------------------------------------------- dC
@@ -98,30 +118,34 @@ void launch_dC_combine(const float* partial, float* dC, int I, int O, int slices
 }
 
 template <int D, int BN, int VEC, int BIC, class Basis>
-void launch_dC(const float* x, const float* dy, float* partial, int B, int I, int O, const DcPlan& p,
-               const typename Basis::Args& ba, hipStream_t s)
+void launch_dC(const float* x, const float* dy, float* partial, int B, int I, int O, int tiles_o, int o_begin,
+               const DcPlan& p, const typename Basis::Args& ba, hipStream_t s)
 {
     using Cfg = DcCfg<D, BN, VEC, BIC>;
     static bool once = (allow_lds(dC_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES), true);
     (void)once;
-    const int tiles_o = (O + BN - 1) / BN;
     const int tiles_i = (I + Cfg::BIC - 1) / Cfg::BIC;
     hipLaunchKernelGGL((dC_mfma_kernel<Cfg, Basis>), dim3((unsigned)((int64_t)tiles_i * tiles_o * p.slices)),
                        dim3(MFMA_THREADS), Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, dy, partial, B, I, O,
-                       tiles_o, tiles_i, p.slices, p.rows_per_slice, ba);
+                       tiles_o, o_begin, tiles_i, p.slices, p.rows_per_slice, ba);
 }
 
 template <int D, int BIC, class Basis>
 void pick_dC_tile(const float* x, const float* dy, float* partial, int B, int I, int O, const DcPlan& p,
                   const typename Basis::Args& ba, hipStream_t s)
 {
-    const bool vec = aligned16(dy) && O % 4 == 0;
+    const bool vec = !(tune_flags() & 16384);   // see pick_fwd
     if (p.bn == 64) {
-        if (vec) launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, B, I, O, p, ba, s);
-        else launch_dC<D, 64, 1, BIC, Basis>(x, dy, partial, B, I, O, p, ba, s);
+        if (vec) launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, B, I, O, 1, 0, p, ba, s);
+        else launch_dC<D, 64, 1, BIC, Basis>(x, dy, partial, B, I, O, 1, 0, p, ba, s);
     } else {
-        if (vec) launch_dC<D, 128, 4, BIC, Basis>(x, dy, partial, B, I, O, p, ba, s);
-        else launch_dC<D, 128, 1, BIC, Basis>(x, dy, partial, B, I, O, p, ba, s);
+        const OutTiling t = out_tiling(O);
+        if (vec) launch_dC<D, 128, 4, BIC, Basis>(x, dy, partial, B, I, O, t.wide_tiles, 0, p, ba, s);
+        else launch_dC<D, 128, 1, BIC, Basis>(x, dy, partial, B, I, O, t.wide_tiles, 0, p, ba, s);
+        if (t.tail_begin >= 0) {
+            if (vec) launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, B, I, O, 1, t.tail_begin, p, ba, s);
+            else launch_dC<D, 64, 1, BIC, Basis>(x, dy, partial, B, I, O, 1, t.tail_begin, p, ba, s);
+        }
     }
 }
 

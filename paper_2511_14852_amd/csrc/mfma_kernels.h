@@ -87,7 +87,9 @@ struct FwdCfg {
 };
 
 // y[b,o] = sum_i sum_k C[i,o,k] T_k(tanh x[b,i])      (paper Eq. 2-3; Alg. 1 as a function)
-// grid.x = ceil(B/128) * ceil(O/BN), output-tile index fastest; grid.y = contraction ranges.
+// grid.x = ceil(B/128) * n_tiles_o, output-tile index fastest; grid.y = contraction ranges.
+// The launch covers the n_tiles_o BN-wide output tiles that start at column o_begin, so a width
+// just above a multiple of 128 can be tiled with 128-wide tiles plus one 64-wide tile.
 //
 // Per chunk c: barrier; first half of chunk c's MFMA steps; generate chunk c+1 into the
 // other LDS stage; request chunk c+2 from HBM; second half of the MFMA steps.  All loads go
@@ -97,7 +99,7 @@ struct FwdCfg {
 template <class Cfg, class Basis = ExactBasis>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float* __restrict__ y,
-                int B, int I, int O, int n_tiles_o, int chunks_per_split, typename Basis::Args bargs)
+                int B, int I, int O, int n_tiles_o, int o_begin, int chunks_per_split, typename Basis::Args bargs)
 {
     constexpr int D = Cfg::D, K = Cfg::K, KP = Cfg::KP, BN = Cfg::BN, BI = Cfg::BI, VEC = Cfg::VEC;
     constexpr int SA = Cfg::SA, SS = Cfg::SS, TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
@@ -109,7 +111,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
     const int tile_o = blockIdx.x % n_tiles_o;
     const int tile_b = blockIdx.x / n_tiles_o;
     const int b0 = tile_b * Cfg::BM;
-    const int o0 = tile_o * BN;
+    const int o0 = o_begin + tile_o * BN;   // a launch covers the BN-wide tiles from column o_begin on
 
     // --- producer role.  Views are based at this tile so that 32-bit offsets suffice.
     const int rows_here = B - b0 < Cfg::BM ? B - b0 : Cfg::BM;
@@ -311,7 +313,8 @@ struct DcCfg {
 template <class Cfg, class Basis = ExactBasis>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ partial,
-               int B, int I, int O, int n_tiles_o, int n_tiles_i, int n_slices, int rows_per_slice, typename Basis::Args bargs)
+               int B, int I, int O, int n_tiles_o, int o_begin, int n_tiles_i, int n_slices, int rows_per_slice,
+               typename Basis::Args bargs)
 {
     constexpr int D = Cfg::D, K = Cfg::K, BN = Cfg::BN, VEC = Cfg::VEC, BB = Cfg::BB, BIC = Cfg::BIC;
     constexpr int SMA = Cfg::SMA, SNB = Cfg::SNB, TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
@@ -341,7 +344,7 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
     const int tile_o = tile % n_tiles_o;
     const int tile_i = tile / n_tiles_o;
     const int i0 = tile_i * BIC;
-    const int o0 = tile_o * BN;
+    const int o0 = o_begin + tile_o * BN;
     const int64_t r_begin = (int64_t)slice * rows_per_slice;
     int64_t r_end = r_begin + rows_per_slice;
     if (r_end > B) r_end = B;
