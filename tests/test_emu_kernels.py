@@ -92,6 +92,23 @@ def _run(exe, B, I, O, d, family, seed=1, lut_size=0, basis=0):
     return (oracle.rel_err(y, oracle.forward(x, C)), oracle.rel_err(dx, dx_ref), oracle.rel_err(dC, dC_ref))
 
 
+# The default run takes one case per kernel family (QUICK); CHEBYKAN_EMU_FULL=1 runs every case
+# (about a quarter of an hour on 8 cores).
+FULL = os.environ.get("CHEBYKAN_EMU_FULL", "0") == "1"
+QUICK = {
+    (140, 7, 130, 6), (129, 5, 257, 8), (140, 40, 72, 6), (300, 64, 1, 6), (40, 12, 70, 15), (33, 6, 130, 24),
+    (200, 8, 64, 6),
+    (130, 9, 64, 4, 65), (300, 64, 1, 6, 65),                 # table variant
+    (130, 9, 64, 4, 1), (129, 5, 130, 8, 3),                  # other bases
+    (129, (5, 64, 12), 3),                                    # stack calls
+}
+
+
+def _select(cases):
+    return [c if (FULL or c in QUICK) else pytest.param(c, marks=pytest.mark.skip(reason="set CHEBYKAN_EMU_FULL=1"))
+            for c in cases]
+
+
 # (B, I, O, degree): ragged in every dimension, both output-tile widths, aligned and
 # unaligned coefficient slabs, several batch slices
 CASES = [
@@ -127,7 +144,7 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("case", CASES, ids=lambda c: "B%d_I%d_O%d_d%d" % c)
+@pytest.mark.parametrize("case", _select(CASES), ids=lambda c: "B%d_I%d_O%d_d%d" % c)
 def test_mfma_family_on_cpu_emulation(emu_driver, case):
     B, I, O, d = case
     errs = _run(emu_driver, B, I, O, d, family=2)
@@ -152,7 +169,7 @@ LUT_CASES = [
 ]
 
 
-@pytest.mark.parametrize("case", LUT_CASES, ids=lambda c: "B%d_I%d_O%d_d%d_n%d" % c)
+@pytest.mark.parametrize("case", _select(LUT_CASES), ids=lambda c: "B%d_I%d_O%d_d%d_n%d" % c)
 def test_table_variant_on_cpu_emulation(emu_driver, case):
     B, I, O, d, n = case
     errs = _run(emu_driver, B, I, O, d, family=2, lut_size=n)
@@ -169,7 +186,7 @@ BASIS_CASES = [
 ]
 
 
-@pytest.mark.parametrize("case", BASIS_CASES, ids=lambda c: "B%d_I%d_O%d_d%d_basis%d" % c)
+@pytest.mark.parametrize("case", _select(BASIS_CASES), ids=lambda c: "B%d_I%d_O%d_d%d_basis%d" % c)
 def test_other_bases_on_cpu_emulation(emu_driver, case):
     B, I, O, d, basis = case
     errs = _run(emu_driver, B, I, O, d, family=2, basis=basis)
@@ -186,7 +203,7 @@ STACK_CASES = [
 ]
 
 
-@pytest.mark.parametrize("case", STACK_CASES, ids=lambda c: "B%d_%s_d%d" % (c[0], "x".join(map(str, c[1])), c[2]))
+@pytest.mark.parametrize("case", _select(STACK_CASES), ids=lambda c: "B%d_%s_d%d" % (c[0], "x".join(map(str, c[1])), c[2]))
 def test_stack_calls_on_cpu_emulation(emu_driver, case):
     B, widths, d = case
     exe = os.path.join(os.path.dirname(emu_driver), "emu_stack_driver")
