@@ -14,20 +14,20 @@ static int g_family = 0;  // 0 auto, 1 generic, 2 mfma
 // Is the current device a gfx950 part?  Cached per device ordinal.
 static chebykan_status check_device()
 {
-    static int verdict[64];  // 0 unknown, 1 ok, -1 wrong arch
+    static int arch_state[64];  // 0 unknown, 1 ok, -1 wrong arch
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0) {
         (void)hipGetLastError();
         return CHEBYKAN_ERR_DEVICE;
     }
-    if (dev < 64 && verdict[dev] != 0) return verdict[dev] > 0 ? CHEBYKAN_OK : CHEBYKAN_ERR_DEVICE;
+    if (dev < 64 && arch_state[dev] != 0) return arch_state[dev] > 0 ? CHEBYKAN_OK : CHEBYKAN_ERR_DEVICE;
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, dev) != hipSuccess) {
         (void)hipGetLastError();
         return CHEBYKAN_ERR_DEVICE;
     }
     const bool ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
-    if (dev < 64) verdict[dev] = ok ? 1 : -1;
+    if (dev < 64) arch_state[dev] = ok ? 1 : -1;
     return ok ? CHEBYKAN_OK : CHEBYKAN_ERR_DEVICE;
 }
 
