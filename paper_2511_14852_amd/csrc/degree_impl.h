@@ -12,7 +12,20 @@
 
 namespace chebykan {
 
-// Dynamic LDS above 64 KiB has to be allowed per kernel once.
+// True the first time it is asked on each device (function attributes are per device).
+struct DeviceOnce {
+    bool done[64] = {};
+    bool first()
+    {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return true;   // unknown device: just set it again
+        if (done[dev]) return false;
+        done[dev] = true;
+        return true;
+    }
+};
+
+// Dynamic LDS above 64 KiB has to be allowed per kernel, once per device.
 template <class KernelT>
 void allow_lds(KernelT kernel, int bytes)
 {
@@ -66,8 +79,8 @@ void launch_fwd(const float* x, const float* C, float* out, int B, int I, int O,
                 const FwdPlan& p, const typename Basis::Args& ba, hipStream_t s)
 {
     using Cfg = FwdCfg<D, BN, forward_chunk_features(D), VEC>;
-    static bool once = (allow_lds(fwd_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES), true);
-    (void)once;
+    static DeviceOnce once;
+    if (once.first()) allow_lds(fwd_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES);
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * tiles_o;
     hipLaunchKernelGGL((fwd_mfma_kernel<Cfg, Basis>), dim3((unsigned)tiles, (unsigned)p.splits), dim3(MFMA_THREADS),
                        Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, out, B, I, O, tiles_o, o_begin,
@@ -107,8 +120,8 @@ void launch_dC_combine(const float* partial, float* dC, int I, int O, int slices
         return;
     }
     const dim3 grid((unsigned)((O + 31) / 32), (unsigned)I);
-    static bool once = (allow_lds(dC_combine_kernel<D, 32>, 1024 * ((D + 1) | 1) * (int)sizeof(float)), true);
-    (void)once;
+    static DeviceOnce once;
+    if (once.first()) allow_lds(dC_combine_kernel<D, 32>, 1024 * ((D + 1) | 1) * (int)sizeof(float));
     if (slices > 32)
         hipLaunchKernelGGL((dC_combine_kernel<D, 32>), grid, dim3(1024), 1024 * ((D + 1) | 1) * sizeof(float), s,
                            partial, dC, I, O, slices);
@@ -122,8 +135,8 @@ void launch_dC(const float* x, const float* dy, float* partial, int B, int I, in
                const DcPlan& p, const typename Basis::Args& ba, hipStream_t s)
 {
     using Cfg = DcCfg<D, BN, VEC, BIC>;
-    static bool once = (allow_lds(dC_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES), true);
-    (void)once;
+    static DeviceOnce once;
+    if (once.first()) allow_lds(dC_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES);
     const int tiles_i = (I + Cfg::BIC - 1) / Cfg::BIC;
     hipLaunchKernelGGL((dC_mfma_kernel<Cfg, Basis>), dim3((unsigned)((int64_t)tiles_i * tiles_o * p.slices)),
                        dim3(MFMA_THREADS), Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, dy, partial, B, I, O,
@@ -168,8 +181,8 @@ void launch_dx(const float* x, const float* C, const float* dy, float* dx, float
                const DxPlan& p, const typename Basis::Args& ba, hipStream_t s)
 {
     using Cfg = DxCfg<D, NB, VEC>;
-    static bool once = (allow_lds(dx_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES), true);
-    (void)once;
+    static DeviceOnce once;
+    if (once.first()) allow_lds(dx_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES);
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * p.feature_tiles;
     hipLaunchKernelGGL((dx_mfma_kernel<Cfg, Basis>), dim3((unsigned)tiles, (unsigned)p.split.splits), dim3(MFMA_THREADS),
                        Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy,
@@ -182,8 +195,8 @@ void launch_dx2(const float* x, const float* C, const float* dy, float* dx, floa
 {
     using Cfg = Dx2Cfg<D, VEC>;
     static_assert(Cfg::BO == (D <= 4 ? 32 : 16), "plan_dx assumes this chunk width");
-    static bool once = (allow_lds(dx2_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES), true);
-    (void)once;
+    static DeviceOnce once;
+    if (once.first()) allow_lds(dx2_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES);
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * p.feature_tiles;
     hipLaunchKernelGGL((dx2_mfma_kernel<Cfg, Basis>), dim3((unsigned)tiles, (unsigned)p.split.splits), dim3(MFMA_THREADS),
                        Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy,
@@ -224,8 +237,8 @@ template <int D, int O, class Basis>
 void launch_narrow_fwd(const float* x, const float* C, float* y, int B, int I, const typename Basis::Args& ba, hipStream_t s)
 {
     const NarrowPlan p = plan_narrow(B, I, NARROW_FWD_WGS);
-    static bool once = (allow_lds(narrow_fwd_kernel<D, O, Basis>, MAX_LDS_BYTES), true);
-    (void)once;
+    static DeviceOnce once;
+    if (once.first()) allow_lds(narrow_fwd_kernel<D, O, Basis>, MAX_LDS_BYTES);
     hipLaunchKernelGGL((narrow_fwd_kernel<D, O, Basis>), dim3((unsigned)p.slices), dim3(NARROW_THREADS),
                        narrow_fwd_lds_floats(I, O, D + 1) * sizeof(float) + basis_lds_bytes<Basis>(ba, D + 1), s, x, C,
                        y, B, I, p.G, p.rows_per_wg, ba);
@@ -237,8 +250,8 @@ void launch_narrow_bwd(const float* x, const float* C, const float* dy, float* d
 {
     const NarrowPlan p = plan_narrow(B, I, NARROW_BWD_WGS);
     const int blocks_i = (I + p.G - 1) / p.G;
-    static bool once = (allow_lds(narrow_bwd_kernel<D, O, Basis>, MAX_LDS_BYTES), true);
-    (void)once;
+    static DeviceOnce once;
+    if (once.first()) allow_lds(narrow_bwd_kernel<D, O, Basis>, MAX_LDS_BYTES);
     hipLaunchKernelGGL((narrow_bwd_kernel<D, O, Basis>), dim3((unsigned)p.slices, (unsigned)blocks_i),
                        dim3(NARROW_THREADS),
                        narrow_bwd_lds_floats(O, D + 1) * sizeof(float) + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy,
@@ -283,8 +296,8 @@ void degree_stack_combine(CombineArgs& a, hipStream_t s)
     }
     if (blocks == 0) return;
     constexpr int lds_bytes = 1024 * ((D + 1) | 1) * (int)sizeof(float);
-    static bool once = (allow_lds(stack_combine_kernel<D>, lds_bytes), true);
-    (void)once;
+    static DeviceOnce once;
+    if (once.first()) allow_lds(stack_combine_kernel<D>, lds_bytes);
     hipLaunchKernelGGL(stack_combine_kernel<D>, dim3((unsigned)blocks), dim3(1024), lds_bytes, s, a);
 }
 
@@ -293,8 +306,8 @@ void degree_stack_combine(CombineArgs& a, hipStream_t s)
 template <int D>
 void degree_chain_forward(const ChainArgs& a, int B, hipStream_t s)
 {
-    static bool once = (allow_lds(fwd_chain_kernel<D>, chain_lds_bytes<D>()), true);
-    (void)once;
+    static DeviceOnce once;
+    if (once.first()) allow_lds(fwd_chain_kernel<D>, chain_lds_bytes<D>());
     hipLaunchKernelGGL(fwd_chain_kernel<D>, dim3((unsigned)((B + 127) / 128)), dim3(MFMA_THREADS),
                        (size_t)chain_lds_bytes<D>(), s, a, B);
 }
@@ -320,9 +333,8 @@ void degree_backward(const float* x, const float* C, const float* dy, float* dx,
     }
     if (dx && dC && use_narrow_in(B, I, O, D)) {   // few inputs, both gradients wanted: one kernel for both
         const NarrowInPlan p = plan_narrow_in(B);
-        static bool once = (allow_lds(bwd_narrow_in_kernel<D, Basis>, Basis::kTable ? MAX_LDS_BYTES : NIN_LDS_BYTES),
-                            true);
-        (void)once;
+        static DeviceOnce once;
+        if (once.first()) allow_lds(bwd_narrow_in_kernel<D, Basis>, Basis::kTable ? MAX_LDS_BYTES : NIN_LDS_BYTES);
         hipLaunchKernelGGL((bwd_narrow_in_kernel<D, Basis>), dim3((unsigned)p.slices), dim3(MFMA_THREADS),
                            NIN_LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy, dx, dC ? partial : nullptr, B,
                            I, O, p.rows_per_slice, ba);
