@@ -307,3 +307,72 @@ def test_calibration_entry_points():
     lib = binding.load()
     assert lib.chebykan_calibrate_copy(dst.data_ptr(), src.data_ptr(), 3, None) == binding.CHEBYKAN_ERR_SHAPE
     assert lib.chebykan_calibrate_mfma(None, 8, 10, None, None) == binding.CHEBYKAN_ERR_NULL
+
+
+def test_batch_whose_outputs_exceed_four_gib():
+    """16.8 million rows of an 8->64 layer: y and dy are 4.3 GB each, so element offsets pass 2^32 bytes.
+    Inputs are generated on the GPU from a fixed seed (no 8 GB host arrays); the oracle runs on sampled rows
+    (forward and dx are independent per row) and on sampled dC entries with the two dy columns they need."""
+    B, I, O, d = (1 << 24) + 77, 8, 64, 6
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(251114852)
+    x = torch.randn((B, I), device="cuda", generator=gen)
+    dy = torch.randn((B, O), device="cuda", generator=gen)
+    C = _dev(wl.make_coeff(I, O, d, 9))
+    y = torch.empty((B, O), device="cuda")
+    dx = torch.empty((B, I), device="cuda")
+    dC = torch.empty_like(C)
+    ws = binding.alloc_workspace(B, I, O, d)
+    binding.chebykan_forward(x, C, y, ws)
+    binding.chebykan_backward(x, C, dy, dx, dC, ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    rows = np.unique(np.concatenate([np.arange(0, 130), np.arange(B - 140, B), rng.integers(0, B, 300),
+                                     np.arange((1 << 24) - 70, (1 << 24) + 70)]))
+    rows_t = torch.from_numpy(rows).cuda()
+    xs, dys, Cn = x[rows_t].cpu().numpy(), dy[rows_t].cpu().numpy(), C.cpu().numpy()
+    assert oracle.rel_err(y[rows_t].cpu().numpy(), oracle.forward(xs, Cn)) <= TOL
+    dx_ref, _ = oracle.backward(xs, Cn, dys, need_dC=False)
+    assert oracle.rel_err(dx[rows_t].cpu().numpy(), dx_ref) <= TOL
+    cols = [5, 63]
+    x_all = x.cpu().numpy()
+    dy_cols = dy[:, cols].contiguous().cpu().numpy()
+    is_, ks = rng.integers(0, I, 6), rng.integers(0, d + 1, 6)
+    os_local = rng.integers(0, 2, 6)
+    ref = oracle.dC_at(x_all, dy_cols, d, is_, os_local, ks)
+    got = dC.cpu().numpy()[is_, np.array(cols)[os_local], ks]
+    scale = float(np.sqrt(np.mean(dC.cpu().numpy().astype(np.float64) ** 2)))
+    assert np.max(np.abs(got - ref)) / scale <= TOL
+
+
+def test_narrow_layer_whose_input_exceeds_four_gib():
+    """16.8 million rows of a 64->1 layer (the streaming kernels): x is 4.3 GB."""
+    B, I, O, d = (1 << 24) + 5, 64, 1, 6
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20251114)
+    x = torch.randn((B, I), device="cuda", generator=gen)
+    dy = torch.randn((B, O), device="cuda", generator=gen)
+    C = _dev(wl.make_coeff(I, O, d, 19))
+    y = torch.empty((B, O), device="cuda")
+    dx = torch.empty((B, I), device="cuda")
+    dC = torch.empty_like(C)
+    ws = binding.alloc_workspace(B, I, O, d)
+    binding.chebykan_forward(x, C, y, ws)
+    binding.chebykan_backward(x, C, dy, dx, dC, ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4)
+    rows = np.unique(np.concatenate([np.arange(0, 70), np.arange(B - 70, B), rng.integers(0, B, 300),
+                                     np.arange((1 << 24) - 40, (1 << 24) + 5)]))
+    rows_t = torch.from_numpy(rows).cuda()
+    xs, dys, Cn = x[rows_t].cpu().numpy(), dy[rows_t].cpu().numpy(), C.cpu().numpy()
+    assert oracle.rel_err(y[rows_t].cpu().numpy(), oracle.forward(xs, Cn)) <= TOL
+    dx_ref, _ = oracle.backward(xs, Cn, dys, need_dC=False)
+    assert oracle.rel_err(dx[rows_t].cpu().numpy(), dx_ref) <= TOL
+    feats = [0, 63]                                  # dC[i, :, :] depends on column i of x only
+    x_cols = x[:, feats].contiguous().cpu().numpy()
+    dy_all = dy.cpu().numpy()
+    is_local, ks = rng.integers(0, 2, 6), rng.integers(0, d + 1, 6)
+    ref = oracle.dC_at(x_cols, dy_all, d, is_local, np.zeros(6, dtype=np.int64), ks)
+    got = dC.cpu().numpy()[np.array(feats)[is_local], 0, ks]
+    scale = float(np.sqrt(np.mean(dC.cpu().numpy().astype(np.float64) ** 2)))
+    assert np.max(np.abs(got - ref)) / scale <= TOL
