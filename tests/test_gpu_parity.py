@@ -107,6 +107,13 @@ SMALL_SHAPES = [
     (32, 512, 1024, 24),
     (100, 600, 130, 2),
     (200, 130, 70, 7),
+    # the highest degree the interface takes and one between the specialised ones
+    (40, 9, 33, 32),
+    (33, 12, 20, 11),
+    # the widest layers the interface takes (16-bit widths), on the matrix-core and the streaming kernels
+    (8, 65535, 8, 2),
+    (8, 8, 65535, 2),
+    (16, 65535, 3, 2),
 ]
 
 
