@@ -61,19 +61,6 @@ inline void launch_sum_slices(const float* partial, float* out, int64_t n, int s
 }
 
 // ------------------------------------------------------------------ forward
-// Output tiling: 128-wide tiles, except that a remainder of 1..64 columns beyond a multiple of 128
-// gets one 64-wide tile (257 outputs: 2 x 128 + 64 computed columns instead of 3 x 128).
-struct OutTiling {
-    int wide_tiles;    // 128-wide tiles from column 0
-    int tail_begin;    // first column of the 64-wide tail tile, or -1
-};
-inline OutTiling out_tiling(int O)
-{
-    const int rem = O % 128;
-    if (O > 128 && rem >= 1 && rem <= 64) return OutTiling{O / 128, (O / 128) * 128};
-    return OutTiling{(O + 127) / 128, -1};
-}
-
 template <int D, int BN, int VEC, class Basis>
 void launch_fwd(const float* x, const float* C, float* out, int B, int I, int O, int tiles_o, int o_begin,
                 const FwdPlan& p, const typename Basis::Args& ba, hipStream_t s)

@@ -84,6 +84,29 @@ inline NarrowInPlan plan_narrow_in(int64_t B)
     return p;
 }
 
+// Output tiling: 128-wide tiles, except that a remainder of 1..64 columns beyond a multiple of 128
+// gets one 64-wide tile from a second launch (257 outputs: 2 x 128 + 64 computed columns
+// instead of 3 x 128).
+struct OutTiling {
+    int wide_tiles;    // 128-wide tiles from column 0
+    int tail_begin;    // first column of the 64-wide tail tile, or -1
+};
+inline OutTiling out_tiling(int O)
+{
+    const int rem = O % 128;
+    if (O > 128 && rem >= 1 && rem <= 64) return OutTiling{O / 128, (O / 128) * 128};
+    return OutTiling{(O + 127) / 128, -1};
+}
+
+// Time of one launch of `wg` equal workgroups, in units of one workgroup's run time when two share
+// a compute unit.  512 are resident at once; one alone on its unit runs in about 0.6 of that time.
+inline double launch_rounds(int64_t wg)
+{
+    if (wg <= 0) return 0.0;
+    const int64_t full = wg / 512, rem = wg % 512;
+    return (double)full + (rem == 0 ? 0.0 : rem <= 256 ? 0.6 : 1.0);
+}
+
 // --------------------------------------------------------------------- dC
 struct DcPlan {
     int bn;              // output tile width
@@ -113,7 +136,10 @@ inline DcPlan plan_dC(int64_t B, int I, int O, int d)
     DcPlan p;
     p.bn = O <= 64 ? 64 : 128;
     const int bic = dc_tile_features_for(I, d);
-    const int64_t tiles = (int64_t)((I + bic - 1) / bic) * ((O + p.bn - 1) / p.bn);
+    const int64_t tiles_i = (I + bic - 1) / bic;
+    const int64_t tiles = tiles_i * ((O + p.bn - 1) / p.bn);
+    const OutTiling ot = out_tiling(O);
+    const bool mixed = p.bn == 128 && ot.tail_begin >= 0;
     int64_t max_s = (B + 255) / 256;
     const int64_t bytes_per_slice = (int64_t)I * K * O * 4;
     const int64_t max_by_bytes = ((int64_t)512 << 20) / bytes_per_slice;
@@ -126,11 +152,16 @@ inline DcPlan plan_dC(int64_t B, int I, int O, int d)
     int64_t best = 1;
     double best_cost = -1.0;
     for (int64_t sl = 1; sl <= max_s; ++sl) {
-        const int64_t wg = tiles * sl;
-        const int64_t rounds = (wg + 511) / 512;
         int64_t r = (B + sl - 1) / sl;
         r = (r + 31) / 32 * 32;
-        const double kernel = (double)rounds * (double)r * (p.bn / 128.0);
+        double kernel;
+        if (mixed) {
+            // two launches: the 128-wide tiles, then the 64-wide tail tile (about half the time per row)
+            kernel = (double)r * ((double)((tiles_i * ot.wide_tiles * sl + 511) / 512) +
+                                  0.5 * (double)((tiles_i * sl + 511) / 512));
+        } else {
+            kernel = (double)((tiles * sl + 511) / 512) * (double)r * (p.bn / 128.0);
+        }
         const double partials = (double)sl * (double)bytes_per_slice * 2.0 / 4.0e12 / 140.0e-9;
         const double cost = kernel + partials;
         if (best_cost < 0.0 || cost < best_cost * 0.995) { best_cost = cost; best = sl; }
@@ -237,7 +268,29 @@ inline FwdPlan plan_forward(int64_t B, int I, int O, int d)
     const int n_chunks = (I + bi - 1) / bi;
     const int64_t tiles = ((B + 127) / 128) * ((O + (O <= 64 ? 63 : 127)) / (O <= 64 ? 64 : 128));
     FwdPlan p{1, n_chunks};
-    if ((tune_flags() & 8) || tiles >= 256 || n_chunks < 4) return p;
+    if ((tune_flags() & 8) || n_chunks < 4) return p;
+    if (tiles >= 256) {
+        // Enough tiles, but with a tail tile they come as two launches that may each leave compute
+        // units idle (257 outputs at 16000 rows: 250 + 125 workgroups).  Estimated time per range
+        // count, in microseconds: both launches, plus writing and summing the partial planes.
+        const OutTiling ot = out_tiling(O);
+        const int64_t row_tiles = (B + 127) / 128;
+        if (O <= 128 || ot.tail_begin < 0 || row_tiles * ot.wide_tiles >= 384) return p;
+        const double t_chunk = 0.1333 * bi * (d + 1);
+        int best = 1;
+        double best_us = 0.0;
+        for (int sp = 1; sp <= 4 && sp <= n_chunks / 2; ++sp) {
+            const int len = (n_chunks + sp - 1) / sp;
+            double us = t_chunk * len * (launch_rounds(row_tiles * ot.wide_tiles * sp) + 0.5 * launch_rounds(row_tiles * sp));
+            if (sp > 1) us += 6.0 + (2.0 * sp + 1.0) * (double)B * O * 4.0 / 3.0e6;
+            if (sp == 1 || us < best_us * 0.97) { best_us = us; best = sp; }
+        }
+        if (best > 1) {
+            p.chunks_per_split = (n_chunks + best - 1) / best;
+            p.splits = (n_chunks + p.chunks_per_split - 1) / p.chunks_per_split;
+        }
+        return p;
+    }
     int64_t want = (512 + tiles - 1) / tiles;
     if (want > n_chunks / 2) want = n_chunks / 2;      // at least 2 chunks per range
     if (want > 64) want = 64;
