@@ -279,6 +279,20 @@ def test_full_size_row_block_elementwise():
     _check_full(x, C, dy, 0, "c4 first layer, %d rows" % B)
 
 
+def test_forward_split_when_the_wide_launch_would_underfill():
+    """16384 rows x 130 outputs: 128 wide tiles plus 128 tail tiles, each launch under one workgroup per
+    compute unit, so the plan splits the contraction over 512 inputs into ranges (the workspace query says
+    so) and sums the planes.  Every element of y against the oracle."""
+    B, I, O, d = 16384, 512, 130, 3
+    assert binding.chebykan_workspace_bytes(B, I, O, d, binding.CHEBYKAN_PASS_FORWARD) >= 2 * B * O * 4
+    x = wl.make_x(B, I, 5151)
+    C = wl.make_coeff(I, O, d, 5152)
+    (y,) = gpu_layer(x, C)
+    err = oracle.rel_err(y, oracle.forward(x, C))
+    print("split forward with tail tile: y=%.2e" % err, flush=True)
+    assert np.isfinite(y).all() and err <= TOL
+
+
 @pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
 def test_full_size_workload_sampled(name):
     """Whole stack at its real size, in the launch configuration the benchmark times.
