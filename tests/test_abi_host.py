@@ -92,6 +92,10 @@ def test_workspace_matches_the_documented_partial_layout():
     assert binding.chebykan_workspace_bytes(65536, 64, 64, 6, binding.CHEBYKAN_PASS_FORWARD) == 0
     n = binding.chebykan_workspace_bytes(32, 512, 1024, 24, binding.CHEBYKAN_PASS_FORWARD)
     assert n > 0 and n % (32 * 1024 * 4) == 0 and 2 <= n // (32 * 1024 * 4) <= 64
+    # a wide launch that would leave most compute units with one workgroup (250 + 125 tail) is split too
+    n = binding.chebykan_workspace_bytes(16000, 512, 257, 5, binding.CHEBYKAN_PASS_FORWARD)
+    assert n > 0 and n % (16000 * 257 * 4) == 0 and 2 <= n // (16000 * 257 * 4) <= 4
+    assert binding.chebykan_workspace_bytes(16000, 512, 512, 5, binding.CHEBYKAN_PASS_FORWARD) == 0
 
 
 def test_kernel_family_switch_round_trips():
