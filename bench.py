@@ -51,6 +51,8 @@ def parse_args():
                     help="number of distinct (x, dy) input sets cycled through, so inputs are not cache-resident")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--no-cold", action="store_true",
+                    help="skip the cold pass (whole buffer sets rotated through at least 512 MB)")
     ap.add_argument("--family", type=int, default=0, help="kernel family override (0 auto)")
     ap.add_argument("--basis", default="exact", choices=["exact", "lut", "legendre", "hermite", "fourier"],
                     help="exact = Chebyshev recurrences (default); lut = the paper's table-interpolated variant "
@@ -189,6 +191,37 @@ def measured_peaks(torch, binding, stream):
     t_copy, nbytes = timed(lambda: binding.chebykan_calibrate_copy(dst, src, stream), 10)
     return {"mfma_f32_tflops": round(flops / t_mfma / 1e12, 1), "copy_gbs_read_plus_write": round(2 * nbytes / t_copy / 1e9, 1),
             "note": "register-only v_mfma_f32_32x32x2_f32 loop on 512 workgroups; 256 MiB device copy"}
+
+
+def cold_pass(st, make_stack, torch, rounds=3):
+    """Steps over whole buffer sets (inputs, activations, gradients, workspaces) rotated through at least
+    512 MB, so that no step finds its tensors in the caches from the one before; event-timed on the launch
+    stream.  The default timing rotates only the inputs: activations are produced and consumed inside the
+    step, as in training, and may stay cache-resident between steps."""
+    def tensors(s):
+        out = [s.x0_sets[0], s.dy_sets[0], s.stack_ws] + s.C + s.y + s.dx + s.dC + s.ws
+        return [t for t in out if t is not None]
+    per_set = sum(t.numel() * t.element_size() for t in tensors(st))
+    n_sets = int(min(16, max(2, -(-(512 << 20) // per_set))))
+    sets = [st]
+    for _ in range(n_sets - 1):
+        s = make_stack()
+        s.stream = st.stream
+        sets.append(s)
+    for s in sets:
+        s.step_fused_calls(0)
+    torch.cuda.synchronize()
+    n = rounds * n_sets
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    ev[0].record(st.stream)
+    for k in range(n):
+        sets[k % n_sets].step_fused_calls(0)
+        ev[k + 1].record(st.stream)
+    torch.cuda.synchronize()
+    ms = np.array([ev[k].elapsed_time(ev[k + 1]) for k in range(n)])
+    del sets
+    return {"buffer_sets": n_sets, "bytes_rotated": int(per_set * n_sets), "steps": n,
+            "step_ms_median": float(np.median(ms)), "step_ms_min": float(np.min(ms))}
 
 
 def cpu_baseline(w, wl, target_seconds, lut_size=0, kind=0):
@@ -377,6 +410,8 @@ def main():
         "calls": per_call,
     }
     line["measured_peaks"] = measured_peaks(torch, binding, st.stream)
+    if not args.no_cold:
+        line["cold"] = cold_pass(st, lambda: Stack(w, 1, torch, binding, wl, lut, kind), torch)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, wl, args.cpu_seconds, args.lut_size if lut is not None else 0, kind)
     print(json.dumps(line), flush=True)
