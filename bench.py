@@ -391,6 +391,9 @@ def main():
 
     total_flops = sum(wl.layer_flops(B, i, o, w.degree) for (i, o) in w.layers)
     total_bytes = sum(wl.layer_bytes(B, i, o, w.degree) for (i, o) in w.layers)
+    # composite roofline of the step: per layer the larger of its MFMA time and its HBM time at the published peaks
+    composite_us = sum(max(wl.layer_flops(B, i, o, w.degree) / (PEAK_MFMA_F32_TFLOPS * 1e12),
+                           wl.layer_bytes(B, i, o, w.degree) / (PEAK_HBM_GBS * 1e9)) for (i, o) in w.layers) * 1e6
     line = {
         "metric": "Cheby-KAN fwd+bwd samples/s", "value": B / (ms_per_step * 1e-3), "unit": "samples/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -406,6 +409,8 @@ def main():
         "mfma_frac": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS,
         "hbm_frac": total_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "roofline": roof,
+        "composite_roofline": {"us": round(composite_us, 2), "frac": round(composite_us / (ms_per_step * 1e3), 4),
+                               "note": "sum over layers of max(MFMA time, HBM time) at the published peaks / measured step"},
         "event_timed": step_stats,
         "calls": per_call,
     }
