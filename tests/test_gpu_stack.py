@@ -65,6 +65,31 @@ def test_stack_calls_against_the_oracle(widths, degree, B):
         assert oracle.rel_err(acts[-1].cpu().numpy(), y.cpu().numpy().astype(np.float64)) <= TOL
 
 
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
+def test_full_size_workload_through_the_stack_calls(name):
+    """Each workload at its real size through the two calls the benchmark times (for the tabular stack:
+    the single-launch forward, the one-kernel first-layer backward and the shared slice-sum launch).
+    Sampled outputs of every layer against the oracle, on the GPU's own fp32 layer inputs."""
+    from test_gpu_parity import _sampled_layer_check
+    w = wl.WORKLOADS[name]
+    x0, Cs, dy_last = wl.workload_inputs(w)
+    B, widths, degree = w.batch, list(w.widths), w.degree
+    dev = lambda a: torch.from_numpy(a).cuda()
+    Cd = [dev(c) for c in Cs]
+    acts = [dev(x0)] + [torch.full((B, wd), float("nan"), device="cuda") for wd in widths[1:]]
+    ws = binding.alloc_stack_workspace(B, widths, degree)
+    binding.chebykan_stack_forward(Cd, acts, ws)
+    grads = [torch.full((B, wd), float("nan"), device="cuda") for wd in widths[:-1]] + [dev(dy_last)]
+    dCd = [torch.full_like(c, float("nan")) for c in Cd]
+    binding.chebykan_stack_backward(Cd, acts, grads, dCd, ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(7 + w.index)
+    for l in range(len(Cs)):
+        _sampled_layer_check(acts[l].cpu().numpy(), Cs[l], grads[l + 1].cpu().numpy(), acts[l + 1].cpu().numpy(),
+                             grads[l].cpu().numpy(), dCd[l].cpu().numpy(), rng,
+                             "%s stack calls, layer %d %s" % (name, l, w.layers[l]))
+
+
 def test_stack_skips_and_errors():
     widths, degree, B = (8, 16, 4), 4, 64
     Cd = [torch.from_numpy(wl.make_coeff(i, o, degree, 5)).cuda() for i, o in zip(widths[:-1], widths[1:])]
