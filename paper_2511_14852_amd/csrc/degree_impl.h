@@ -2,6 +2,7 @@
 // translation units (deg_NN.hip), each of which instantiates degree_forward<D> and
 // degree_backward<D> for its degree; the dispatcher only sees their declarations.
 #pragma once
+#include <type_traits>
 #include <hip/hip_runtime.h>
 
 #include "chain_kernels.h"
@@ -61,11 +62,11 @@ inline void launch_sum_slices(const float* partial, float* out, int64_t n, int s
 }
 
 // ------------------------------------------------------------------ forward
-template <int D, int BN, int VEC, class Basis>
+template <int D, int BN, int VEC, class Basis, int RB = 4>
 void launch_fwd(const float* x, const float* C, float* out, int B, int I, int O, int tiles_o, int o_begin,
                 const FwdPlan& p, const typename Basis::Args& ba, hipStream_t s)
 {
-    using Cfg = FwdCfg<D, BN, forward_chunk_features(D), VEC>;
+    using Cfg = FwdCfg<D, BN, forward_chunk_features(D), VEC, RB>;
     static DeviceOnce once;
     if (once.first()) allow_lds(fwd_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES);
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * tiles_o;
@@ -87,7 +88,16 @@ void pick_fwd(const float* x, const float* C, float* y, float* partial, int B, i
         else launch_fwd<D, 64, 1, Basis>(x, C, out, B, I, O, 1, 0, p, ba, s);
     } else {
         const OutTiling t = out_tiling(O);
-        if (vec) launch_fwd<D, 128, 4, Basis>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s);
+        // batches of at most 64 rows (the paper's operator shapes): waves side by side, no MFMAs on
+        // row blocks that are all padding; built for the exact basis at the degrees those shapes use
+        constexpr bool small_batch_built = D >= 7 && std::is_same<Basis, ExactBasis>::value;
+        bool done = false;
+        if constexpr (small_batch_built) {
+            if (vec && B <= 32) { launch_fwd<D, 128, 4, Basis, 1>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s); done = true; }
+            else if (vec && B <= 64) { launch_fwd<D, 128, 4, Basis, 2>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s); done = true; }
+        }
+        if (done) {}
+        else if (vec) launch_fwd<D, 128, 4, Basis>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s);
         else launch_fwd<D, 128, 1, Basis>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s);
         if (t.tail_begin >= 0) {
             if (vec) launch_fwd<D, 64, 4, Basis>(x, C, out, B, I, O, 1, t.tail_begin, p, ba, s);
@@ -118,33 +128,37 @@ void launch_dC_combine(const float* partial, float* dC, int I, int O, int slices
 }
 
 template <int D, int BN, int VEC, int BIC, class Basis>
-void launch_dC(const float* x, const float* dy, float* partial, int B, int I, int O, int tiles_o, int o_begin,
-               const DcPlan& p, const typename Basis::Args& ba, hipStream_t s)
+void launch_dC(const float* x, const float* dy, float* partial, float* direct, int B, int I, int O, int tiles_o,
+               int o_begin, const DcPlan& p, const typename Basis::Args& ba, hipStream_t s)
 {
     using Cfg = DcCfg<D, BN, VEC, BIC>;
+    constexpr int kAllow = Basis::kTable ? MAX_LDS_BYTES
+                                         : (Cfg::DIRECT_LDS_BYTES > Cfg::LDS_BYTES ? Cfg::DIRECT_LDS_BYTES : Cfg::LDS_BYTES);
     static DeviceOnce once;
-    if (once.first()) allow_lds(dC_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES);
+    if (once.first()) allow_lds(dC_mfma_kernel<Cfg, Basis>, kAllow);
     const int tiles_i = (I + Cfg::BIC - 1) / Cfg::BIC;
+    size_t lds_bytes = Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1);
+    if (direct && lds_bytes < (size_t)Cfg::DIRECT_LDS_BYTES) lds_bytes = Cfg::DIRECT_LDS_BYTES;   // the epilogue's layout turn
     hipLaunchKernelGGL((dC_mfma_kernel<Cfg, Basis>), dim3((unsigned)((int64_t)tiles_i * tiles_o * p.slices)),
-                       dim3(MFMA_THREADS), Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, dy, partial, B, I, O,
-                       tiles_o, o_begin, tiles_i, p.slices, p.rows_per_slice, ba);
+                       dim3(MFMA_THREADS), lds_bytes, s, x, dy, partial, B, I, O, tiles_o, o_begin, tiles_i, p.slices,
+                       p.rows_per_slice, ba, direct);
 }
 
 template <int D, int BIC, class Basis>
-void pick_dC_tile(const float* x, const float* dy, float* partial, int B, int I, int O, const DcPlan& p,
+void pick_dC_tile(const float* x, const float* dy, float* partial, float* direct, int B, int I, int O, const DcPlan& p,
                   const typename Basis::Args& ba, hipStream_t s)
 {
     const bool vec = !(tune_flags() & 16384);   // see pick_fwd
     if (p.bn == 64) {
-        if (vec) launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, B, I, O, 1, 0, p, ba, s);
-        else launch_dC<D, 64, 1, BIC, Basis>(x, dy, partial, B, I, O, 1, 0, p, ba, s);
+        if (vec) launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, direct, B, I, O, 1, 0, p, ba, s);
+        else launch_dC<D, 64, 1, BIC, Basis>(x, dy, partial, direct, B, I, O, 1, 0, p, ba, s);
     } else {
         const OutTiling t = out_tiling(O);
-        if (vec) launch_dC<D, 128, 4, BIC, Basis>(x, dy, partial, B, I, O, t.wide_tiles, 0, p, ba, s);
-        else launch_dC<D, 128, 1, BIC, Basis>(x, dy, partial, B, I, O, t.wide_tiles, 0, p, ba, s);
+        if (vec) launch_dC<D, 128, 4, BIC, Basis>(x, dy, partial, direct, B, I, O, t.wide_tiles, 0, p, ba, s);
+        else launch_dC<D, 128, 1, BIC, Basis>(x, dy, partial, direct, B, I, O, t.wide_tiles, 0, p, ba, s);
         if (t.tail_begin >= 0) {
-            if (vec) launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, B, I, O, 1, t.tail_begin, p, ba, s);
-            else launch_dC<D, 64, 1, BIC, Basis>(x, dy, partial, B, I, O, 1, t.tail_begin, p, ba, s);
+            if (vec) launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, direct, B, I, O, 1, t.tail_begin, p, ba, s);
+            else launch_dC<D, 64, 1, BIC, Basis>(x, dy, partial, direct, B, I, O, 1, t.tail_begin, p, ba, s);
         }
     }
 }
@@ -153,21 +167,30 @@ template <int D, class Basis>
 void pick_dC(const float* x, const float* dy, float* dC, float* partial, int B, int I, int O, const DcPlan& p,
              const typename Basis::Args& ba, hipStream_t s)
 {
+    // With one batch slice the tiles are final: the slice kernel writes dC itself, in the caller's
+    // layout, and the slice sum is not launched.  Only with enough tiles: each workgroup turns its
+    // own tile, and a handful of workgroups do that slower than the many blocks of the sum kernel
+    // (measured: 3 and 6 tiles lose 1-4 us, 128 and 824 tiles gain 4 and 9 us).
+    // Bit 15 (value 32768) of the tuning mask turns this off.
+    const int bic = dc_tile_features_for(I, D);
+    const int64_t tiles = (int64_t)((I + bic - 1) / bic) * ((O + p.bn - 1) / p.bn);
+    // Bit 16 (value 65536): also with few tiles (tests of that epilogue on small inputs).
+    float* direct = (p.slices == 1 && (tiles >= 64 || (tune_flags() & 65536)) && !(tune_flags() & 32768)) ? dC : nullptr;
     if constexpr (D == 6) {
-        if (dc_tile_features_for(I, D) == 16) pick_dC_tile<D, 16, Basis>(x, dy, partial, B, I, O, p, ba, s);
-        else pick_dC_tile<D, dc_tile_features(D), Basis>(x, dy, partial, B, I, O, p, ba, s);
+        if (dc_tile_features_for(I, D) == 16) pick_dC_tile<D, 16, Basis>(x, dy, partial, direct, B, I, O, p, ba, s);
+        else pick_dC_tile<D, dc_tile_features(D), Basis>(x, dy, partial, direct, B, I, O, p, ba, s);
     } else {
-        pick_dC_tile<D, dc_tile_features(D), Basis>(x, dy, partial, B, I, O, p, ba, s);
+        pick_dC_tile<D, dc_tile_features(D), Basis>(x, dy, partial, direct, B, I, O, p, ba, s);
     }
-    launch_dC_combine<D>(partial, dC, I, O, p.slices, s);
+    if (!direct) launch_dC_combine<D>(partial, dC, I, O, p.slices, s);
 }
 
 // --------------------------------------------------------------------- dx
-template <int D, int NB, int VEC, class Basis>
+template <int D, int NB, int VEC, class Basis, int RB = 4>
 void launch_dx(const float* x, const float* C, const float* dy, float* dx, float* partial, int B, int I, int O,
                const DxPlan& p, const typename Basis::Args& ba, hipStream_t s)
 {
-    using Cfg = DxCfg<D, NB, VEC>;
+    using Cfg = DxCfg<D, NB, VEC, RB>;
     static DeviceOnce once;
     if (once.first()) allow_lds(dx_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES);
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * p.feature_tiles;
@@ -201,6 +224,23 @@ void pick_dx(const float* x, const float* C, const float* dy, float* dx, float* 
         if (p.per_lane) {
             if (vec) launch_dx2<D, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s);
             else launch_dx2<D, 1, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s);
+            done = true;
+        }
+    }
+    // batches of at most 64 rows: one column block per wave (see DxCfg); built like the forward variant
+    if constexpr (D >= 7 && std::is_same<Basis, ExactBasis>::value) {
+        if (!done && vec && B <= 64) {
+            const bool one = B <= 32;
+            switch (p.nb) {
+                case 1: one ? launch_dx<D, 1, 4, Basis, 1>(x, C, dy, dx, partial, B, I, O, p, ba, s)
+                            : launch_dx<D, 1, 4, Basis, 2>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
+                case 2: one ? launch_dx<D, 2, 4, Basis, 1>(x, C, dy, dx, partial, B, I, O, p, ba, s)
+                            : launch_dx<D, 2, 4, Basis, 2>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
+                case 3: one ? launch_dx<D, 3, 4, Basis, 1>(x, C, dy, dx, partial, B, I, O, p, ba, s)
+                            : launch_dx<D, 3, 4, Basis, 2>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
+                default: one ? launch_dx<D, 4, 4, Basis, 1>(x, C, dy, dx, partial, B, I, O, p, ba, s)
+                             : launch_dx<D, 4, 4, Basis, 2>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
+            }
             done = true;
         }
     }

@@ -61,11 +61,15 @@ __device__ __forceinline__ floatx16 zero16()
 __device__ __forceinline__ int mfma_row(int r, int h) { return 8 * (r >> 2) + 4 * h + (r & 3); }
 
 // ============================================================== forward
-template <int D_, int BN_, int BI_, int VEC_>
+// RB_ = 32-row blocks of the tile that can hold real rows.  4: the waves form a 2 x 2 grid
+// (64 rows x BN/2 outputs each).  1 or 2 (a batch of at most 32 or 64 rows, BN = 128): the four
+// waves stand side by side, 32 outputs each, and issue no MFMA for row blocks that are all padding.
+template <int D_, int BN_, int BI_, int VEC_, int RB_ = 4>
 struct FwdCfg {
     static constexpr int D = D_, K = D_ + 1, KP = K | 1;      // KP: odd per-output stride in LDS
-    static constexpr int BM = 128, BN = BN_, BI = BI_, VEC = VEC_;
-    static constexpr int WN = BN / 2, TM = 2, TN = WN / 32;
+    static constexpr int BM = 128, BN = BN_, BI = BI_, VEC = VEC_, RB = RB_;
+    static constexpr int WN = RB == 4 ? BN / 2 : BN / 4, TM = RB == 4 ? 2 : RB, TN = WN / 32;
+    static_assert(RB == 4 || ((RB == 1 || RB == 2) && BN == 128), "small-batch tiles are 128 outputs wide");
     static constexpr int CH = BI * K;                          // contraction terms per chunk
     static constexpr int SA = CH | 1;                          // odd row stride of the Phi tile
     static constexpr int SS = BN * KP;                         // stride between feature slabs
@@ -188,7 +192,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
 
     // --- consumer role
     const int lane = t & 63, wave = t >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = Cfg::RB == 4 ? wave >> 1 : 0, wn = Cfg::RB == 4 ? wave & 1 : wave;
     const int l32 = lane & 31, h = lane >> 5;
     const int aBase = (wm * 64 + l32) * SA + h * (BI / 2) * K;
     const int bBase = h * (BI / 2) * SS + (wn * WN + l32) * KP;
@@ -302,6 +306,10 @@ struct DcCfg {
     static_assert(NEB % (VEC * MFMA_THREADS) == 0, "dy tile must split evenly");
     static_assert(A_FLOATS % 4 == 0, "dy tile must stay 16-byte aligned");
     static_assert(BIC >= 1 && BMR <= 128, "tile rows");
+    // single-slice launches turn their tile to the caller's [i][o][k] layout in LDS: [feature][output][K|1]
+    static constexpr int KP = K | 1;
+    static constexpr int DIRECT_FLOATS = BIC * BN * KP;
+    static constexpr int DIRECT_LDS_BYTES = DIRECT_FLOATS * 4 > LDS_BYTES ? DIRECT_FLOATS * 4 : LDS_BYTES;
 };
 
 // partial[s][(i,k)][o] = sum over the rows of batch slice s of T_k(tanh x[b,i]) dy[b,o]
@@ -314,7 +322,7 @@ template <class Cfg, class Basis = ExactBasis>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ partial,
                int B, int I, int O, int n_tiles_o, int o_begin, int n_tiles_i, int n_slices, int rows_per_slice,
-               typename Basis::Args bargs)
+               typename Basis::Args bargs, float* __restrict__ direct)
 {
     constexpr int D = Cfg::D, K = Cfg::K, BN = Cfg::BN, VEC = Cfg::VEC, BB = Cfg::BB, BIC = Cfg::BIC;
     constexpr int SMA = Cfg::SMA, SNB = Cfg::SNB, TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
@@ -467,6 +475,35 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
 
     CHEBYKAN_PROBE(2);
     const int64_t IK = (int64_t)I * K;
+    if (direct) {
+        // One slice only (the host passes `direct` = dC then): the tile is final.  It goes through LDS
+        // as [feature][output][K|1] and leaves as one contiguous run of outputs x K per feature - the
+        // caller's [i][o][k] layout - so no partial tensor and no second kernel are needed.
+        constexpr int KP = Cfg::KP;
+        __syncthreads();   // every wave has finished reading the last stage
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const floatx16 v = total[i][j] + acc[i][j];
+                const int col = wn * WN + j * 32 + l32;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ml = wm * 64 + i * 32 + mfma_row(r, h);
+                    if (ml < Cfg::BMR) lds[((ml / K) * BN + col) * KP + ml % K] = v[r];
+                }
+            }
+        __syncthreads();
+        const int cols_here = O - o0 < BN ? O - o0 : BN;
+        for (int e = t; e < BIC * BN * K; e += MFMA_THREADS) {
+            const int il = e / (BN * K), rem = e % (BN * K);
+            const int col = rem / K, k = rem % K;
+            if (i0 + il < I && col < cols_here)
+                direct[((int64_t)(i0 + il) * O + o0) * K + rem] = lds[(il * BN + col) * KP + k];
+        }
+        CHEBYKAN_PROBE(3);
+        return;
+    }
     float* out = partial + (int64_t)slice * IK * O;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -594,9 +631,14 @@ __global__ void __launch_bounds__(1024) stack_combine_kernel(CombineArgs a)
 }
 
 // ============================================================ input gradient
-template <int D_, int NB_, int VEC_>
+// RB_ = 32-row blocks of the tile that can hold real rows.  4: wave w takes row block w and all
+// NB column blocks.  1 or 2 (a batch of at most 32 or 64 rows): wave w takes column block w and
+// the RB row blocks, so no MFMA is issued for row blocks that are all padding.
+template <int D_, int NB_, int VEC_, int RB_ = 4>
 struct DxCfg {
-    static constexpr int D = D_, K = D_ + 1, NB = NB_, VEC = VEC_;
+    static constexpr int D = D_, K = D_ + 1, NB = NB_, VEC = VEC_, RB = RB_;
+    static constexpr int NACC = RB == 4 ? NB : RB;      // accumulators per wave
+    static_assert(RB == 4 || RB == 1 || RB == 2, "row blocks");
     static constexpr int BM = 128;
     static constexpr int BNC = 32 * NB;                 // tile columns (NB MFMA column blocks)
     static constexpr int BIX = BNC / D;                 // input features per tile
@@ -725,19 +767,35 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
         bBase[j] = il * SSX + h * (BO / 2) * K + kq + 1;
     }
 
-    floatx16 acc[NB], total[NB];
+    constexpr int NACC = Cfg::NACC;
+    floatx16 acc[NACC], total[NACC];
 #pragma unroll
-    for (int j = 0; j < NB; ++j) { acc[j] = zero16(); total[j] = zero16(); }
+    for (int j = 0; j < NACC; ++j) { acc[j] = zero16(); total[j] = zero16(); }
+    // small batch: this wave's column block (a wave beyond the last block repeats it and stores nothing)
+    const int my_block = wave < NB ? wave : NB - 1;
+    int bBaseSmall = bBase[0];
+#pragma unroll
+    for (int j = 1; j < NB; ++j) bBaseSmall = my_block == j ? bBase[j] : bBaseSmall;
+    const int aBaseSmall = l32 * SAX + h * (BO / 2);
 
     auto mfma_steps = [&](const float* sA, const float* sB, int s0, int s1) {
 #pragma unroll
         for (int s = s0; s < s1; ++s) {
-            const float a = sA[aBase + s];
-            float b[NB];
+            if constexpr (Cfg::RB == 4) {
+                const float a = sA[aBase + s];
+                float b[NB];
 #pragma unroll
-            for (int j = 0; j < NB; ++j) b[j] = sB[bBase[j] + s * K];
+                for (int j = 0; j < NB; ++j) b[j] = sB[bBase[j] + s * K];
 #pragma unroll
-            for (int j = 0; j < NB; ++j) acc[j] = mfma32(a, b[j], acc[j]);
+                for (int j = 0; j < NB; ++j) acc[j] = mfma32(a, b[j], acc[j]);
+            } else {
+                const float b = sB[bBaseSmall + s * K];
+                float a[NACC];
+#pragma unroll
+                for (int i = 0; i < NACC; ++i) a[i] = sA[aBaseSmall + i * 32 * SAX + s];
+#pragma unroll
+                for (int i = 0; i < NACC; ++i) acc[i] = mfma32(a[i], b, acc[i]);
+            }
         }
     };
 
@@ -760,27 +818,37 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
         load_chunk((c_begin + c + 2) * BO);
         mfma_steps(sA, sA + Cfg::A_FLOATS, Cfg::NSTEP / 2, Cfg::NSTEP);
 #pragma unroll
-        for (int q = 0; q < Cfg::NSTEP * NB; ++q) {
+        for (int q = 0; q < Cfg::NSTEP * NACC; ++q) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-            __builtin_amdgcn_sched_group_barrier(0x402, 2, 0);   // two vector-ALU
-            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
+            __builtin_amdgcn_sched_group_barrier(0x402, Cfg::RB == 4 ? 2 : 4, 0);   // vector-ALU
+            __builtin_amdgcn_sched_group_barrier(0x200, Cfg::RB == 4 ? 1 : 2, 0);   // LDS writes
             __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
         }
         if ((c + 1) % Cfg::FOLD == 0) {
 #pragma unroll
-            for (int j = 0; j < NB; ++j) { total[j] += acc[j]; acc[j] = zero16(); }
+            for (int j = 0; j < NACC; ++j) { total[j] += acc[j]; acc[j] = zero16(); }
         }
     }
 
     // --- epilogue: G tile to LDS, then each thread finishes (row, feature) pairs
     __syncthreads();
+    if constexpr (Cfg::RB == 4) {
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        const floatx16 v = total[j] + acc[j];
-        const int col = j * 32 + l32;
+        for (int j = 0; j < NB; ++j) {
+            const floatx16 v = total[j] + acc[j];
+            const int col = j * 32 + l32;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) lds[(wave * 32 + mfma_row(r, h)) * SG + col] = v[r];
+            for (int r = 0; r < 16; ++r) lds[(wave * 32 + mfma_row(r, h)) * SG + col] = v[r];
+        }
+    } else if (wave < NB) {   // rows past 32 * RB of the G tile are not written and not read (they are past B)
+#pragma unroll
+        for (int i = 0; i < NACC; ++i) {
+            const floatx16 v = total[i] + acc[i];
+            const int col = wave * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) lds[(i * 32 + mfma_row(r, h)) * SG + col] = v[r];
+        }
     }
     __syncthreads();
 #pragma unroll

@@ -43,6 +43,8 @@ constexpr bool chain_degree(int d) { return d >= 3 && d <= 6; }
 // Bit 11 (value 2048): a stack's backward sums each layer's slices in its own launch.
 // Bit 14 (value 16384): scalar instead of 16-byte loads in the forward and dC producers.
 // Bit 9 (value 512): fuse a stack's forward at any batch size (tests of that kernel on small inputs).
+// Bit 15 (value 32768): a single-slice coefficient gradient goes through the partial tensor and the slice sum
+//   instead of writing dC from the slice kernel.  Bit 16 (value 65536): that direct write also with few tiles.
 inline int tune_flags()
 {
     static const int flags = [] {

@@ -57,7 +57,7 @@ def emu_driver():
     return exe
 
 
-def _run(exe, B, I, O, d, family, seed=1, lut_size=0, basis=0):
+def _run(exe, B, I, O, d, family, seed=1, lut_size=0, basis=0, tune=None):
     x = wl.make_x(B, I, seed)
     C = wl.make_coeff(I, O, d, seed + 1)
     dy = wl.make_dy(B, O, seed + 2)
@@ -73,7 +73,8 @@ def _run(exe, B, I, O, d, family, seed=1, lut_size=0, basis=0):
             args.append(str(lut_size))
         elif basis:
             args += ["0", str(basis)]
-        r = subprocess.run(args, capture_output=True, text=True, timeout=600)
+        env = dict(os.environ, CHEBYKAN_TUNE=str(tune)) if tune is not None else None
+        r = subprocess.run(args, capture_output=True, text=True, timeout=600, env=env)
         assert r.returncode == 0, (r.stdout[-1000:], r.stderr[-4000:])
         y = np.fromfile(os.path.join(td, "y.bin"), dtype=np.float32).reshape(B, O)
         dx = np.fromfile(os.path.join(td, "dx.bin"), dtype=np.float32).reshape(B, I)
@@ -141,6 +142,9 @@ CASES = [
     (200, 8, 64, 6),
     (100, 5, 40, 8),
     (300, 16, 33, 3),
+    # at most 32 and at most 64 rows at the degrees of the paper's operator shapes: waves side by side
+    (30, 9, 200, 8),
+    (50, 20, 130, 15),
 ]
 
 
@@ -148,6 +152,14 @@ CASES = [
 def test_mfma_family_on_cpu_emulation(emu_driver, case):
     B, I, O, d = case
     errs = _run(emu_driver, B, I, O, d, family=2)
+    assert all(np.isfinite(e) and e <= 1e-5 for e in errs), errs
+
+
+@pytest.mark.parametrize("case", [(129, 5, 257, 8), (40, 12, 70, 15)], ids=lambda c: "B%d_I%d_O%d_d%d" % c)
+def test_single_slice_dC_written_by_the_slice_kernel(emu_driver, case):
+    """One batch slice: the coefficient-gradient kernel turns its tile to [i][o][k] in LDS and writes dC
+    itself (forced here at a small tile count; both output-tile widths, ragged tiles)."""
+    errs = _run(emu_driver, *case, family=2, tune=65536)
     assert all(np.isfinite(e) and e <= 1e-5 for e in errs), errs
 
 

@@ -114,6 +114,8 @@ SMALL_SHAPES = [
     (8, 65535, 8, 2),
     (8, 8, 65535, 2),
     (16, 65535, 3, 2),
+    # one batch slice and enough tiles for the slice kernel to write dC itself, 128-wide tiles and a tail tile
+    (100, 1000, 130, 3),
 ]
 
 
