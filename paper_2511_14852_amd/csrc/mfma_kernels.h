@@ -495,11 +495,27 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
             }
         __syncthreads();
         const int cols_here = O - o0 < BN ? O - o0 : BN;
-        for (int e = t; e < BIC * BN * K; e += MFMA_THREADS) {
-            const int il = e / (BN * K), rem = e % (BN * K);
-            const int col = rem / K, k = rem % K;
-            if (i0 + il < I && col < cols_here)
-                direct[((int64_t)(i0 + il) * O + o0) * K + rem] = lds[(il * BN + col) * KP + k];
+        bool copied = false;
+        if constexpr (KP == K) {
+            // odd K: the LDS tile is already the run, element for element; with O a multiple of 4 every
+            // run starts 16-byte aligned and its valid part is whole float4s
+            if ((O & 3) == 0 && (reinterpret_cast<uintptr_t>(direct) & 15) == 0) {
+                for (int e = t * 4; e < BIC * BN * K; e += MFMA_THREADS * 4) {
+                    const int il = e / (BN * K), rem = e % (BN * K);
+                    if (i0 + il < I && rem < cols_here * K)
+                        *reinterpret_cast<floatx4*>(direct + ((int64_t)(i0 + il) * O + o0) * K + rem) =
+                            *reinterpret_cast<const floatx4*>(lds + il * BN * K + rem);
+                }
+                copied = true;
+            }
+        }
+        if (!copied) {
+            for (int e = t; e < BIC * BN * K; e += MFMA_THREADS) {
+                const int il = e / (BN * K), rem = e % (BN * K);
+                const int col = rem / K, k = rem % K;
+                if (i0 + il < I && col < cols_here)
+                    direct[((int64_t)(i0 + il) * O + o0) * K + rem] = lds[(il * BN + col) * KP + k];
+            }
         }
         CHEBYKAN_PROBE(3);
         return;
