@@ -170,12 +170,14 @@ void pick_dC(const float* x, const float* dy, float* dC, float* partial, int B, 
     // With one batch slice the tiles are final: the slice kernel writes dC itself, in the caller's
     // layout, and the slice sum is not launched.  Only with enough tiles: each workgroup turns its
     // own tile, and a handful of workgroups do that slower than the many blocks of the sum kernel
-    // (measured: 3 and 6 tiles lose 1-4 us, 128 and 824 tiles gain 4 and 9 us).
+    // (measured with the element-wise copy: 3 and 6 tiles lose 1-4 us, 128 and 824 tiles gain 4 and 9 us).
     // Bit 15 (value 32768) of the tuning mask turns this off.
     const int bic = dc_tile_features_for(I, D);
     const int64_t tiles = (int64_t)((I + bic - 1) / bic) * ((O + p.bn - 1) / p.bn);
     // Bit 16 (value 65536): also with few tiles (tests of that epilogue on small inputs).
-    float* direct = (p.slices == 1 && (tiles >= 64 || (tune_flags() & 65536)) && !(tune_flags() & 32768)) ? dC : nullptr;
+    // With an odd K and 16-byte aligned runs the tile leaves LDS as whole float4s, which wins at any tile count.
+    const bool vector_out = (D + 1) % 2 == 1 && O % 4 == 0 && aligned16(dC);
+    float* direct = (p.slices == 1 && (tiles >= 64 || vector_out || (tune_flags() & 65536)) && !(tune_flags() & 32768)) ? dC : nullptr;
     if constexpr (D == 6) {
         if (dc_tile_features_for(I, D) == 16) pick_dC_tile<D, 16, Basis>(x, dy, partial, direct, B, I, O, p, ba, s);
         else pick_dC_tile<D, dc_tile_features(D), Basis>(x, dy, partial, direct, B, I, O, p, ba, s);
