@@ -45,6 +45,7 @@ constexpr bool chain_degree(int d) { return d >= 3 && d <= 6; }
 // Bit 9 (value 512): fuse a stack's forward at any batch size (tests of that kernel on small inputs).
 // Bit 15 (value 32768): a single-slice coefficient gradient goes through the partial tensor and the slice sum
 //   instead of writing dC from the slice kernel.  Bit 16 (value 65536): that direct write also with few tiles.
+// Bit 17 (value 131072): small batches keep at least 256 rows per coefficient-gradient slice.
 inline int tune_flags()
 {
     static const int flags = [] {
@@ -142,7 +143,10 @@ inline DcPlan plan_dC(int64_t B, int I, int O, int d)
     const int64_t tiles = tiles_i * ((O + p.bn - 1) / p.bn);
     const OutTiling ot = out_tiling(O);
     const bool mixed = p.bn == 128 && ot.tail_begin >= 0;
-    int64_t max_s = (B + 255) / 256;
+    // at least 256 rows per slice; a small batch with few tiles may go down to one 32-row chunk per
+    // workgroup, which shortens the serial chain of chunks when only a handful of workgroups exist
+    const int64_t min_rows = (tiles < 64 && B < 4096 && !(tune_flags() & 131072)) ? 32 : 256;
+    int64_t max_s = (B + min_rows - 1) / min_rows;
     const int64_t bytes_per_slice = (int64_t)I * K * O * 4;
     const int64_t max_by_bytes = ((int64_t)512 << 20) / bytes_per_slice;
     if (max_s > max_by_bytes) max_s = max_by_bytes;
@@ -165,7 +169,8 @@ inline DcPlan plan_dC(int64_t B, int I, int O, int d)
             kernel = (double)((tiles * sl + 511) / 512) * (double)r * (p.bn / 128.0);
         }
         const double partials = (double)sl * (double)bytes_per_slice * 2.0 / 4.0e12 / 140.0e-9;
-        const double cost = kernel + partials;
+        // more than one slice needs the slice-sum launch (about 6 us, 40 row units) that a single slice avoids
+        const double cost = kernel + partials + (sl > 1 ? 40.0 : 0.0);
         if (best_cost < 0.0 || cost < best_cost * 0.995) { best_cost = cost; best = sl; }
     }
     int64_t rows = (B + best - 1) / best;
