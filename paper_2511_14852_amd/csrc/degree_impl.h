@@ -175,8 +175,8 @@ void pick_dC(const float* x, const float* dy, float* dC, float* partial, int B, 
     const int bic = dc_tile_features_for(I, D);
     const int64_t tiles = (int64_t)((I + bic - 1) / bic) * ((O + p.bn - 1) / p.bn);
     // Bit 16 (value 65536): also with few tiles (tests of that epilogue on small inputs).
-    // With an odd K and 16-byte aligned runs the tile leaves LDS as whole float4s, which wins at any tile count.
-    const bool vector_out = (D + 1) % 2 == 1 && O % 4 == 0 && aligned16(dC);
+    // With 16-byte aligned runs the tile leaves as whole float4 stores, which wins at any tile count.
+    const bool vector_out = O % 4 == 0 && aligned16(dC);
     float* direct = (p.slices == 1 && (tiles >= 64 || vector_out || (tune_flags() & 65536)) && !(tune_flags() & 32768)) ? dC : nullptr;
     if constexpr (D == 6) {
         if (dc_tile_features_for(I, D) == 16) pick_dC_tile<D, 16, Basis>(x, dy, partial, direct, B, I, O, p, ba, s);

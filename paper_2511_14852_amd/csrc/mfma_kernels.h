@@ -509,6 +509,21 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
                 copied = true;
             }
         }
+        if constexpr (KP != K) {
+            // even K: the LDS rows are padded, so four elements are gathered; the store is still one float4
+            if ((O & 3) == 0 && (reinterpret_cast<uintptr_t>(direct) & 15) == 0) {
+                for (int e = t * 4; e < BIC * BN * K; e += MFMA_THREADS * 4) {
+                    const int il = e / (BN * K), rem = e % (BN * K);
+                    if (i0 + il < I && rem < cols_here * K) {
+                        floatx4 v;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) v[q] = lds[(il * BN + (rem + q) / K) * KP + (rem + q) % K];
+                        *reinterpret_cast<floatx4*>(direct + ((int64_t)(i0 + il) * O + o0) * K + rem) = v;
+                    }
+                }
+                copied = true;
+            }
+        }
         if (!copied) {
             for (int e = t; e < BIC * BN * K; e += MFMA_THREADS) {
                 const int il = e / (BN * K), rem = e % (BN * K);

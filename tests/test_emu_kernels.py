@@ -155,7 +155,7 @@ def test_mfma_family_on_cpu_emulation(emu_driver, case):
     assert all(np.isfinite(e) and e <= 1e-5 for e in errs), errs
 
 
-@pytest.mark.parametrize("case", [(129, 5, 257, 8), (40, 12, 70, 15), (60, 9, 72, 8)], ids=lambda c: "B%d_I%d_O%d_d%d" % c)
+@pytest.mark.parametrize("case", [(129, 5, 257, 8), (40, 12, 70, 15), (60, 9, 72, 8), (50, 12, 72, 15)], ids=lambda c: "B%d_I%d_O%d_d%d" % c)
 def test_single_slice_dC_written_by_the_slice_kernel(emu_driver, case):
     """One batch slice: the coefficient-gradient kernel turns its tile to [i][o][k] in LDS and writes dC
     itself (forced here at a small tile count; both output-tile widths, ragged tiles, the scalar and the
