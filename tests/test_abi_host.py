@@ -98,6 +98,31 @@ def test_workspace_matches_the_documented_partial_layout():
     assert binding.chebykan_workspace_bytes(16000, 512, 512, 5, binding.CHEBYKAN_PASS_FORWARD) == 0
 
 
+def test_workspace_query_over_random_shapes():
+    """The host-side plans behind the workspace query, over 400 seeded random shapes: a backward workspace is a
+    whole number of partial tensors with at most one slice per 32 rows, a forward workspace a whole number
+    (2..64) of output planes, and both stay under 2 GiB + one tensor."""
+    rng = np.random.default_rng(20251114)
+    for _ in range(400):
+        B = int(rng.choice([1, 7, 32, 33, 64, 100, 255, 256, 1000, 4095, 4096, 16000, 65536, 300000]))
+        I = int(rng.choice([1, 3, 8, 17, 64, 80, 257, 512, 1024, 3000]))
+        O = int(rng.choice([1, 2, 4, 5, 33, 64, 65, 128, 129, 192, 257, 512, 1000]))
+        d = int(rng.choice([0, 1, 2, 3, 4, 5, 6, 7, 8, 11, 15, 24, 32]))
+        per_slice = I * O * (d + 1) * 4
+        nb = binding.chebykan_workspace_bytes(B, I, O, d, binding.CHEBYKAN_PASS_BACKWARD)
+        nf = binding.chebykan_workspace_bytes(B, I, O, d, binding.CHEBYKAN_PASS_FORWARD)
+        assert nb >= 0 and nf >= 0
+        if nb:
+            # partial coefficient tensors, or (small batches) partial dx planes if those need more room
+            planes = B * I * 4
+            assert nb % per_slice == 0 or nb % planes == 0, (B, I, O, d, nb)
+            if nb % per_slice == 0 and nb // per_slice > 64:
+                assert nb // per_slice <= (B + 31) // 32, (B, I, O, d, nb)
+            assert nb <= (2 << 30) + per_slice + planes
+        if nf:
+            assert nf % (B * O * 4) == 0 and 2 <= nf // (B * O * 4) <= 64, (B, I, O, d, nf)
+
+
 def test_kernel_family_switch_round_trips():
     prev = binding.chebykan_set_kernel_family(1)
     assert binding.chebykan_set_kernel_family(prev) == 1
