@@ -284,4 +284,28 @@ sum_slices_kernel(const float* __restrict__ partial, float* __restrict__ out, in
     }
 }
 
+// The same sum for a few slices (up to 8): plain streaming, four consecutive elements per thread, slices
+// added in slice order.  VEC = 4 when n is a multiple of 4 and both pointers are 16-byte aligned: every
+// slice's run of four is then one 16-byte access.  grid.x = ceil(n / 1024).
+template <int VEC>
+__global__ void __launch_bounds__(256)
+sum_few_slices_kernel(const float* __restrict__ partial, float* __restrict__ out, int64_t n, int n_slices)
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (e >= n) return;
+    if constexpr (VEC == 4) {
+        f4 s = *reinterpret_cast<const f4*>(partial + e);
+        for (int q = 1; q < n_slices; ++q) s += *reinterpret_cast<const f4*>(partial + (int64_t)q * n + e);
+        *reinterpret_cast<f4*>(out + e) = s;
+    } else {
+        const int64_t end = e + 4 < n ? e + 4 : n;
+        for (int64_t i = e; i < end; ++i) {
+            float s = partial[i];
+            for (int q = 1; q < n_slices; ++q) s += partial[(int64_t)q * n + i];
+            out[i] = s;
+        }
+    }
+}
+
 }  // namespace chebykan

@@ -281,11 +281,13 @@ def test_full_size_row_block_elementwise():
     _check_full(x, C, dy, 0, "c4 first layer, %d rows" % B)
 
 
-def test_forward_split_when_the_wide_launch_would_underfill():
-    """16384 rows x 130 outputs: 128 wide tiles plus 128 tail tiles, each launch under one workgroup per
-    compute unit, so the plan splits the contraction over 512 inputs into ranges (the workspace query says
-    so) and sums the planes.  Every element of y against the oracle."""
-    B, I, O, d = 16384, 512, 130, 3
+@pytest.mark.parametrize("B", [16384, 16389], ids=["planes_16B_aligned", "planes_ragged"])
+def test_forward_split_when_the_wide_launch_would_underfill(B):
+    """About 16384 rows x 130 outputs: 128 wide tiles plus 128 tail tiles, each launch under one workgroup
+    per compute unit, so the plan splits the contraction over 512 inputs into ranges (the workspace query
+    says so) and sums the planes (streaming sum, with and without 16-byte accesses).  Every element of y
+    against the oracle."""
+    I, O, d = 512, 130, 3
     assert binding.chebykan_workspace_bytes(B, I, O, d, binding.CHEBYKAN_PASS_FORWARD) >= 2 * B * O * 4
     x = wl.make_x(B, I, 5151)
     C = wl.make_coeff(I, O, d, 5152)
