@@ -31,6 +31,8 @@
  *  - `stream` is a hipStream_t passed as an opaque pointer (NULL = the null
  *    stream).  All work is enqueued on it; the call returns without
  *    synchronising.  The library allocates nothing and frees nothing.
+ *  - Entry points may be called from several host threads at once (on
+ *    different streams or devices); the library keeps no per-call state.
  *  - Results are bitwise reproducible from run to run for fixed shapes: every
  *    reduction has a fixed order and no floating-point atomics are used.
  *  - batch == 0 is a successful no-op for forward and dx; dC is then zeroed.
@@ -202,37 +204,19 @@ chebykan_status chebykan_stack_backward(int n_layers, const int *widths, int deg
                                         float *const *grad, float *const *dC,
                                         void *workspace, size_t workspace_bytes, chebykan_stream_t stream);
 
+/*
+ * Prepares the CURRENT device for the library: checks that it is a gfx950 part and raises the
+ * dynamic-LDS limit of every kernel of the library on it.  Every entry point does this by itself
+ * on its first call on a device, so calling chebykan_init is optional - except that function
+ * attributes cannot be changed while a stream is being captured: a caller who captures the
+ * library's launches into a HIP graph calls chebykan_init (or any entry point) once on that device
+ * before the capture starts.  Idempotent and thread-safe; enqueues nothing.
+ * CHEBYKAN_ERR_DEVICE when no gfx950 device is current, CHEBYKAN_ERR_LAUNCH if HIP refuses.
+ */
+chebykan_status chebykan_init(void);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *chebykan_status_string(chebykan_status status);
-
-/*
- * Kernel-family override for tests and tuning: 0 = automatic choice (default),
- * 1 = force the generic any-degree kernels, 2 = force the MFMA kernels where
- * the shape supports them.  Process-wide, not thread-safe; returns the previous
- * value.  Not part of the paper's method.
- */
-int chebykan_set_kernel_family(int family);
-
-/*
- * Roofline calibration (measurement aids, no part of the paper's method): what
- * the GPU sustains on the two limits the layer kernels are priced against.
- *
- * chebykan_calibrate_mfma enqueues `workgroups` workgroups of 4 waves, each wave
- * issuing iterations*32 register-only v_mfma_f32_32x32x2_f32 (no memory traffic
- * in the loop).  `sink` is device memory of at least workgroups*256 floats that
- * the kernel overwrites; *flops (host pointer, may be NULL) receives the number
- * of floating-point operations of the launch.  The caller times the launch.
- *
- * chebykan_calibrate_copy enqueues dst[0..n) = src[0..n) as a plain streaming
- * copy (16 bytes per thread): n*4 bytes read and n*4 bytes written.  dst and src
- * are device pointers, 16-byte aligned, non-overlapping; n is a multiple of 4.
- *
- * Both return CHEBYKAN_ERR_NULL / CHEBYKAN_ERR_SHAPE for bad arguments and
- * CHEBYKAN_ERR_LAUNCH if HIP refuses the launch; nothing is allocated.
- */
-chebykan_status chebykan_calibrate_mfma(float *sink, int workgroups, int iterations, double *flops,
-                                        chebykan_stream_t stream);
-chebykan_status chebykan_calibrate_copy(float *dst, const float *src, int64_t n, chebykan_stream_t stream);
 
 /* Library/ABI version: major*1000 + minor. */
 int chebykan_version(void);

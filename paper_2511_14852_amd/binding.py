@@ -29,6 +29,8 @@ EXPORTS = (
     "chebykan_lut_build", "chebykan_forward_lut", "chebykan_backward_lut",
     "chebykan_forward_basis", "chebykan_backward_basis",
     "chebykan_stack_workspace_bytes", "chebykan_stack_forward", "chebykan_stack_backward",
+    "chebykan_init",
+    "chebykan_trace_begin", "chebykan_trace_end", "chebykan_trace_get", "chebykan_trace_free",
 )
 
 _lib: Optional[ctypes.CDLL] = None
@@ -86,6 +88,17 @@ def load() -> ctypes.CDLL:
         lib.chebykan_calibrate_mfma.restype = ci
         lib.chebykan_calibrate_copy.argtypes = [vp, vp, i64, vp]
         lib.chebykan_calibrate_copy.restype = ci
+        lib.chebykan_init.argtypes = []
+        lib.chebykan_init.restype = ci
+        lib.chebykan_trace_begin.argtypes = [ci]
+        lib.chebykan_trace_begin.restype = ci
+        lib.chebykan_trace_end.argtypes = [ctypes.POINTER(ci)]
+        lib.chebykan_trace_end.restype = ci
+        lib.chebykan_trace_get.argtypes = [ci, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_uint * 3),
+                                           ctypes.POINTER(ctypes.c_uint), ctypes.POINTER(ctypes.c_float)]
+        lib.chebykan_trace_get.restype = ci
+        lib.chebykan_trace_free.argtypes = []
+        lib.chebykan_trace_free.restype = None
         _lib = lib
     return _lib
 
@@ -117,6 +130,45 @@ def chebykan_set_kernel_family(family: int) -> int:
 
 def chebykan_version() -> int:
     return int(load().chebykan_version())
+
+
+def chebykan_init() -> None:
+    """Prepare the current device (optional; needed before capturing the library's launches into a graph)."""
+    st = int(load().chebykan_init())
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_init")
+
+
+def chebykan_trace_begin(max_kernels: int) -> None:
+    """Start timing every kernel the library launches from this thread (two event records per launch)."""
+    st = int(load().chebykan_trace_begin(int(max_kernels)))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_trace_begin")
+
+
+def chebykan_trace_end():
+    """Stop timing; returns (timed launches, launches dropped beyond the capacity)."""
+    dropped = ctypes.c_int(0)
+    n = int(load().chebykan_trace_end(ctypes.byref(dropped)))
+    return n, int(dropped.value)
+
+
+def chebykan_trace_records(count: int):
+    """(kernel name, grid (x, y, z), block threads, microseconds) per timed launch, in launch order.
+    The streams the launches went to must have been synchronised."""
+    lib = load()
+    out = []
+    name, grid, block, us = ctypes.c_char_p(), (ctypes.c_uint * 3)(), ctypes.c_uint(0), ctypes.c_float(0.0)
+    for i in range(count):
+        st = int(lib.chebykan_trace_get(i, ctypes.byref(name), ctypes.byref(grid), ctypes.byref(block), ctypes.byref(us)))
+        if st != CHEBYKAN_OK:
+            raise ChebykanError(st, "chebykan_trace_get")
+        out.append((name.value.decode(), (int(grid[0]), int(grid[1]), int(grid[2])), int(block.value), float(us.value)))
+    return out
+
+
+def chebykan_trace_free() -> None:
+    load().chebykan_trace_free()
 
 
 def chebykan_calibrate_mfma(sink, workgroups: int, iterations: int, stream=None) -> float:

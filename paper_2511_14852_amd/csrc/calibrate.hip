@@ -4,7 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "../../include/chebykan.h"
+#include "../../include/chebykan_tools.h"
+#include "launch.h"
 
 namespace {
 
@@ -57,8 +58,8 @@ chebykan_status chebykan_calibrate_mfma(float* sink, int workgroups, int iterati
 {
     if (!sink) return CHEBYKAN_ERR_NULL;
     if (workgroups <= 0 || workgroups > 65536 || iterations <= 0) return CHEBYKAN_ERR_SHAPE;
-    hipLaunchKernelGGL(mfma_loop_kernel, dim3((unsigned)workgroups), dim3(CAL_THREADS), 0,
-                       static_cast<hipStream_t>(stream), sink, iterations);
+    chebykan::launch<mfma_loop_kernel>(dim3((unsigned)workgroups), dim3(CAL_THREADS), 0, static_cast<hipStream_t>(stream),
+                                       sink, iterations);
     if (hipGetLastError() != hipSuccess) return CHEBYKAN_ERR_LAUNCH;
     if (flops)
         *flops = (double)workgroups * (CAL_THREADS / 64) * (double)iterations * CAL_UNROLL * CAL_ACCS * (32.0 * 32 * 2 * 2);
@@ -70,8 +71,8 @@ chebykan_status chebykan_calibrate_copy(float* dst, const float* src, int64_t n,
     if (!dst || !src) return CHEBYKAN_ERR_NULL;
     if (n <= 0 || n % 4 != 0 || (reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) % 16 != 0)
         return CHEBYKAN_ERR_SHAPE;
-    hipLaunchKernelGGL(copy_kernel, dim3(256 * 16), dim3(CAL_THREADS), 0, static_cast<hipStream_t>(stream),
-                       reinterpret_cast<floatx4*>(dst), reinterpret_cast<const floatx4*>(src), n / 4);
+    chebykan::launch<copy_kernel>(dim3(256 * 16), dim3(CAL_THREADS), 0, static_cast<hipStream_t>(stream),
+                                  reinterpret_cast<floatx4*>(dst), reinterpret_cast<const floatx4*>(src), n / 4);
     if (hipGetLastError() != hipSuccess) return CHEBYKAN_ERR_LAUNCH;
     return CHEBYKAN_OK;
 }

@@ -6,30 +6,10 @@
 #include "../../include/chebykan.h"
 #include "dispatch.h"
 #include "generic_kernels.h"
+#include "launch.h"
+#include "runtime.h"
 
 namespace chebykan {
-
-static int g_family = 0;  // 0 auto, 1 generic, 2 mfma
-
-// Is the current device a gfx950 part?  Cached per device ordinal.
-static chebykan_status check_device()
-{
-    static int arch_state[64];  // 0 unknown, 1 ok, -1 wrong arch
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0) {
-        (void)hipGetLastError();
-        return CHEBYKAN_ERR_DEVICE;
-    }
-    if (dev < 64 && arch_state[dev] != 0) return arch_state[dev] > 0 ? CHEBYKAN_OK : CHEBYKAN_ERR_DEVICE;
-    hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) {
-        (void)hipGetLastError();
-        return CHEBYKAN_ERR_DEVICE;
-    }
-    const bool ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
-    if (dev < 64) arch_state[dev] = ok ? 1 : -1;
-    return ok ? CHEBYKAN_OK : CHEBYKAN_ERR_DEVICE;
-}
 
 static bool shape_ok(int64_t batch, int in, int out, int degree)
 {
@@ -50,21 +30,21 @@ static void generic_forward(const float* x, const float* C, float* y, int64_t B,
                             hipStream_t s)
 {
     dim3 block(64, 4), grid((unsigned)((B + 3) / 4), (unsigned)((O + 63) / 64));
-    hipLaunchKernelGGL(generic_forward_kernel, grid, block, 0, s, x, C, y, B, I, O, d);
+    launch<generic_forward_kernel>(grid, block, 0, s, x, C, y, B, I, O, d);
 }
 
 static void generic_dx(const float* x, const float* C, const float* dy, float* dx, int64_t B, int I, int O,
                        int d, hipStream_t s)
 {
     dim3 block(64, 4), grid((unsigned)((B + 3) / 4), (unsigned)((I + 63) / 64));
-    hipLaunchKernelGGL(generic_dx_kernel, grid, block, 0, s, x, C, dy, dx, B, I, O, d);
+    launch<generic_dx_kernel>(grid, block, 0, s, x, C, dy, dx, B, I, O, d);
 }
 
 static void generic_dC(const float* x, const float* dy, float* dC, int64_t B, int I, int O, int d,
                        hipStream_t s)
 {
     const int64_t n = (int64_t)I * O * (d + 1);
-    hipLaunchKernelGGL(generic_dC_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, dy, dC, B, I,
+    launch<generic_dC_kernel>(dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, dy, dC, B, I,
                        O, d);
 }
 
@@ -72,21 +52,21 @@ static void generic_forward_table(const float* x, const float* C, const float* l
                                   int I, int O, int d, hipStream_t s)
 {
     dim3 block(64, 4), grid((unsigned)((B + 3) / 4), (unsigned)((O + 63) / 64));
-    hipLaunchKernelGGL(generic_forward_table_kernel, grid, block, 0, s, x, C, lut, n, y, B, I, O, d);
+    launch<generic_forward_table_kernel>(grid, block, 0, s, x, C, lut, n, y, B, I, O, d);
 }
 
 static void generic_dx_table(const float* x, const float* C, const float* dy, const float* lut, int n, float* dx,
                              int64_t B, int I, int O, int d, hipStream_t s)
 {
     dim3 block(64, 4), grid((unsigned)((B + 3) / 4), (unsigned)((I + 63) / 64));
-    hipLaunchKernelGGL(generic_dx_table_kernel, grid, block, 0, s, x, C, dy, lut, n, dx, B, I, O, d);
+    launch<generic_dx_table_kernel>(grid, block, 0, s, x, C, dy, lut, n, dx, B, I, O, d);
 }
 
 static void generic_dC_table(const float* x, const float* dy, const float* lut, int n, float* dC, int64_t B, int I,
                              int O, int d, hipStream_t s)
 {
     const int64_t cnt = (int64_t)I * O * (d + 1);
-    hipLaunchKernelGGL(generic_dC_table_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, x, dy, lut, n,
+    launch<generic_dC_table_kernel>(dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, x, dy, lut, n,
                        dC, B, I, O, d);
 }
 
@@ -98,12 +78,7 @@ extern "C" {
 
 int chebykan_version(void) { return 1000; }
 
-int chebykan_set_kernel_family(int family)
-{
-    const int prev = g_family;
-    if (family >= 0 && family <= 2) g_family = family;
-    return prev;
-}
+chebykan_status chebykan_init(void) { return prepare_device(); }
 
 const char* chebykan_status_string(chebykan_status status)
 {
@@ -134,12 +109,12 @@ chebykan_status chebykan_forward(const float* x, const float* C, float* y, int64
     if (!shape_ok(batch, in, out, degree)) return CHEBYKAN_ERR_SHAPE;
     const size_t need = forward_workspace_bytes(batch, in, out, degree);
     if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
-    const chebykan_status dev = check_device();
+    const chebykan_status dev = prepare_device();
     if (dev != CHEBYKAN_OK) return dev;
     if (batch == 0) return CHEBYKAN_OK;
     hipStream_t s = (hipStream_t)stream;
     (void)hipGetLastError();
-    if (g_family != 1 && fast_forward(x, C, y, batch, in, out, degree, workspace, s)) return launch_status();
+    if (kernel_family() != 1 && fast_forward(x, C, y, batch, in, out, degree, workspace, s)) return launch_status();
     generic_forward(x, C, y, batch, in, out, degree, s);
     return launch_status();
 }
@@ -153,11 +128,11 @@ chebykan_status chebykan_backward(const float* x, const float* C, const float* d
     if (!shape_ok(batch, in, out, degree)) return CHEBYKAN_ERR_SHAPE;
     const size_t need = backward_workspace_bytes(batch, in, out, degree);
     if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
-    const chebykan_status dev = check_device();
+    const chebykan_status dev = prepare_device();
     if (dev != CHEBYKAN_OK) return dev;
     hipStream_t s = (hipStream_t)stream;
     (void)hipGetLastError();
-    if (g_family != 1 && batch > 0 && fast_backward(x, C, dy, dx, dC, batch, in, out, degree, workspace, s))
+    if (kernel_family() != 1 && batch > 0 && fast_backward(x, C, dy, dx, dC, batch, in, out, degree, workspace, s))
         return launch_status();
     if (dx && batch > 0) generic_dx(x, C, dy, dx, batch, in, out, degree, s);
     // batch == 0 still defines dC (all zeros): the generic kernel's empty sum gives that.
@@ -196,12 +171,12 @@ chebykan_status chebykan_forward_lut(const float* x, const float* C, const float
         return CHEBYKAN_ERR_SHAPE;
     const size_t need = forward_workspace_bytes(batch, in, out, degree);
     if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
-    const chebykan_status dev = check_device();
+    const chebykan_status dev = prepare_device();
     if (dev != CHEBYKAN_OK) return dev;
     if (batch == 0) return CHEBYKAN_OK;
     hipStream_t s = (hipStream_t)stream;
     (void)hipGetLastError();
-    if (g_family != 1 && fast_forward_table(x, C, lut, lut_size, y, batch, in, out, degree, workspace, s))
+    if (kernel_family() != 1 && fast_forward_table(x, C, lut, lut_size, y, batch, in, out, degree, workspace, s))
         return launch_status();
     generic_forward_table(x, C, lut, lut_size, y, batch, in, out, degree, s);
     return launch_status();
@@ -218,11 +193,11 @@ chebykan_status chebykan_backward_lut(const float* x, const float* C, const floa
         return CHEBYKAN_ERR_SHAPE;
     const size_t need = backward_workspace_bytes(batch, in, out, degree);
     if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
-    const chebykan_status dev = check_device();
+    const chebykan_status dev = prepare_device();
     if (dev != CHEBYKAN_OK) return dev;
     hipStream_t s = (hipStream_t)stream;
     (void)hipGetLastError();
-    if (g_family != 1 && batch > 0 &&
+    if (kernel_family() != 1 && batch > 0 &&
         fast_backward_table(x, C, dy, lut, lut_size, dx, dC, batch, in, out, degree, workspace, s))
         return launch_status();
     if (dx && batch > 0) generic_dx_table(x, C, dy, lut, lut_size, dx, batch, in, out, degree, s);
@@ -267,12 +242,12 @@ chebykan_status chebykan_stack_forward(int n_layers, const int* widths, int degr
     if (!stack_ok(n_layers, widths, degree, batch)) return CHEBYKAN_ERR_SHAPE;
     const size_t need = chebykan_stack_workspace_bytes(batch, n_layers, widths, degree);
     if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
-    const chebykan_status dev = check_device();
+    const chebykan_status dev = prepare_device();
     if (dev != CHEBYKAN_OK) return dev;
     if (batch == 0) return CHEBYKAN_OK;
     // narrow stacks run all layers in one kernel, each workgroup keeping its rows' activations in LDS
     (void)hipGetLastError();
-    if (g_family != 1 && fast_chain_forward(n_layers, widths, degree, batch, C, act, (hipStream_t)stream))
+    if (kernel_family() != 1 && fast_chain_forward(n_layers, widths, degree, batch, C, act, (hipStream_t)stream))
         return launch_status();
     // every argument is validated: the per-layer calls below can only fail at launch
     for (int l = 0; l < n_layers; ++l) {
@@ -297,9 +272,9 @@ chebykan_status chebykan_stack_backward(int n_layers, const int* widths, int deg
     if (!stack_ok(n_layers, widths, degree, batch)) return CHEBYKAN_ERR_SHAPE;
     const size_t need = chebykan_stack_workspace_bytes(batch, n_layers, widths, degree);
     if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
-    const chebykan_status dev = check_device();
+    const chebykan_status dev = prepare_device();
     if (dev != CHEBYKAN_OK) return dev;
-    if (batch > 0 && g_family != 1) {
+    if (batch > 0 && kernel_family() != 1) {
         (void)hipGetLastError();
         if (fast_stack_backward(n_layers, widths, degree, batch, C, act, grad, dC, workspace, (hipStream_t)stream))
             return launch_status();
@@ -328,15 +303,15 @@ chebykan_status chebykan_forward_basis(int basis, const float* x, const float* C
     if (!shape_ok(batch, in, out, degree) || !basis_ok(basis, degree)) return CHEBYKAN_ERR_SHAPE;
     const size_t need = forward_workspace_bytes(batch, in, out, degree);
     if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
-    const chebykan_status dev = check_device();
+    const chebykan_status dev = prepare_device();
     if (dev != CHEBYKAN_OK) return dev;
     if (batch == 0) return CHEBYKAN_OK;
     hipStream_t s = (hipStream_t)stream;
     (void)hipGetLastError();
-    if (g_family != 1 && fast_forward_family(basis, x, C, y, batch, in, out, degree, workspace, s))
+    if (kernel_family() != 1 && fast_forward_family(basis, x, C, y, batch, in, out, degree, workspace, s))
         return launch_status();
     dim3 block(64, 4), grid((unsigned)((batch + 3) / 4), (unsigned)((out + 63) / 64));
-    hipLaunchKernelGGL(generic_forward_family_kernel, grid, block, 0, s, basis, x, C, y, batch, in, out, degree);
+    launch<generic_forward_family_kernel>(grid, block, 0, s, basis, x, C, y, batch, in, out, degree);
     return launch_status();
 }
 
@@ -351,20 +326,20 @@ chebykan_status chebykan_backward_basis(int basis, const float* x, const float* 
     if (!shape_ok(batch, in, out, degree) || !basis_ok(basis, degree)) return CHEBYKAN_ERR_SHAPE;
     const size_t need = backward_workspace_bytes(batch, in, out, degree);
     if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
-    const chebykan_status dev = check_device();
+    const chebykan_status dev = prepare_device();
     if (dev != CHEBYKAN_OK) return dev;
     hipStream_t s = (hipStream_t)stream;
     (void)hipGetLastError();
-    if (g_family != 1 && batch > 0 &&
+    if (kernel_family() != 1 && batch > 0 &&
         fast_backward_family(basis, x, C, dy, dx, dC, batch, in, out, degree, workspace, s))
         return launch_status();
     if (dx && batch > 0) {
         dim3 block(64, 4), grid((unsigned)((batch + 3) / 4), (unsigned)((in + 63) / 64));
-        hipLaunchKernelGGL(generic_dx_family_kernel, grid, block, 0, s, basis, x, C, dy, dx, batch, in, out, degree);
+        launch<generic_dx_family_kernel>(grid, block, 0, s, basis, x, C, dy, dx, batch, in, out, degree);
     }
     if (dC) {
         const int64_t cnt = (int64_t)in * out * (degree + 1);
-        hipLaunchKernelGGL(generic_dC_family_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, basis, x, dy,
+        launch<generic_dC_family_kernel>(dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, basis, x, dy,
                            dC, batch, in, out, degree);
     }
     return launch_status();

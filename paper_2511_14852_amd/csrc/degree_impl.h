@@ -6,33 +6,13 @@
 #include <hip/hip_runtime.h>
 
 #include "chain_kernels.h"
+#include "launch.h"
 #include "mfma_kernels.h"
 #include "narrow_in_kernels.h"
 #include "narrow_kernels.h"
 #include "plans.h"
 
 namespace chebykan {
-
-// True the first time it is asked on each device (function attributes are per device).
-struct DeviceOnce {
-    bool done[64] = {};
-    bool first()
-    {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return true;   // unknown device: just set it again
-        if (done[dev]) return false;
-        done[dev] = true;
-        return true;
-    }
-};
-
-// Dynamic LDS above 64 KiB has to be allowed per kernel, once per device.
-template <class KernelT>
-void allow_lds(KernelT kernel, int bytes)
-{
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              bytes);
-}
 
 // A workgroup may use the whole 160 KiB of a compute unit when a basis table rides along.
 constexpr int MAX_LDS_BYTES = 160 * 1024;
@@ -58,15 +38,15 @@ inline void launch_sum_slices(const float* partial, float* out, int64_t n, int s
     if (slices <= 8 && n >= ((int64_t)1 << 20)) {
         const dim3 grid((unsigned)((n + 1023) / 1024));
         if (n % 4 == 0 && aligned16(partial) && aligned16(out))
-            hipLaunchKernelGGL(sum_few_slices_kernel<4>, grid, dim3(256), 0, s, partial, out, n, slices);
+            launch<sum_few_slices_kernel<4>, 0, Tags<Int<4>>>(grid, dim3(256), 0, s, partial, out, n, slices);
         else
-            hipLaunchKernelGGL(sum_few_slices_kernel<1>, grid, dim3(256), 0, s, partial, out, n, slices);
+            launch<sum_few_slices_kernel<1>, 0, Tags<Int<1>>>(grid, dim3(256), 0, s, partial, out, n, slices);
     } else if (slices > 16)
-        hipLaunchKernelGGL(sum_slices_kernel<32>, dim3((unsigned)((n + 7) / 8)), dim3(256), 32 * 9 * sizeof(float), s,
-                           partial, out, n, slices);
+        launch<sum_slices_kernel<32>, 0, Tags<Int<32>>>(dim3((unsigned)((n + 7) / 8)), dim3(256), 32 * 9 * sizeof(float), s, partial, out, n,
+                                      slices);
     else
-        hipLaunchKernelGGL(sum_slices_kernel<4>, dim3((unsigned)((n + 63) / 64)), dim3(256), 4 * 65 * sizeof(float),
-                           s, partial, out, n, slices);
+        launch<sum_slices_kernel<4>, 0, Tags<Int<4>>>(dim3((unsigned)((n + 63) / 64)), dim3(256), 4 * 65 * sizeof(float), s, partial, out, n,
+                                     slices);
 }
 
 // ------------------------------------------------------------------ forward
@@ -75,25 +55,21 @@ void launch_fwd(const float* x, const float* C, float* out, int B, int I, int O,
                 const FwdPlan& p, const typename Basis::Args& ba, hipStream_t s)
 {
     using Cfg = FwdCfg<D, BN, forward_chunk_features(D), VEC, RB>;
-    static DeviceOnce once;
-    if (once.first()) allow_lds(fwd_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES);
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * tiles_o;
-    hipLaunchKernelGGL((fwd_mfma_kernel<Cfg, Basis>), dim3((unsigned)tiles, (unsigned)p.splits), dim3(MFMA_THREADS),
-                       Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, out, B, I, O, tiles_o, o_begin,
-                       p.chunks_per_split, ba);
+    launch<fwd_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES, Tags<Cfg, Basis>>(
+        dim3((unsigned)tiles, (unsigned)p.splits), dim3(MFMA_THREADS), Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s,
+        x, C, out, B, I, O, tiles_o, o_begin, p.chunks_per_split, ba);
 }
 
 template <int D, class Basis>
 void pick_fwd(const float* x, const float* C, float* y, float* partial, int B, int I, int O, const typename Basis::Args& ba, hipStream_t s)
 {
-    // 16-byte loads only need 4-byte aligned addresses in global memory; the LDS side of the copy stays aligned
-    const bool vec = !(tune_flags() & 16384);
-    (void)C;
+    // coefficient slabs are copied with 16-byte loads: global memory only needs 4-byte aligned addresses for
+    // them, and the LDS side of the copy stays 16-byte aligned
     const FwdPlan p = plan_forward(B, I, O, D);
     float* out = p.splits > 1 ? partial : y;
     if (O <= 64) {
-        if (vec) launch_fwd<D, 64, 4, Basis>(x, C, out, B, I, O, 1, 0, p, ba, s);
-        else launch_fwd<D, 64, 1, Basis>(x, C, out, B, I, O, 1, 0, p, ba, s);
+        launch_fwd<D, 64, 4, Basis>(x, C, out, B, I, O, 1, 0, p, ba, s);
     } else {
         const OutTiling t = out_tiling(O);
         // batches of at most 64 rows (the paper's operator shapes): waves side by side, no MFMAs on
@@ -101,16 +77,11 @@ void pick_fwd(const float* x, const float* C, float* y, float* partial, int B, i
         constexpr bool small_batch_built = D >= 7 && std::is_same<Basis, ExactBasis>::value;
         bool done = false;
         if constexpr (small_batch_built) {
-            if (vec && B <= 32) { launch_fwd<D, 128, 4, Basis, 1>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s); done = true; }
-            else if (vec && B <= 64) { launch_fwd<D, 128, 4, Basis, 2>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s); done = true; }
+            if (B <= 32) { launch_fwd<D, 128, 4, Basis, 1>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s); done = true; }
+            else if (B <= 64) { launch_fwd<D, 128, 4, Basis, 2>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s); done = true; }
         }
-        if (done) {}
-        else if (vec) launch_fwd<D, 128, 4, Basis>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s);
-        else launch_fwd<D, 128, 1, Basis>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s);
-        if (t.tail_begin >= 0) {
-            if (vec) launch_fwd<D, 64, 4, Basis>(x, C, out, B, I, O, 1, t.tail_begin, p, ba, s);
-            else launch_fwd<D, 64, 1, Basis>(x, C, out, B, I, O, 1, t.tail_begin, p, ba, s);
-        }
+        if (!done) launch_fwd<D, 128, 4, Basis>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s);
+        if (t.tail_begin >= 0) launch_fwd<D, 64, 4, Basis>(x, C, out, B, I, O, 1, t.tail_begin, p, ba, s);
     }
     if (p.splits > 1) launch_sum_slices(partial, y, (int64_t)B * O, p.splits, s);
 }
@@ -125,14 +96,11 @@ void launch_dC_combine(const float* partial, float* dC, int I, int O, int slices
         return;
     }
     const dim3 grid((unsigned)((O + 31) / 32), (unsigned)I);
-    static DeviceOnce once;
-    if (once.first()) allow_lds(dC_combine_kernel<D, 32>, 1024 * ((D + 1) | 1) * (int)sizeof(float));
+    constexpr int lds32 = 1024 * ((D + 1) | 1) * (int)sizeof(float), lds8 = 256 * ((D + 1) | 1) * (int)sizeof(float);
     if (slices > 32)
-        hipLaunchKernelGGL((dC_combine_kernel<D, 32>), grid, dim3(1024), 1024 * ((D + 1) | 1) * sizeof(float), s,
-                           partial, dC, I, O, slices);
+        launch<dC_combine_kernel<D, 32>, lds32, Tags<Int<D>, Int<32>>>(grid, dim3(1024), lds32, s, partial, dC, I, O, slices);
     else
-        hipLaunchKernelGGL((dC_combine_kernel<D, 8>), grid, dim3(256), 256 * ((D + 1) | 1) * sizeof(float), s,
-                           partial, dC, I, O, slices);
+        launch<dC_combine_kernel<D, 8>, lds8, Tags<Int<D>, Int<8>>>(grid, dim3(256), lds8, s, partial, dC, I, O, slices);
 }
 
 template <int D, int BN, int VEC, int BIC, class Basis>
@@ -142,32 +110,25 @@ void launch_dC(const float* x, const float* dy, float* partial, float* direct, i
     using Cfg = DcCfg<D, BN, VEC, BIC>;
     constexpr int kAllow = Basis::kTable ? MAX_LDS_BYTES
                                          : (Cfg::DIRECT_LDS_BYTES > Cfg::LDS_BYTES ? Cfg::DIRECT_LDS_BYTES : Cfg::LDS_BYTES);
-    static DeviceOnce once;
-    if (once.first()) allow_lds(dC_mfma_kernel<Cfg, Basis>, kAllow);
     const int tiles_i = (I + Cfg::BIC - 1) / Cfg::BIC;
     size_t lds_bytes = Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1);
     if (direct && lds_bytes < (size_t)Cfg::DIRECT_LDS_BYTES) lds_bytes = Cfg::DIRECT_LDS_BYTES;   // the epilogue's layout turn
-    hipLaunchKernelGGL((dC_mfma_kernel<Cfg, Basis>), dim3((unsigned)((int64_t)tiles_i * tiles_o * p.slices)),
-                       dim3(MFMA_THREADS), lds_bytes, s, x, dy, partial, B, I, O, tiles_o, o_begin, tiles_i, p.slices,
-                       p.rows_per_slice, ba, direct);
+    launch<dC_mfma_kernel<Cfg, Basis>, kAllow, Tags<Cfg, Basis>>(dim3((unsigned)((int64_t)tiles_i * tiles_o * p.slices)), dim3(MFMA_THREADS),
+                                               lds_bytes, s, x, dy, partial, B, I, O, tiles_o, o_begin, tiles_i, p.slices,
+                                               p.rows_per_slice, ba, direct);
 }
 
 template <int D, int BIC, class Basis>
 void pick_dC_tile(const float* x, const float* dy, float* partial, float* direct, int B, int I, int O, const DcPlan& p,
                   const typename Basis::Args& ba, hipStream_t s)
 {
-    const bool vec = !(tune_flags() & 16384);   // see pick_fwd
+    // dy rows are copied with 16-byte loads at any 4-byte aligned address (see pick_fwd)
     if (p.bn == 64) {
-        if (vec) launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, direct, B, I, O, 1, 0, p, ba, s);
-        else launch_dC<D, 64, 1, BIC, Basis>(x, dy, partial, direct, B, I, O, 1, 0, p, ba, s);
+        launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, direct, B, I, O, 1, 0, p, ba, s);
     } else {
         const OutTiling t = out_tiling(O);
-        if (vec) launch_dC<D, 128, 4, BIC, Basis>(x, dy, partial, direct, B, I, O, t.wide_tiles, 0, p, ba, s);
-        else launch_dC<D, 128, 1, BIC, Basis>(x, dy, partial, direct, B, I, O, t.wide_tiles, 0, p, ba, s);
-        if (t.tail_begin >= 0) {
-            if (vec) launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, direct, B, I, O, 1, t.tail_begin, p, ba, s);
-            else launch_dC<D, 64, 1, BIC, Basis>(x, dy, partial, direct, B, I, O, 1, t.tail_begin, p, ba, s);
-        }
+        launch_dC<D, 128, 4, BIC, Basis>(x, dy, partial, direct, B, I, O, t.wide_tiles, 0, p, ba, s);
+        if (t.tail_begin >= 0) launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, direct, B, I, O, 1, t.tail_begin, p, ba, s);
     }
 }
 
@@ -179,13 +140,12 @@ void pick_dC(const float* x, const float* dy, float* dC, float* partial, int B, 
     // layout, and the slice sum is not launched.  Only with enough tiles: each workgroup turns its
     // own tile, and a handful of workgroups do that slower than the many blocks of the sum kernel
     // (measured with the element-wise copy: 3 and 6 tiles lose 1-4 us, 128 and 824 tiles gain 4 and 9 us).
-    // Bit 15 (value 32768) of the tuning mask turns this off.
     const int bic = dc_tile_features_for(I, D);
     const int64_t tiles = (int64_t)((I + bic - 1) / bic) * ((O + p.bn - 1) / p.bn);
-    // Bit 16 (value 65536): also with few tiles (tests of that epilogue on small inputs).
     // With 16-byte aligned runs the tile leaves as whole float4 stores, which wins at any tile count.
+    // (The test hook TEST_DIRECT_DC takes this path at any tile count: tests of that epilogue on small inputs.)
     const bool vector_out = O % 4 == 0 && aligned16(dC);
-    float* direct = (p.slices == 1 && (tiles >= 64 || vector_out || (tune_flags() & 65536)) && !(tune_flags() & 32768)) ? dC : nullptr;
+    float* direct = (p.slices == 1 && (tiles >= 64 || vector_out || (test_hooks() & TEST_DIRECT_DC))) ? dC : nullptr;
     if constexpr (D == 6) {
         if (dc_tile_features_for(I, D) == 16) pick_dC_tile<D, 16, Basis>(x, dy, partial, direct, B, I, O, p, ba, s);
         else pick_dC_tile<D, dc_tile_features(D), Basis>(x, dy, partial, direct, B, I, O, p, ba, s);
@@ -201,12 +161,10 @@ void launch_dx(const float* x, const float* C, const float* dy, float* dx, float
                const DxPlan& p, const typename Basis::Args& ba, hipStream_t s)
 {
     using Cfg = DxCfg<D, NB, VEC, RB>;
-    static DeviceOnce once;
-    if (once.first()) allow_lds(dx_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES);
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * p.feature_tiles;
-    hipLaunchKernelGGL((dx_mfma_kernel<Cfg, Basis>), dim3((unsigned)tiles, (unsigned)p.split.splits), dim3(MFMA_THREADS),
-                       Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy,
-                       p.split.splits > 1 ? partial : dx, B, I, O, p.feature_tiles, p.split.chunks_per_split, ba);
+    launch<dx_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES, Tags<Cfg, Basis>>(
+        dim3((unsigned)tiles, (unsigned)p.split.splits), dim3(MFMA_THREADS), Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1),
+        s, x, C, dy, p.split.splits > 1 ? partial : dx, B, I, O, p.feature_tiles, p.split.chunks_per_split, ba);
 }
 
 template <int D, int VEC, class Basis>
@@ -215,12 +173,10 @@ void launch_dx2(const float* x, const float* C, const float* dy, float* dx, floa
 {
     using Cfg = Dx2Cfg<D, VEC>;
     static_assert(Cfg::BO == (D <= 4 ? 32 : 16), "plan_dx assumes this chunk width");
-    static DeviceOnce once;
-    if (once.first()) allow_lds(dx2_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES);
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * p.feature_tiles;
-    hipLaunchKernelGGL((dx2_mfma_kernel<Cfg, Basis>), dim3((unsigned)tiles, (unsigned)p.split.splits), dim3(MFMA_THREADS),
-                       Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy,
-                       p.split.splits > 1 ? partial : dx, B, I, O, p.feature_tiles, p.split.chunks_per_split, ba);
+    launch<dx2_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES, Tags<Cfg, Basis>>(
+        dim3((unsigned)tiles, (unsigned)p.split.splits), dim3(MFMA_THREADS), Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1),
+        s, x, C, dy, p.split.splits > 1 ? partial : dx, B, I, O, p.feature_tiles, p.split.chunks_per_split, ba);
 }
 
 template <int D, class Basis>
@@ -274,11 +230,10 @@ template <int D, int O, class Basis>
 void launch_narrow_fwd(const float* x, const float* C, float* y, int B, int I, const typename Basis::Args& ba, hipStream_t s)
 {
     const NarrowPlan p = plan_narrow(B, I, NARROW_FWD_WGS);
-    static DeviceOnce once;
-    if (once.first()) allow_lds(narrow_fwd_kernel<D, O, Basis>, MAX_LDS_BYTES);
-    hipLaunchKernelGGL((narrow_fwd_kernel<D, O, Basis>), dim3((unsigned)p.slices), dim3(NARROW_THREADS),
-                       narrow_fwd_lds_floats(I, O, D + 1) * sizeof(float) + basis_lds_bytes<Basis>(ba, D + 1), s, x, C,
-                       y, B, I, p.G, p.rows_per_wg, ba);
+    launch<narrow_fwd_kernel<D, O, Basis>, MAX_LDS_BYTES, Tags<Int<D>, Int<O>, Basis>>(
+        dim3((unsigned)p.slices), dim3(NARROW_THREADS),
+        narrow_fwd_lds_floats(I, O, D + 1) * sizeof(float) + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, y, B, I, p.G,
+        p.rows_per_wg, ba);
 }
 
 template <int D, int O, class Basis>
@@ -287,12 +242,10 @@ void launch_narrow_bwd(const float* x, const float* C, const float* dy, float* d
 {
     const NarrowPlan p = plan_narrow(B, I, NARROW_BWD_WGS);
     const int blocks_i = (I + p.G - 1) / p.G;
-    static DeviceOnce once;
-    if (once.first()) allow_lds(narrow_bwd_kernel<D, O, Basis>, MAX_LDS_BYTES);
-    hipLaunchKernelGGL((narrow_bwd_kernel<D, O, Basis>), dim3((unsigned)p.slices, (unsigned)blocks_i),
-                       dim3(NARROW_THREADS),
-                       narrow_bwd_lds_floats(O, D + 1) * sizeof(float) + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy,
-                       dx, dC ? partial : nullptr, B, I, p.G, p.rows_per_wg, ba);
+    launch<narrow_bwd_kernel<D, O, Basis>, MAX_LDS_BYTES, Tags<Int<D>, Int<O>, Basis>>(
+        dim3((unsigned)p.slices, (unsigned)blocks_i), dim3(NARROW_THREADS),
+        narrow_bwd_lds_floats(O, D + 1) * sizeof(float) + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy, dx,
+        dC ? partial : nullptr, B, I, p.G, p.rows_per_wg, ba);
     if (dC) {
         if (g_deferred_combine) *g_deferred_combine = CombineJob{partial, dC, I, O, p.slices, 1, (int64_t)I * O * (D + 1), 0};
         else launch_sum_slices(partial, dC, (int64_t)I * O * (D + 1), p.slices, s);
@@ -333,9 +286,7 @@ void degree_stack_combine(CombineArgs& a, hipStream_t s)
     }
     if (blocks == 0) return;
     constexpr int lds_bytes = 1024 * ((D + 1) | 1) * (int)sizeof(float);
-    static DeviceOnce once;
-    if (once.first()) allow_lds(stack_combine_kernel<D>, lds_bytes);
-    hipLaunchKernelGGL(stack_combine_kernel<D>, dim3((unsigned)blocks), dim3(1024), lds_bytes, s, a);
+    launch<stack_combine_kernel<D>, lds_bytes, Tags<Int<D>>>(dim3((unsigned)blocks), dim3(1024), lds_bytes, s, a);
 }
 
 // ------------------------------------------------------------ fused narrow stack
@@ -343,10 +294,8 @@ void degree_stack_combine(CombineArgs& a, hipStream_t s)
 template <int D>
 void degree_chain_forward(const ChainArgs& a, int B, hipStream_t s)
 {
-    static DeviceOnce once;
-    if (once.first()) allow_lds(fwd_chain_kernel<D>, chain_lds_bytes<D>());
-    hipLaunchKernelGGL(fwd_chain_kernel<D>, dim3((unsigned)((B + 127) / 128)), dim3(MFMA_THREADS),
-                       (size_t)chain_lds_bytes<D>(), s, a, B);
+    launch<fwd_chain_kernel<D>, chain_lds_bytes<D>(), Tags<Int<D>>>(dim3((unsigned)((B + 127) / 128)), dim3(MFMA_THREADS),
+                                                      (size_t)chain_lds_bytes<D>(), s, a, B);
 }
 
 // ------------------------------------------------------- per-degree entry points
@@ -370,11 +319,9 @@ void degree_backward(const float* x, const float* C, const float* dy, float* dx,
     }
     if (dx && dC && use_narrow_in(B, I, O, D)) {   // few inputs, both gradients wanted: one kernel for both
         const NarrowInPlan p = plan_narrow_in(B);
-        static DeviceOnce once;
-        if (once.first()) allow_lds(bwd_narrow_in_kernel<D, Basis>, Basis::kTable ? MAX_LDS_BYTES : NIN_LDS_BYTES);
-        hipLaunchKernelGGL((bwd_narrow_in_kernel<D, Basis>), dim3((unsigned)p.slices), dim3(MFMA_THREADS),
-                           NIN_LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy, dx, dC ? partial : nullptr, B,
-                           I, O, p.rows_per_slice, ba);
+        launch<bwd_narrow_in_kernel<D, Basis>, Basis::kTable ? MAX_LDS_BYTES : NIN_LDS_BYTES, Tags<Int<D>, Basis>>(
+            dim3((unsigned)p.slices), dim3(MFMA_THREADS), NIN_LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy, dx,
+            dC ? partial : nullptr, B, I, O, p.rows_per_slice, ba);
         if (dC) launch_dC_combine<D>(partial, dC, I, O, p.slices, s);
         return;
     }

@@ -150,8 +150,8 @@ bool fast_backward_table(const float* x, const float* C, const float* dy, const 
 // 1..4 outputs is finished on the vector ALUs.
 bool chain_eligible(int n_layers, const int* widths, int d, int64_t B, const float* const* C)
 {
-    if ((tune_flags() & 256) || !chain_degree(d) || n_layers < 2 || n_layers > CHAIN_MAX_LAYERS) return false;
-    if ((B < 128 * 256 && !(tune_flags() & 512)) || B > 0x7fffffff) return false;   // bit 9: any batch (tests)
+    if (!chain_degree(d) || n_layers < 2 || n_layers > CHAIN_MAX_LAYERS) return false;
+    if ((B < 128 * 256 && !(test_hooks() & TEST_CHAIN_ANY_BATCH)) || B > 0x7fffffff) return false;
     if ((int64_t)B * (widths[0] > CHAIN_WIDTH ? widths[0] : CHAIN_WIDTH) >= ((int64_t)1 << 30)) return false;
     for (int l = 0; l < n_layers; ++l) {
         const int O = widths[l + 1];
@@ -193,7 +193,7 @@ size_t stack_backward_workspace_bytes(int n_layers, const int* widths, int d, in
 bool fast_stack_backward(int n_layers, const int* widths, int d, int64_t B, const float* const* C,
                          const float* const* act, float* const* grad, float* const* dC, void* ws, hipStream_t s)
 {
-    if ((tune_flags() & 2048) || n_layers > COMBINE_MAX_JOBS || !degree_specialised(d) || B <= 0) return false;
+    if (n_layers > COMBINE_MAX_JOBS || !degree_specialised(d) || B <= 0) return false;
     for (int l = 0; l < n_layers; ++l)
         if (!shape_fits(B, widths[l], widths[l + 1], d)) return false;
     CombineArgs jobs;

@@ -37,23 +37,24 @@ constexpr bool fourier_degree_specialised(int d) { return d == 4 || d == 6 || d 
 #define CHEBYKAN_FOR_EACH_CHAIN_DEGREE(X) X(3) X(4) X(5) X(6)
 constexpr bool chain_degree(int d) { return d >= 3 && d <= 6; }
 
-// Tuning switches for kernel experiments: integer bit mask in the environment variable
-// CHEBYKAN_TUNE, read once.  Bit 2 (value 4): always use the packed-column dx kernel.
-// Bit 3 (value 8): never split the forward contraction.  Bit 8 (value 256): never fuse a stack's forward.
-// Bit 11 (value 2048): a stack's backward sums each layer's slices in its own launch.
-// Bit 14 (value 16384): scalar instead of 16-byte loads in the forward and dC producers.
-// Bit 9 (value 512): fuse a stack's forward at any batch size (tests of that kernel on small inputs).
-// Bit 15 (value 32768): a single-slice coefficient gradient goes through the partial tensor and the slice sum
-//   instead of writing dC from the slice kernel.  Bit 16 (value 65536): that direct write also with few tiles.
-// Bit 17 (value 131072): small batches keep at least 256 rows per coefficient-gradient slice.
-inline int tune_flags()
+// Test hooks.  Three plan decisions depend on sizes that only large inputs reach; the host-side
+// emulation tests need them on small inputs.  A build with -DCHEBYKAN_TEST_HOOKS reads a bit mask
+// from the environment variable CHEBYKAN_TEST_HOOKS once; the product build has no such switch.
+constexpr int TEST_CHAIN_ANY_BATCH = 1;   // fuse a narrow stack's forward at any batch size
+constexpr int TEST_DIRECT_DC = 2;         // a single-slice dC is written by the slice kernel at any tile count
+constexpr int TEST_DC_MIN_256_ROWS = 4;   // small batches keep at least 256 rows per coefficient-gradient slice
+#ifdef CHEBYKAN_TEST_HOOKS
+inline int test_hooks()
 {
     static const int flags = [] {
-        const char* e = getenv("CHEBYKAN_TUNE");
+        const char* e = getenv("CHEBYKAN_TEST_HOOKS");
         return e ? atoi(e) : 0;
     }();
     return flags;
 }
+#else
+constexpr int test_hooks() { return 0; }
+#endif
 
 // Input features per forward chunk: about 28-50 contraction terms per chunk.
 constexpr int forward_chunk_features(int d)
@@ -65,10 +66,10 @@ inline bool use_narrow_shape(int I, int O, int d) { return O <= 4 && (int64_t)I 
 
 // ------------------------------------------------- layers with very few inputs
 // Both gradients of a layer whose (i,k) rows and outputs fit one 64 x 64 tile come from one
-// kernel (narrow_in_kernels.h).  Bit 10 (value 1024) of the tuning mask turns this off.
+// kernel (narrow_in_kernels.h).
 inline bool use_narrow_in(int64_t B, int I, int O, int d)
 {
-    return !(tune_flags() & 1024) && B >= 1 && I * (d + 1) <= 64 && I <= 16 && O <= 64 && O > 4;
+    return B >= 1 && I * (d + 1) <= 64 && I <= 16 && O <= 64 && O > 4;
 }
 
 struct NarrowInPlan {
@@ -145,7 +146,7 @@ inline DcPlan plan_dC(int64_t B, int I, int O, int d)
     const bool mixed = p.bn == 128 && ot.tail_begin >= 0;
     // at least 256 rows per slice; a small batch with few tiles may go down to one 32-row chunk per
     // workgroup, which shortens the serial chain of chunks when only a handful of workgroups exist
-    const int64_t min_rows = (tiles < 64 && B < 4096 && !(tune_flags() & 131072)) ? 32 : 256;
+    const int64_t min_rows = (tiles < 64 && B < 4096 && !(test_hooks() & TEST_DC_MIN_256_ROWS)) ? 32 : 256;
     int64_t max_s = (B + min_rows - 1) / min_rows;
     const int64_t bytes_per_slice = (int64_t)I * K * O * 4;
     const int64_t max_by_bytes = ((int64_t)512 << 20) / bytes_per_slice;
@@ -275,7 +276,7 @@ inline FwdPlan plan_forward(int64_t B, int I, int O, int d)
     const int n_chunks = (I + bi - 1) / bi;
     const int64_t tiles = ((B + 127) / 128) * ((O + (O <= 64 ? 63 : 127)) / (O <= 64 ? 64 : 128));
     FwdPlan p{1, n_chunks};
-    if ((tune_flags() & 8) || n_chunks < 4) return p;
+    if (n_chunks < 4) return p;
     if (tiles >= 256) {
         // Enough tiles, but with a tail tile they come as two launches that may each leave compute
         // units idle (257 outputs at 16000 rows: 250 + 125 workgroups).  Estimated time per range
@@ -314,7 +315,7 @@ inline FwdPlan plan_dx_split(int64_t B, int feature_tiles, int O, int chunk_outp
     const int n_chunks = (O + chunk_outputs - 1) / chunk_outputs;
     const int64_t tiles = ((B + 127) / 128) * feature_tiles;
     FwdPlan p{1, n_chunks};
-    if ((tune_flags() & 8) || tiles >= 256 || n_chunks < 4) return p;
+    if (tiles >= 256 || n_chunks < 4) return p;
     int64_t want = (512 + tiles - 1) / tiles;
     if (want > n_chunks / 2) want = n_chunks / 2;
     if (want > 32) want = 32;
@@ -335,7 +336,7 @@ struct DxPlan {
 inline DxPlan plan_dx(int64_t B, int I, int O, int d)
 {
     DxPlan p;
-    p.per_lane = d >= 1 && dx_feature_per_lane(I, d) && !(tune_flags() & 4);
+    p.per_lane = d >= 1 && dx_feature_per_lane(I, d);
     p.nb = d >= 1 ? dx_column_blocks(I, d) : 1;
     if (p.per_lane) {
         p.feature_tiles = (I + 31) / 32;

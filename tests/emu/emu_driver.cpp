@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "../../include/chebykan.h"
+#include "../../include/chebykan_tools.h"
 
 static std::vector<float> read_bin(const std::string& path, size_t n)
 {
