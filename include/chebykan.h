@@ -99,6 +99,27 @@ chebykan_status chebykan_backward(const float *x, const float *C, const float *d
                                   chebykan_stream_t stream);
 
 /*
+ * chebykan_backward for callers that can neither allocate nor hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same
+ * arguments (without the workspace) and same results, bit for bit, as chebykan_backward; the
+ * partial coefficient gradients and split-contraction planes go to a scratch array of
+ * CHEBYKAN_NOALLOC_SCRATCH_BYTES that is part of the library's device image (every GPU the
+ * library runs on holds it until the process ends).  A shape whose
+ * chebykan_workspace_bytes(..., CHEBYKAN_PASS_BACKWARD) exceeds that size is refused with
+ * CHEBYKAN_ERR_WORKSPACE and nothing is enqueued.  The call allocates and frees nothing; its
+ * only set-up is a symbol-address lookup on the first call per device, which chebykan_init does
+ * ahead of time (call that before a stream capture).  All calls on one GPU share the one array:
+ * two such calls that may run at the same time on that GPU (different streams, or graphs
+ * replayed concurrently) race and give undefined results - keep them on one stream or order them.
+ * The array keeps what the last call left in it; no call depends on its contents.
+ */
+#define CHEBYKAN_NOALLOC_SCRATCH_BYTES (32u << 20)
+chebykan_status chebykan_backward_noalloc(const float *x, const float *C, const float *dy,
+                                          float *dx, float *dC,
+                                          int64_t batch, int in, int out, int degree,
+                                          chebykan_stream_t stream);
+
+/*
  * Table-interpolated variant (paper Sec. 4.2, "Polynomial Operators Acceleration
  * via LUT").  The basis is not evaluated by the recurrence but read from a table
  *

@@ -29,7 +29,7 @@ EXPORTS = (
     "chebykan_lut_build", "chebykan_forward_lut", "chebykan_backward_lut",
     "chebykan_forward_basis", "chebykan_backward_basis",
     "chebykan_stack_workspace_bytes", "chebykan_stack_forward", "chebykan_stack_backward",
-    "chebykan_init",
+    "chebykan_init", "chebykan_backward_noalloc",
     "chebykan_trace_begin", "chebykan_trace_end", "chebykan_trace_get", "chebykan_trace_free",
 )
 
@@ -88,6 +88,8 @@ def load() -> ctypes.CDLL:
         lib.chebykan_calibrate_mfma.restype = ci
         lib.chebykan_calibrate_copy.argtypes = [vp, vp, i64, vp]
         lib.chebykan_calibrate_copy.restype = ci
+        lib.chebykan_backward_noalloc.argtypes = [vp, vp, vp, vp, vp, i64, ci, ci, ci, vp]
+        lib.chebykan_backward_noalloc.restype = ci
         lib.chebykan_init.argtypes = []
         lib.chebykan_init.restype = ci
         lib.chebykan_trace_begin.argtypes = [ci]
@@ -257,6 +259,33 @@ def chebykan_backward(x, C, dy, dx, dC, workspace=None, stream=None) -> None:
                       B, I, O, K - 1, ws_ptr, ws_bytes, _stream_ptr(stream))
     if st != CHEBYKAN_OK:
         raise ChebykanError(st, "chebykan_backward")
+
+
+CHEBYKAN_NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def raw_backward_noalloc(x_ptr, C_ptr, dy_ptr, dx_ptr, dC_ptr, batch, n_in, n_out, degree, stream=None) -> int:
+    return int(load().chebykan_backward_noalloc(x_ptr, C_ptr, dy_ptr, dx_ptr, dC_ptr, batch, n_in, n_out, degree, stream))
+
+
+def chebykan_backward_noalloc(x, C, dy, dx, dC, stream=None) -> None:
+    """chebykan_backward on the library's own static scratch: no workspace argument, no allocation."""
+    _check(x, "x")
+    B, I = x.shape
+    _check(C, "C")
+    if C.dim() != 3 or C.shape[0] != I:
+        raise ValueError("C must be [in, out, degree+1]")
+    O, K = int(C.shape[1]), int(C.shape[2])
+    _check(dy, "dy", (B, O))
+    if dx is not None:
+        _check(dx, "dx", (B, I))
+    if dC is not None:
+        _check(dC, "dC", (I, O, K))
+    st = raw_backward_noalloc(x.data_ptr(), C.data_ptr(), dy.data_ptr(),
+                              None if dx is None else dx.data_ptr(), None if dC is None else dC.data_ptr(),
+                              B, I, O, K - 1, _stream_ptr(stream))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_backward_noalloc")
 
 
 def chebykan_lut_build(degree: int, lut_size: int):

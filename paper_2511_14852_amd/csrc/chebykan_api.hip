@@ -3,6 +3,9 @@
 #include <hip/hip_runtime.h>
 #include <string.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "../../include/chebykan.h"
 #include "dispatch.h"
 #include "generic_kernels.h"
@@ -10,6 +13,38 @@
 #include "runtime.h"
 
 namespace chebykan {
+
+// Scratch of chebykan_backward_noalloc: one array per GPU that loads the library, held until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress - never a device
+// address: everything below uses the per-device address that call returns.
+static __device__ __align__(256) unsigned char scratch[CHEBYKAN_NOALLOC_SCRATCH_BYTES];
+
+// Device address of `scratch` on the current device, looked up once per device.
+static chebykan_status scratch_address(void** out)
+{
+    constexpr int MAX_DEVICES = 64;
+    static std::atomic<void*> address[MAX_DEVICES];
+    static std::mutex lookup_mutex;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        (void)hipGetLastError();
+        return CHEBYKAN_ERR_DEVICE;
+    }
+    void* p = address[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(lookup_mutex);
+        p = address[dev].load();
+        if (!p) {
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+                (void)hipGetLastError();
+                return CHEBYKAN_ERR_LAUNCH;
+            }
+            address[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return CHEBYKAN_OK;
+}
 
 static bool shape_ok(int64_t batch, int in, int out, int degree)
 {
@@ -78,7 +113,13 @@ extern "C" {
 
 int chebykan_version(void) { return 1000; }
 
-chebykan_status chebykan_init(void) { return prepare_device(); }
+chebykan_status chebykan_init(void)
+{
+    const chebykan_status st = prepare_device();
+    if (st != CHEBYKAN_OK) return st;
+    void* p = nullptr;
+    return scratch_address(&p);   // so that chebykan_backward_noalloc has nothing left to look up
+}
 
 const char* chebykan_status_string(chebykan_status status)
 {
@@ -138,6 +179,24 @@ chebykan_status chebykan_backward(const float* x, const float* C, const float* d
     // batch == 0 still defines dC (all zeros): the generic kernel's empty sum gives that.
     if (dC) generic_dC(x, dy, dC, batch, in, out, degree, s);
     return launch_status();
+}
+
+chebykan_status chebykan_backward_noalloc(const float* x, const float* C, const float* dy, float* dx, float* dC,
+                                          int64_t batch, int in, int out, int degree, chebykan_stream_t stream)
+{
+    if (!C || (batch != 0 && (!x || !dy))) return CHEBYKAN_ERR_NULL;
+    if (!dx && !dC && batch != 0) return CHEBYKAN_ERR_NULL;
+    if (!shape_ok(batch, in, out, degree)) return CHEBYKAN_ERR_SHAPE;
+    if (backward_workspace_bytes(batch, in, out, degree) > (size_t)CHEBYKAN_NOALLOC_SCRATCH_BYTES)
+        return CHEBYKAN_ERR_WORKSPACE;
+    const chebykan_status dev = prepare_device();
+    if (dev != CHEBYKAN_OK) return dev;
+    void* ws = nullptr;
+    const chebykan_status st = scratch_address(&ws);
+    if (st != CHEBYKAN_OK) return st;
+    // The kernels write every scratch element they later read within this call, so what an earlier
+    // call left there does not matter and nothing is cleared.
+    return chebykan_backward(x, C, dy, dx, dC, batch, in, out, degree, ws, CHEBYKAN_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 chebykan_status chebykan_lut_build(float* lut, int degree, int lut_size)
