@@ -45,21 +45,26 @@ chebykan_status chebykan_calibrate_copy(float *dst, const float *src, int64_t n,
  * library launches FROM THE CALLING THREAD is bracketed by two hipEventRecord calls on the stream
  * it is launched on; afterwards chebykan_trace_get returns, for the index-th launch in launch
  * order, the kernel's name with its template arguments (storage valid until the next call on this
- * thread), its grid and block size, and the time between its two events in microseconds.
+ * thread), its grid and block size, what it computes - `layer`: the layer of a stack call it
+ * belongs to (0 for single-layer calls, -1 for a kernel that covers every layer of the stack),
+ * `ops`: CHEBYKAN_OP_* bits - and the time between its two events in microseconds.
  *
  * chebykan_trace_begin creates 2*max_kernels events (the only calls here that allocate); launches
  * beyond max_kernels are not timed and are counted in *dropped by chebykan_trace_end, which
  * returns the number of timed launches.  The caller must have synchronised the stream(s) before
  * chebykan_trace_get (else CHEBYKAN_ERR_LAUNCH); CHEBYKAN_ERR_NULL when nothing was collected or
- * collection is still on, CHEBYKAN_ERR_SHAPE for a bad index.  Any of name, grid, block,
- * microseconds may be NULL.  chebykan_trace_free destroys the events.  Event records cannot be
+ * collection is still on, CHEBYKAN_ERR_SHAPE for a bad index.  Any output pointer may be NULL.  chebykan_trace_free destroys the events.  Event records cannot be
  * captured into a graph by a thread that is timing; the layer entry points behave as always
  * otherwise (an event record costs about a microsecond on the stream).
  */
+#define CHEBYKAN_OP_FORWARD 1   /* the kernel computes y                                  */
+#define CHEBYKAN_OP_DX 2        /* ... dx                                                */
+#define CHEBYKAN_OP_DC 4        /* ... dC (or its per-slice partial sums)                */
+#define CHEBYKAN_OP_SUM 8       /* ... only adds partial results of the marked output(s) */
 chebykan_status chebykan_trace_begin(int max_kernels);
 int chebykan_trace_end(int *dropped);
 chebykan_status chebykan_trace_get(int index, const char **name, unsigned grid[3], unsigned *block,
-                                   float *microseconds);
+                                   int *layer, int *ops, float *microseconds);
 void chebykan_trace_free(void);
 
 #ifdef __cplusplus

@@ -64,6 +64,7 @@ static chebykan_status launch_status()
 static void generic_forward(const float* x, const float* C, float* y, int64_t B, int I, int O, int d,
                             hipStream_t s)
 {
+    const ScopedOps ops(OP_FWD);
     dim3 block(64, 4), grid((unsigned)((B + 3) / 4), (unsigned)((O + 63) / 64));
     launch<generic_forward_kernel>(grid, block, 0, s, x, C, y, B, I, O, d);
 }
@@ -71,6 +72,7 @@ static void generic_forward(const float* x, const float* C, float* y, int64_t B,
 static void generic_dx(const float* x, const float* C, const float* dy, float* dx, int64_t B, int I, int O,
                        int d, hipStream_t s)
 {
+    const ScopedOps ops(OP_DX);
     dim3 block(64, 4), grid((unsigned)((B + 3) / 4), (unsigned)((I + 63) / 64));
     launch<generic_dx_kernel>(grid, block, 0, s, x, C, dy, dx, B, I, O, d);
 }
@@ -78,6 +80,7 @@ static void generic_dx(const float* x, const float* C, const float* dy, float* d
 static void generic_dC(const float* x, const float* dy, float* dC, int64_t B, int I, int O, int d,
                        hipStream_t s)
 {
+    const ScopedOps ops(OP_DC);
     const int64_t n = (int64_t)I * O * (d + 1);
     launch<generic_dC_kernel>(dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, dy, dC, B, I,
                        O, d);
@@ -86,6 +89,7 @@ static void generic_dC(const float* x, const float* dy, float* dC, int64_t B, in
 static void generic_forward_table(const float* x, const float* C, const float* lut, int n, float* y, int64_t B,
                                   int I, int O, int d, hipStream_t s)
 {
+    const ScopedOps ops(OP_FWD);
     dim3 block(64, 4), grid((unsigned)((B + 3) / 4), (unsigned)((O + 63) / 64));
     launch<generic_forward_table_kernel>(grid, block, 0, s, x, C, lut, n, y, B, I, O, d);
 }
@@ -93,6 +97,7 @@ static void generic_forward_table(const float* x, const float* C, const float* l
 static void generic_dx_table(const float* x, const float* C, const float* dy, const float* lut, int n, float* dx,
                              int64_t B, int I, int O, int d, hipStream_t s)
 {
+    const ScopedOps ops(OP_DX);
     dim3 block(64, 4), grid((unsigned)((B + 3) / 4), (unsigned)((I + 63) / 64));
     launch<generic_dx_table_kernel>(grid, block, 0, s, x, C, dy, lut, n, dx, B, I, O, d);
 }
@@ -100,6 +105,7 @@ static void generic_dx_table(const float* x, const float* C, const float* dy, co
 static void generic_dC_table(const float* x, const float* dy, const float* lut, int n, float* dC, int64_t B, int I,
                              int O, int d, hipStream_t s)
 {
+    const ScopedOps ops(OP_DC);
     const int64_t cnt = (int64_t)I * O * (d + 1);
     launch<generic_dC_table_kernel>(dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, x, dy, lut, n,
                        dC, B, I, O, d);
@@ -310,6 +316,7 @@ chebykan_status chebykan_stack_forward(int n_layers, const int* widths, int degr
         return launch_status();
     // every argument is validated: the per-layer calls below can only fail at launch
     for (int l = 0; l < n_layers; ++l) {
+        const ScopedLayer layer(l);
         const chebykan_status st = chebykan_forward(act[l], C[l], act[l + 1], batch, widths[l], widths[l + 1], degree,
                                                     workspace, workspace_bytes, stream);
         if (st != CHEBYKAN_OK) return st;
@@ -339,6 +346,7 @@ chebykan_status chebykan_stack_backward(int n_layers, const int* widths, int deg
             return launch_status();
     }
     for (int l = n_layers - 1; l >= 0; --l) {
+        const ScopedLayer layer(l);
         const chebykan_status st = chebykan_backward(act[l], C[l], grad[l + 1], grad[l], dC[l], batch, widths[l],
                                                      widths[l + 1], degree, workspace, workspace_bytes, stream);
         if (st != CHEBYKAN_OK) return st;
@@ -369,6 +377,7 @@ chebykan_status chebykan_forward_basis(int basis, const float* x, const float* C
     (void)hipGetLastError();
     if (kernel_family() != 1 && fast_forward_family(basis, x, C, y, batch, in, out, degree, workspace, s))
         return launch_status();
+    const ScopedOps ops(OP_FWD);
     dim3 block(64, 4), grid((unsigned)((batch + 3) / 4), (unsigned)((out + 63) / 64));
     launch<generic_forward_family_kernel>(grid, block, 0, s, basis, x, C, y, batch, in, out, degree);
     return launch_status();
@@ -393,10 +402,12 @@ chebykan_status chebykan_backward_basis(int basis, const float* x, const float* 
         fast_backward_family(basis, x, C, dy, dx, dC, batch, in, out, degree, workspace, s))
         return launch_status();
     if (dx && batch > 0) {
+        const ScopedOps ops(OP_DX);
         dim3 block(64, 4), grid((unsigned)((batch + 3) / 4), (unsigned)((in + 63) / 64));
         launch<generic_dx_family_kernel>(grid, block, 0, s, basis, x, C, dy, dx, batch, in, out, degree);
     }
     if (dC) {
+        const ScopedOps ops(OP_DC);
         const int64_t cnt = (int64_t)in * out * (degree + 1);
         launch<generic_dC_family_kernel>(dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, basis, x, dy,
                            dC, batch, in, out, degree);

@@ -83,13 +83,17 @@ void pick_fwd(const float* x, const float* C, float* y, float* partial, int B, i
         if (!done) launch_fwd<D, 128, 4, Basis>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s);
         if (t.tail_begin >= 0) launch_fwd<D, 64, 4, Basis>(x, C, out, B, I, O, 1, t.tail_begin, p, ba, s);
     }
-    if (p.splits > 1) launch_sum_slices(partial, y, (int64_t)B * O, p.splits, s);
+    if (p.splits > 1) {
+        const ScopedOps ops(OP_FWD | OP_SUM);
+        launch_sum_slices(partial, y, (int64_t)B * O, p.splits, s);
+    }
 }
 
 // --------------------------------------------------------------------- dC
 template <int D>
 void launch_dC_combine(const float* partial, float* dC, int I, int O, int slices, hipStream_t s)
 {
+    const ScopedOps ops(OP_DC | OP_SUM);
     // small sums are latency-bound and gain from sharing one launch; large ones run at once
     if (g_deferred_combine && (int64_t)((O + 31) / 32) * I <= 512) {
         *g_deferred_combine = CombineJob{partial, dC, I, O, slices, 0, 0, 0};
@@ -222,7 +226,10 @@ void pick_dx(const float* x, const float* C, const float* dy, float* dx, float* 
             default: launch_dx<D, 4, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
         }
     }
-    if (p.split.splits > 1) launch_sum_slices(partial, dx, (int64_t)B * I, p.split.splits, s);
+    if (p.split.splits > 1) {
+        const ScopedOps ops(OP_DX | OP_SUM);
+        launch_sum_slices(partial, dx, (int64_t)B * I, p.split.splits, s);
+    }
 }
 
 // ------------------------------------------------------------ narrow layers
@@ -248,7 +255,10 @@ void launch_narrow_bwd(const float* x, const float* C, const float* dy, float* d
         dC ? partial : nullptr, B, I, p.G, p.rows_per_wg, ba);
     if (dC) {
         if (g_deferred_combine) *g_deferred_combine = CombineJob{partial, dC, I, O, p.slices, 1, (int64_t)I * O * (D + 1), 0};
-        else launch_sum_slices(partial, dC, (int64_t)I * O * (D + 1), p.slices, s);
+        else {
+            const ScopedOps ops(OP_DC | OP_SUM);
+            launch_sum_slices(partial, dC, (int64_t)I * O * (D + 1), p.slices, s);
+        }
     }
 }
 
@@ -279,6 +289,8 @@ void narrow_bwd_by_out(const float* x, const float* C, const float* dy, float* d
 template <int D>
 void degree_stack_combine(CombineArgs& a, hipStream_t s)
 {
+    const ScopedLayer all_layers(-1);
+    const ScopedOps ops(OP_DC | OP_SUM);
     int blocks = 0;
     for (int q = 0; q < a.n_jobs; ++q) {
         a.job[q].first_block = blocks;
@@ -294,6 +306,8 @@ void degree_stack_combine(CombineArgs& a, hipStream_t s)
 template <int D>
 void degree_chain_forward(const ChainArgs& a, int B, hipStream_t s)
 {
+    const ScopedLayer all_layers(-1);
+    const ScopedOps ops(OP_FWD);
     launch<fwd_chain_kernel<D>, chain_lds_bytes<D>(), Tags<Int<D>>>(dim3((unsigned)((B + 127) / 128)), dim3(MFMA_THREADS),
                                                       (size_t)chain_lds_bytes<D>(), s, a, B);
 }
@@ -304,6 +318,7 @@ void degree_chain_forward(const ChainArgs& a, int B, hipStream_t s)
 template <int D, class Basis>
 void degree_forward(const float* x, const float* C, float* y, int B, int I, int O, void* ws, const typename Basis::Args& ba, hipStream_t s)
 {
+    const ScopedOps ops(OP_FWD);
     if (use_narrow(B, I, O, D)) narrow_fwd_by_out<D, Basis>(x, C, y, B, I, O, ba, s);
     else pick_fwd<D, Basis>(x, C, y, static_cast<float*>(ws), B, I, O, ba, s);
 }
@@ -313,6 +328,7 @@ void degree_backward(const float* x, const float* C, const float* dy, float* dx,
                      void* ws, const typename Basis::Args& ba, hipStream_t s)
 {
     float* partial = static_cast<float*>(ws);
+    const ScopedOps both((dx ? OP_DX : 0) | (dC ? OP_DC : 0));
     if (use_narrow(B, I, O, D)) {
         narrow_bwd_by_out<D, Basis>(x, C, dy, dx, dC, partial, B, I, O, ba, s);
         return;
@@ -326,8 +342,14 @@ void degree_backward(const float* x, const float* C, const float* dy, float* dx,
         return;
     }
     // the dx partials are summed before the dC kernel reuses the workspace (same stream)
-    if (dx) pick_dx<D, Basis>(x, C, dy, dx, partial, B, I, O, ba, s);
-    if (dC) pick_dC<D, Basis>(x, dy, dC, partial, B, I, O, plan_dC(B, I, O, D), ba, s);
+    if (dx) {
+        const ScopedOps ops(OP_DX);
+        pick_dx<D, Basis>(x, C, dy, dx, partial, B, I, O, ba, s);
+    }
+    if (dC) {
+        const ScopedOps ops(OP_DC);
+        pick_dC<D, Basis>(x, dy, dC, partial, B, I, O, plan_dC(B, I, O, D), ba, s);
+    }
 }
 
 }  // namespace chebykan

@@ -30,6 +30,27 @@ bool register_kernel(KernelRecord* rec, const void* fn, int max_lds_bytes, const
 // First record of the registry.
 KernelRecord* kernel_registry();
 
+// What the calling thread's launches compute, for the timing report: the layer of a stack call
+// they belong to (-1: every layer at once; 0 for single-layer calls) and which results
+// (OP_* bits; OP_SUM marks a kernel that only adds partial results).  Set by the dispatch code
+// through the two scoped helpers; read only while timing is on.
+enum : int { OP_FWD = 1, OP_DX = 2, OP_DC = 4, OP_SUM = 8 };
+struct LaunchContext {
+    int layer;
+    int ops;
+};
+extern thread_local LaunchContext g_launch_context;
+struct ScopedOps {
+    int saved;
+    explicit ScopedOps(int ops) : saved(g_launch_context.ops) { g_launch_context.ops = ops; }
+    ~ScopedOps() { g_launch_context.ops = saved; }
+};
+struct ScopedLayer {
+    int saved;
+    explicit ScopedLayer(int layer) : saved(g_launch_context.layer) { g_launch_context.layer = layer; }
+    ~ScopedLayer() { g_launch_context.layer = saved; }
+};
+
 // Kernel timing of the calling thread: null when off.
 struct TraceSink;
 extern thread_local TraceSink* g_trace;

@@ -7,6 +7,7 @@
 #include "basis.h"
 #include "chain_kernels.h"
 #include "dispatch.h"
+#include "launch.h"
 #include "mfma_kernels.h"
 #include "plans.h"
 
@@ -202,6 +203,7 @@ bool fast_stack_backward(int n_layers, const int* widths, int d, int64_t B, cons
     for (int l = n_layers - 1; l >= 0; --l) {
         CombineJob job{nullptr, nullptr, 0, 0, 0, 0, 0, 0};
         g_deferred_combine = &job;
+        const ScopedLayer layer(l);
         const bool ok = fast_backward(act[l], C[l], grad[l + 1], grad[l], dC[l], B, widths[l], widths[l + 1], d, region, s);
         g_deferred_combine = nullptr;
         if (!ok) return false;   // cannot happen after the checks above; nothing more is enqueued

@@ -109,6 +109,7 @@ int kernel_family() { return g_family.load(std::memory_order_relaxed); }
 struct TraceRecord {
     const char* signature;
     unsigned grid[3], block;
+    LaunchContext context;
 };
 struct TraceSink {
     std::vector<hipEvent_t> events;     // two per kernel, created by chebykan_trace_begin
@@ -119,6 +120,7 @@ struct TraceSink {
     std::string name;                   // scratch for chebykan_trace_get
 };
 thread_local TraceSink* g_trace = nullptr;
+thread_local LaunchContext g_launch_context = {0, 0};
 static thread_local TraceSink* g_sink = nullptr;   // this thread's sink, collecting or not
 
 void trace_before(TraceSink* sink, const char* signature, dim3 grid, dim3 block, hipStream_t s)
@@ -129,7 +131,7 @@ void trace_before(TraceSink* sink, const char* signature, dim3 grid, dim3 block,
         return;
     }
     (void)hipEventRecord(sink->events[2 * sink->records.size()], s);
-    sink->records.push_back(TraceRecord{signature, {grid.x, grid.y, grid.z}, block.x * block.y * block.z});
+    sink->records.push_back(TraceRecord{signature, {grid.x, grid.y, grid.z}, block.x * block.y * block.z, g_launch_context});
     sink->open = true;
 }
 
@@ -192,7 +194,8 @@ int chebykan_trace_end(int* dropped)
     return g_sink ? (int)g_sink->records.size() : 0;
 }
 
-chebykan_status chebykan_trace_get(int index, const char** name, unsigned grid[3], unsigned* block, float* microseconds)
+chebykan_status chebykan_trace_get(int index, const char** name, unsigned grid[3], unsigned* block, int* layer, int* ops,
+                                   float* microseconds)
 {
     TraceSink* sink = g_sink;
     if (!sink || g_trace) return CHEBYKAN_ERR_NULL;               // nothing collected, or still collecting
@@ -224,6 +227,8 @@ chebykan_status chebykan_trace_get(int index, const char** name, unsigned grid[3
     }
     if (grid) { grid[0] = r.grid[0]; grid[1] = r.grid[1]; grid[2] = r.grid[2]; }
     if (block) *block = r.block;
+    if (layer) *layer = r.context.layer;
+    if (ops) *ops = r.context.ops;
     if (microseconds) {
         float ms = 0.0f;
         if (hipEventElapsedTime(&ms, sink->events[2 * (size_t)index], sink->events[2 * (size_t)index + 1]) != hipSuccess) {

@@ -46,8 +46,17 @@ def test_kernel_timing_names_and_durations():
     assert names[0].startswith("fwd_mfma_kernel<FwdCfg<6, 64")
     assert any(nm.startswith("dx2_mfma_kernel<") or nm.startswith("dx_mfma_kernel<") for nm in names)
     assert any(nm.startswith("dC_mfma_kernel<") for nm in names)
-    for name, grid, block, us in recs:
+    for name, grid, block, layer, ops, us in recs:
         assert grid[0] >= 1 and block in (256, 1024) and 0.5 < us < 5000.0, (name, grid, block, us)
+        assert layer == 0
+        if name.startswith("fwd_mfma_kernel"):
+            assert ops == binding.OP_FORWARD
+        if name.startswith("dx2_mfma_kernel") or name.startswith("dx_mfma_kernel"):
+            assert ops == binding.OP_DX
+        if name.startswith("dC_mfma_kernel"):
+            assert ops == binding.OP_DC
+        if name.startswith("dC_combine_kernel"):
+            assert ops == binding.OP_DC | binding.OP_SUM
     # the timed calls computed what the untimed ones compute
     y_ref = oracle.forward(x.cpu().numpy(), C.cpu().numpy())
     assert oracle.rel_err(y.cpu().numpy(), y_ref) <= 1e-5
