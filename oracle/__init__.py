@@ -68,6 +68,12 @@ def _load() -> ctypes.CDLL:
         lib.oracle_forward_lut.restype = ctypes.c_int
         lib.oracle_backward_lut.argtypes = [dp, dp, dp, dp, i64, i8p, dp, dp, dp, i64, i64, i64, ctypes.c_int]
         lib.oracle_backward_lut.restype = ctypes.c_int
+        lib.oracle_lut_build_derivative.argtypes = [dp, ctypes.c_int, i64]
+        lib.oracle_lut_build_derivative.restype = ctypes.c_int
+        lib.oracle_lut_eval_derivative.argtypes = [dp, ctypes.c_int, i64, ctypes.c_double, dp]
+        lib.oracle_lut_eval_derivative.restype = None
+        lib.oracle_dx_lut2.argtypes = [dp, dp, dp, dp, i64, dp, i64, i64, i64, ctypes.c_int]
+        lib.oracle_dx_lut2.restype = ctypes.c_int
         lib.oracle_basis_eval.argtypes = [ctypes.c_int, ctypes.c_double, ctypes.c_int, dp, dp]
         lib.oracle_basis_eval.restype = ctypes.c_int
         lib.oracle_forward_basis.argtypes = [ctypes.c_int, dp, dp, dp, i64, i64, i64, ctypes.c_int]
@@ -228,6 +234,37 @@ def lut_eval(lut, u: float, shift: int = 0):
     _load().oracle_lut_eval(_dp(lut), K - 1, n, float(u), int(shift), _dp(T), _dp(dT), ctypes.byref(cell),
                             ctypes.byref(frac))
     return T, dT, cell.value, frac.value
+
+
+def lut_build_derivative(degree: int, n: int) -> np.ndarray:
+    """dLUT[k, i] = T_k'(-1 + i*2/(n-1)) in fp64, shape [degree+1, n]: the auxiliary derivative table."""
+    dlut = np.empty((degree + 1, n), dtype=np.float64)
+    rc = _load().oracle_lut_build_derivative(_dp(dlut), int(degree), int(n))
+    if rc != 0:
+        raise ValueError("oracle_lut_build_derivative failed")
+    return dlut
+
+
+def lut_eval_derivative(dlut, u: float) -> np.ndarray:
+    """The interpolated derivative table at u: dT_0..dT_d."""
+    dlut = _f64(dlut)
+    K, n = dlut.shape
+    dT = np.empty(K)
+    _load().oracle_lut_eval_derivative(_dp(dlut), K - 1, n, float(u), _dp(dT))
+    return dT
+
+
+def dx_lut2(x, C, dy, dlut) -> np.ndarray:
+    """dx of the table variant whose derivative comes from the interpolated auxiliary table."""
+    B, I, O, d = _check_shapes(x, C, dy)
+    x64, C64, dy64, dlut = _f64(x), _f64(C), _f64(dy), _f64(dlut)
+    if dlut.shape[0] != d + 1:
+        raise ValueError("table has %d rows, layer needs %d" % (dlut.shape[0], d + 1))
+    dx = np.empty((B, I), dtype=np.float64)
+    rc = _load().oracle_dx_lut2(_dp(x64), _dp(C64), _dp(dy64), _dp(dlut), dlut.shape[1], _dp(dx), B, I, O, d)
+    if rc != 0:
+        raise ValueError("oracle_dx_lut2 failed")
+    return dx
 
 
 def forward_lut(x, C, lut) -> np.ndarray:

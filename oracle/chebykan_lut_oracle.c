@@ -28,6 +28,17 @@
  * cell boundary, where an fp32 implementation may legitimately pick the other
  * cell: T is continuous across the boundary, the difference quotient is not.
  *
+ * Second-order derivative ("auxiliary table", the other option Sec. 4.2.2 names for the
+ * derivative).  Reading taken: the auxiliary table holds samples of the derivative itself,
+ *   dLUT[k][i] = T_k'(x_i) = k U_{k-1}(x_i)   (second-kind recurrence, finite at x = +-1),
+ * and is interpolated exactly like the value table,
+ *   T_k'(u) ~ dLUT[k][c] + f * (dLUT[k][c+1] - dLUT[k][c]),
+ * which is second-order in Delta (error <= Delta^2/8 max|T_k'''|,  max|T_k'''| =
+ * k^2 (k^2-1)(k^2-4)/15 at x = +-1) and continuous across knots.  A table of pre-computed
+ * neighbour differences would reproduce the first-order quotient above bit for bit and is
+ * therefore not a separate variant.  oracle_dx_lut2 is the dx of oracle_backward_lut with this
+ * derivative; dC does not involve the derivative and is unchanged.
+ *
  * Pins (tests/test_oracle_lut_pins.py): table against cos(k acos x); exactness
  * at grid points and for degree <= 1; |T_lut - T| <= Delta^2/8 * max|T_k''|;
  * the difference quotient equals T_k' somewhere inside the cell; dx is the
@@ -58,6 +69,39 @@ int oracle_lut_build(double *lut, int d, int64_t n)
         }
     }
     return 0;
+}
+
+/* dLUT[k][i] = T_k'(x_i) on the same grid, T_k' = k U_{k-1} with U_0 = 1, U_1 = 2x, U_{j+1} = 2x U_j - U_{j-1}. */
+int oracle_lut_build_derivative(double *dlut, int d, int64_t n)
+{
+    if (d < 0 || d > LUT_ORACLE_MAX_DEGREE || n < 2) return -1;
+    const double delta = 2.0 / (double)(n - 1);
+    for (int64_t i = 0; i < n; ++i) {
+        const double xi = (i == n - 1) ? 1.0 : -1.0 + (double)i * delta;
+        double u_prev = 0.0, u_cur = 1.0;   /* U_{-1} = 0, U_0 = 1 */
+        dlut[0 * n + i] = 0.0;
+        for (int k = 1; k <= d; ++k) {
+            dlut[(int64_t)k * n + i] = (double)k * u_cur;     /* k U_{k-1} */
+            const double u_next = 2.0 * xi * u_cur - u_prev;
+            u_prev = u_cur;
+            u_cur = u_next;
+        }
+    }
+    return 0;
+}
+
+/* Interpolated derivative table at u: dT[k] = dLUT[k][c] + f (dLUT[k][c+1] - dLUT[k][c]), same cell rule. */
+void oracle_lut_eval_derivative(const double *dlut, int d, int64_t n, double u, double *dT)
+{
+    const double pos = (u + 1.0) / 2.0 * (double)(n - 1);
+    int64_t c = (int64_t)floor(pos);
+    if (c > n - 2) c = n - 2;
+    if (c < 0) c = 0;
+    const double f = pos - (double)c;
+    for (int k = 0; k <= d; ++k) {
+        const double lo = dlut[(int64_t)k * n + c], hi = dlut[(int64_t)k * n + c + 1];
+        dT[k] = lo + f * (hi - lo);
+    }
 }
 
 /* Interpolated T_0..T_d and difference quotients dT_0..dT_d at u in [-1,1]. */
@@ -144,6 +188,30 @@ int oracle_backward_lut(const double *x, const double *C, const double *dy, cons
                     for (int64_t k = 0; k < K; ++k) dC[(i * O + o) * K + k] += T[k] * g;
                 }
             }
+        }
+    }
+    return 0;
+}
+
+/* dx of the layer with the interpolated derivative table in place of the difference quotient. */
+int oracle_dx_lut2(const double *x, const double *C, const double *dy, const double *dlut, int64_t n, double *dx,
+                   int64_t B, int64_t I, int64_t O, int d)
+{
+    if (d < 0 || d > LUT_ORACLE_MAX_DEGREE || n < 2) return -1;
+    const int64_t K = d + 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t b = 0; b < B; ++b) {
+        double dT[LUT_ORACLE_MAX_DEGREE + 1];
+        for (int64_t i = 0; i < I; ++i) {
+            const double u = tanh(x[b * I + i]);
+            oracle_lut_eval_derivative(dlut, d, n, u, dT);
+            double acc = 0.0;
+            for (int64_t o = 0; o < O; ++o) {
+                double inner = 0.0;
+                for (int64_t k = 1; k < K; ++k) inner += C[(i * O + o) * K + k] * dT[k];
+                acc += dy[b * O + o] * inner;
+            }
+            dx[b * I + i] = (1.0 - u * u) * acc;
         }
     }
     return 0;

@@ -2,8 +2,8 @@
 
 Bar: max |gpu - oracle| / RMS(oracle) <= 1e-5 for each of y, dx, dC (exact
 basis, fp32 arithmetic).  Small shapes are compared element by element; the
-full-size workloads are compared on sampled outputs that the oracle computes
-one by one, layer by layer on the GPU's own fp32 layer inputs.
+full-size workloads are compared, layer by layer on the GPU's own fp32 layer
+inputs, on whole rows and whole coefficient slabs that reach every output tile.
 """
 import numpy as np
 import pytest
@@ -253,18 +253,40 @@ def test_non_default_stream():
 
 # ------------------------------------------------------- full-size workloads
 
-def _sampled_layer_check(x, C, dy, y, dx, dC, rng, label, n=1500):
+def _tile_covering_rows(B):
+    """One row out of every block of 128 consecutive rows, at an offset that walks through all 128 positions
+    (so every 32-row block position and both edges of a tile occur), plus the first and last rows of the tensor."""
+    tiles = np.arange((B + 127) // 128)
+    rows = tiles * 128 + (tiles * 37 + 5) % 128
+    rows = np.concatenate([rows[rows < B], [0, 127 % B, B - 1, max(B - 128, 0)]])
+    return np.unique(rows)
+
+
+def _tile_covering_features(I, degree):
+    """One input feature out of every block of min(16, 128 // (degree+1)) features - no coefficient-gradient
+    tile is wider than that - at a walking offset, plus the first and last feature."""
+    step = max(1, min(16, 128 // (degree + 1)))
+    blocks = np.arange((I + step - 1) // step)
+    feats = blocks * step + (blocks * 5 + 3) % step
+    return np.unique(np.concatenate([feats[feats < I], [0, I - 1]]))
+
+
+def _covering_layer_check(x, C, dy, y, dx, dC, label):
+    """A full-size layer against the oracle on whole rows and whole coefficient slabs chosen so that every
+    output tile of y, dx and dC holds compared elements: y[b, :] and dx[b, :] for one row of every 128-row
+    block, dC[i, :, :] for one feature of every feature block.  dC[i] needs only column i of x.
+    Each tensor's error is normalised by the RMS of the oracle values compared."""
     B, I = x.shape
     _, O, K = C.shape
-    bs, os_ = rng.integers(0, B, n), rng.integers(0, O, n)
-    is_, ks = rng.integers(0, I, n), rng.integers(0, K, n)
-    x64, C64, dy64 = x.astype(np.float64), C.astype(np.float64), dy.astype(np.float64)
-    e_y = oracle.rel_err(y[bs, os_], oracle.forward_at(x64, C64, bs, os_))
-    e_dx = oracle.rel_err(dx[bs, is_], oracle.dx_at(x64, C64, dy64, bs, is_))
-    nc = min(n, 400)
-    e_dC = oracle.rel_err(dC[is_[:nc], os_[:nc], ks[:nc]],
-                          oracle.dC_at(x64, dy64, K - 1, is_[:nc], os_[:nc], ks[:nc]))
-    print("%s y=%.2e dx=%.2e dC=%.2e" % (label, e_y, e_dx, e_dC), flush=True)
+    rows = _tile_covering_rows(B)
+    feats = _tile_covering_features(I, K - 1)
+    xr, dyr = np.ascontiguousarray(x[rows]), np.ascontiguousarray(dy[rows])
+    e_y = oracle.rel_err(y[rows], oracle.forward(xr, C))
+    dx_ref, _ = oracle.backward(xr, C, dyr, need_dC=False)
+    e_dx = oracle.rel_err(dx[rows], dx_ref)
+    _, dC_ref = oracle.backward(np.ascontiguousarray(x[:, feats]), np.ascontiguousarray(C[feats]), dy, need_dx=False)
+    e_dC = oracle.rel_err(dC[feats], dC_ref)
+    print("%s rows=%d features=%d y=%.2e dx=%.2e dC=%.2e" % (label, rows.size, feats.size, e_y, e_dx, e_dC), flush=True)
     assert np.isfinite(y).all() and np.isfinite(dx).all() and np.isfinite(dC).all()
     assert e_y <= TOL and e_dx <= TOL and e_dC <= TOL, (label, e_y, e_dx, e_dC)
 
@@ -298,12 +320,11 @@ def test_forward_split_when_the_wide_launch_would_underfill(B):
 
 
 @pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
-def test_full_size_workload_sampled(name):
-    """Whole stack at its real size, in the launch configuration the benchmark times.
-    Each layer is checked on the GPU's own fp32 inputs (x_l = y_{l-1}, dy_l = dx_{l+1})."""
+def test_full_size_workload_every_tile(name):
+    """Whole stack at its real size through the single-layer calls.  Each layer is checked on the GPU's own
+    fp32 inputs (x_l = y_{l-1}, dy_l = dx_{l+1}), on whole rows and coefficient slabs that reach every tile."""
     w = wl.WORKLOADS[name]
     x0, Cs, dy_last = wl.workload_inputs(w)
-    rng = np.random.default_rng(99 + w.index)
     xs = [x0]
     for C in Cs:
         (y,) = gpu_layer(xs[-1], C)
@@ -313,7 +334,7 @@ def test_full_size_workload_sampled(name):
     for l in reversed(range(len(Cs))):
         y, dx, dC = gpu_layer(xs[l], Cs[l], dys[l])
         assert np.array_equal(y, xs[l + 1])          # forward is reproducible
-        _sampled_layer_check(xs[l], Cs[l], dys[l], y, dx, dC, rng, "%s layer %d %s" % (name, l, w.layers[l]))
+        _covering_layer_check(xs[l], Cs[l], dys[l], y, dx, dC, "%s layer %d %s" % (name, l, w.layers[l]))
         if l > 0:
             dys[l - 1] = dx
 

@@ -69,8 +69,9 @@ def test_stack_calls_against_the_oracle(widths, degree, B):
 def test_full_size_workload_through_the_stack_calls(name):
     """Each workload at its real size through the two calls the benchmark times (for the tabular stack:
     the single-launch forward, the one-kernel first-layer backward and the shared slice-sum launch).
-    Sampled outputs of every layer against the oracle, on the GPU's own fp32 layer inputs."""
-    from test_gpu_parity import _sampled_layer_check
+    Whole rows and coefficient slabs that reach every output tile of every layer against the oracle, on
+    the GPU's own fp32 layer inputs."""
+    from test_gpu_parity import _covering_layer_check
     w = wl.WORKLOADS[name]
     x0, Cs, dy_last = wl.workload_inputs(w)
     B, widths, degree = w.batch, list(w.widths), w.degree
@@ -83,11 +84,10 @@ def test_full_size_workload_through_the_stack_calls(name):
     dCd = [torch.full_like(c, float("nan")) for c in Cd]
     binding.chebykan_stack_backward(Cd, acts, grads, dCd, ws)
     torch.cuda.synchronize()
-    rng = np.random.default_rng(7 + w.index)
     for l in range(len(Cs)):
-        _sampled_layer_check(acts[l].cpu().numpy(), Cs[l], grads[l + 1].cpu().numpy(), acts[l + 1].cpu().numpy(),
-                             grads[l].cpu().numpy(), dCd[l].cpu().numpy(), rng,
-                             "%s stack calls, layer %d %s" % (name, l, w.layers[l]))
+        _covering_layer_check(acts[l].cpu().numpy(), Cs[l], grads[l + 1].cpu().numpy(), acts[l + 1].cpu().numpy(),
+                              grads[l].cpu().numpy(), dCd[l].cpu().numpy(),
+                              "%s stack calls, layer %d %s" % (name, l, w.layers[l]))
 
 
 def test_stack_skips_and_errors():

@@ -222,3 +222,119 @@ def test_sampled_dC_matches_the_full_computation():
     is_, os_, ks = [0, 5, 3, 2], [4, 0, 2, 2], [0, 4, 1, 3]
     got = oracle.dC_lut_at(x, dy, lut, is_, os_, ks)
     assert np.allclose(got, dC[is_, os_, ks], rtol=1e-13, atol=1e-13)
+
+
+# ------------------------------------------- auxiliary derivative table (second-order dx)
+
+def _d3_bound(k):
+    """max |T_k'''| on [-1, 1], attained at the ends: k^2 (k^2-1)(k^2-4) / 15."""
+    return k * k * (k * k - 1) * (k * k - 4) / 15.0
+
+
+@pytest.mark.parametrize("n", [2, 3, 17, 1025])
+def test_derivative_table_matches_closed_forms(n):
+    d = 9
+    dlut = oracle.lut_build_derivative(d, n)
+    assert dlut.shape == (d + 1, n)
+    xs = np.linspace(-1.0, 1.0, n)
+    k = np.arange(d + 1)
+    # ends: T_k'(+-1) = (+-1)^(k+1) k^2, exactly
+    assert np.array_equal(dlut[:, -1], (k * k).astype(float))
+    assert np.array_equal(dlut[:, 0], ((-1.0) ** (k + 1)) * k * k)
+    # interior: k sin(k t) / sin t at x = cos t
+    inner = slice(1, n - 1)
+    if n > 2:
+        t = np.arccos(xs[inner])
+        want = k[:, None] * np.sin(k[:, None] * t[None, :]) / np.sin(t)[None, :]
+        assert np.max(np.abs(dlut[:, inner] - want)) < 2e-10
+    # numpy's Chebyshev derivative as an independent generator
+    for kk in range(d + 1):
+        c = np.zeros(kk + 1)
+        c[kk] = 1.0
+        der = np.polynomial.chebyshev.chebder(c) if kk >= 1 else np.zeros(1)
+        assert np.max(np.abs(dlut[kk] - np.polynomial.chebyshev.chebval(xs, der))) < 1e-10
+
+
+def test_hand_worked_derivative_table(golden_dir):
+    rows, example = [], None
+    with open(os.path.join(golden_dir, "dlut_n5_degree3.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            if "|" in line:
+                u, vals = line.split("|")
+                example = (float(u), np.array(vals.split(), dtype=float))
+            else:
+                rows.append([float(t) for t in line.split()])
+    dlut = oracle.lut_build_derivative(3, 5)
+    assert np.array_equal(dlut, np.array(rows))
+    assert np.allclose(oracle.lut_eval_derivative(dlut, example[0]), example[1], atol=1e-15)
+
+
+def test_interpolated_derivative_is_exact_where_it_must_be():
+    n, d = 33, 7
+    dlut = oracle.lut_build_derivative(d, n)
+    xs = np.linspace(-1.0, 1.0, n)
+    for i in (0, 1, 7, 16, 31, 32):                       # at grid points (both ends: the clamped last cell)
+        assert np.allclose(oracle.lut_eval_derivative(dlut, xs[i]), dlut[:, i], rtol=0, atol=1e-12)
+    for u in (-0.93, -0.2, 0.031, 0.77):                  # T_0' = 0, T_1' = 1, T_2' = 4u are linear: no error
+        got = oracle.lut_eval_derivative(dlut, u)
+        assert np.allclose(got[:3], [0.0, 1.0, 4.0 * u], atol=1e-13)
+
+
+@pytest.mark.parametrize("n", [17, 129, 1025])
+def test_interpolated_derivative_error_bound_and_order(n):
+    """Linear interpolation of T_k' errs by at most Delta^2/8 max|T_k'''|; near the ends (where T_k''' is
+    largest) a cell midpoint comes close to the bound; halving the step divides the error by about four."""
+    d = 8
+    def worst(nn):
+        dlut = oracle.lut_build_derivative(d, nn)
+        us = np.linspace(-1.0, 1.0, 40 * (nn - 1) + 1)
+        got = np.array([oracle.lut_eval_derivative(dlut, u) for u in us])
+        want = np.array([oracle.cheb_dT(u, d) for u in us])
+        return np.max(np.abs(got - want), axis=0)
+    delta = 2.0 / (n - 1)
+    err = worst(n)
+    for k in range(d + 1):
+        bound = delta * delta / 8.0 * _d3_bound(k)
+        assert err[k] <= bound * (1 + 1e-9) + 1e-12, (k, err[k], bound)
+        if k >= 3 and n >= 129:
+            assert err[k] >= 0.8 * bound, (k, err[k], bound)     # nearly attained in the end cells
+    if n >= 129:                                              # 17 samples are too coarse for the asymptotic order
+        err2 = worst(2 * (n - 1) + 1)
+        for k in range(3, d + 1):
+            assert 3.5 <= err[k] / err2[k] <= 4.5, (k, err[k] / err2[k])
+
+
+def test_dx_with_derivative_table_against_a_written_out_sum():
+    """The layer formula around the table: dx[b,i] = (1-u^2) sum_o dy[b,o] sum_{k>=1} C[i,o,k] dT_k(u), with dT
+    taken from numpy's own piecewise-linear interpolation of the table rows."""
+    B, I, O, d, n = 3, 4, 2, 5, 21
+    x, C, dy = _layer(71, B, I, O, d)
+    dlut = oracle.lut_build_derivative(d, n)
+    grid = np.linspace(-1.0, 1.0, n)
+    want = np.zeros((B, I))
+    for b in range(B):
+        for i in range(I):
+            u = np.tanh(x[b, i])
+            dT = np.array([np.interp(u, grid, dlut[k]) for k in range(d + 1)])
+            want[b, i] = (1.0 - u * u) * sum(dy[b, o] * sum(C[i, o, k] * dT[k] for k in range(1, d + 1)) for o in range(O))
+    assert np.allclose(oracle.dx_lut2(x, C, dy, dlut), want, rtol=1e-12, atol=1e-13)
+    # coefficients of T_0 never reach dx
+    C2 = C.copy()
+    C2[:, :, 0] += 5.0
+    assert np.allclose(oracle.dx_lut2(x, C2, dy, dlut), want, rtol=1e-12, atol=1e-13)
+
+
+def test_dx_with_derivative_table_converges_to_the_exact_layer_at_second_order():
+    x, C, dy = _layer(81, 300, 20, 12, 8)
+    exact, _ = oracle.backward(x, C, dy, need_dC=False)
+    errs = [oracle.rel_err(oracle.dx_lut2(x, C, dy, oracle.lut_build_derivative(8, n)), exact) for n in (129, 257, 513, 1025)]
+    for a, b in zip(errs, errs[1:]):
+        assert 3.0 <= a / b <= 5.0, errs
+    assert errs[-1] <= 1e-3                                # the bound stated for any table variant, at 1025 samples
+    # the first-order difference quotient of the plain table is far outside it at the same size
+    lut = oracle.lut_build(8, 1025)
+    first_order, _ = oracle.backward_lut(x, C, dy, lut, need_dC=False)
+    assert oracle.rel_err(first_order, exact) > 1e-2
