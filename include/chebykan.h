@@ -162,6 +162,27 @@ chebykan_status chebykan_backward_lut(const float *x, const float *C, const floa
                                       void *workspace, size_t workspace_bytes, chebykan_stream_t stream);
 
 /*
+ * Second-order derivative for the table variant.  Sec. 4.2.2 names two sources for the
+ * derivative: the difference of neighbouring samples (chebykan_backward_lut above, first order
+ * in Delta) or an auxiliary table.  Here the auxiliary table holds samples of the derivative,
+ *
+ *   dLUT[k][i] = T_k'(-1 + i*Delta) = k U_{k-1}(-1 + i*Delta),     same grid, same layout,
+ *   T_k'(u) ~ dLUT[k][c] + f*(dLUT[k][c+1] - dLUT[k][c])            same cell c and fraction f,
+ *
+ * whose error is at most Delta^2/8 * k^2(k^2-1)(k^2-4)/15 and which is continuous across table
+ * knots.  chebykan_lut_build_derivative fills a HOST array like chebykan_lut_build does;
+ * chebykan_backward_lut2 is chebykan_backward_lut with `dlut` (DEVICE, same layout as `lut`)
+ * supplying the derivative in dx; dC and every other convention are unchanged.  The forward
+ * pass of this variant is chebykan_forward_lut.  Both tables are staged on chip together when
+ * 2*(degree+1)*lut_size*4 bytes <= 80 KiB at degrees 2..8; otherwise the any-degree kernels run.
+ */
+chebykan_status chebykan_lut_build_derivative(float *dlut, int degree, int lut_size);
+chebykan_status chebykan_backward_lut2(const float *x, const float *C, const float *dy, const float *lut,
+                                       const float *dlut, int lut_size, float *dx, float *dC,
+                                       int64_t batch, int in, int out, int degree,
+                                       void *workspace, size_t workspace_bytes, chebykan_stream_t stream);
+
+/*
  * Other KAN bases on the same layer skeleton (paper Sec. 2.3: every variant expands
  * each input into K = degree+1 basis functions by a short recurrence and contracts
  * them with C; Sec. 6.3 reports the method on Fourier, Legendre and Hermite KANs).

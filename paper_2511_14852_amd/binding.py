@@ -27,6 +27,7 @@ EXPORTS = (
     "chebykan_status_string", "chebykan_set_kernel_family", "chebykan_version",
     "chebykan_calibrate_mfma", "chebykan_calibrate_copy",
     "chebykan_lut_build", "chebykan_forward_lut", "chebykan_backward_lut",
+    "chebykan_lut_build_derivative", "chebykan_backward_lut2",
     "chebykan_forward_basis", "chebykan_backward_basis",
     "chebykan_stack_workspace_bytes", "chebykan_stack_forward", "chebykan_stack_backward",
     "chebykan_init", "chebykan_backward_noalloc",
@@ -84,6 +85,10 @@ def load() -> ctypes.CDLL:
         lib.chebykan_forward_lut.restype = ci
         lib.chebykan_backward_lut.argtypes = [vp, vp, vp, vp, ci, vp, vp, i64, ci, ci, ci, vp, sz, vp]
         lib.chebykan_backward_lut.restype = ci
+        lib.chebykan_lut_build_derivative.argtypes = [vp, ci, ci]
+        lib.chebykan_lut_build_derivative.restype = ci
+        lib.chebykan_backward_lut2.argtypes = [vp, vp, vp, vp, vp, ci, vp, vp, i64, ci, ci, ci, vp, sz, vp]
+        lib.chebykan_backward_lut2.restype = ci
         lib.chebykan_calibrate_mfma.argtypes = [vp, ci, ci, ctypes.POINTER(ctypes.c_double), vp]
         lib.chebykan_calibrate_mfma.restype = ci
         lib.chebykan_calibrate_copy.argtypes = [vp, vp, i64, vp]
@@ -352,6 +357,42 @@ def chebykan_backward_lut(x, C, dy, lut, dx, dC, workspace=None, stream=None) ->
                                           B, I, O, K - 1, ws_ptr, ws_bytes, _stream_ptr(stream)))
     if st != CHEBYKAN_OK:
         raise ChebykanError(st, "chebykan_backward_lut")
+
+
+def chebykan_lut_build_derivative(degree: int, lut_size: int):
+    """The auxiliary table of T_0'..T_degree' on the same grid as chebykan_lut_build, CPU fp32 [degree+1, lut_size]."""
+    import torch
+    dlut = torch.empty((degree + 1, lut_size), dtype=torch.float32)
+    st = int(load().chebykan_lut_build_derivative(dlut.data_ptr(), int(degree), int(lut_size)))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_lut_build_derivative")
+    return dlut
+
+
+def chebykan_backward_lut2(x, C, dy, lut, dlut, dx, dC, workspace=None, stream=None) -> None:
+    """Table-interpolated backward with the derivative taken from the auxiliary table dlut."""
+    _check(x, "x")
+    B, I = x.shape
+    _check(C, "C")
+    if C.dim() != 3 or C.shape[0] != I:
+        raise ValueError("C must be [in, out, degree+1]")
+    O, K = int(C.shape[1]), int(C.shape[2])
+    n = _check_lut(lut, K)
+    if _check_lut(dlut, K) != n:
+        raise ValueError("lut and dlut must have the same number of samples")
+    _check(dy, "dy", (B, O))
+    if dx is not None:
+        _check(dx, "dx", (B, I))
+    if dC is not None:
+        _check(dC, "dC", (I, O, K))
+    need = chebykan_workspace_bytes(B, I, O, K - 1, CHEBYKAN_PASS_BACKWARD)
+    ws_ptr, ws_bytes = _ws(workspace, need)
+    st = int(load().chebykan_backward_lut2(x.data_ptr(), C.data_ptr(), dy.data_ptr(), lut.data_ptr(), dlut.data_ptr(), n,
+                                           None if dx is None else dx.data_ptr(),
+                                           None if dC is None else dC.data_ptr(),
+                                           B, I, O, K - 1, ws_ptr, ws_bytes, _stream_ptr(stream)))
+    if st != CHEBYKAN_OK:
+        raise ChebykanError(st, "chebykan_backward_lut2")
 
 
 BASIS_CHEBYSHEV, BASIS_LEGENDRE, BASIS_HERMITE, BASIS_FOURIER = 0, 1, 2, 3

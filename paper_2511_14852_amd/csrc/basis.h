@@ -114,6 +114,7 @@ __device__ __forceinline__ void cheb_dT(float u, float (&dT)[D > 0 ? D : 1])
 // its GPU; 160 KB of LDS per compute unit hold tables of a few thousand samples.
 struct ExactBasis {
     static constexpr bool kTable = false;
+    static constexpr int kTableRows = 0;   // tables staged per sample: 0 none, 1 values, 2 values and derivatives
     struct Args {};
     __device__ ExactBasis(const Args&, float*, int, int, int) {}
     template <int D>
@@ -148,6 +149,7 @@ struct ExactBasis {
 // (dT is dB_k/dx).
 struct LegendreBasis {   // (k+1) P_{k+1} = (2k+1) u P_k - k P_{k-1};  P'_{k+1} = P'_{k-1} + (2k+1) P_k;  u = tanh x
     static constexpr bool kTable = false;
+    static constexpr int kTableRows = 0;
     struct Args {};
     __device__ LegendreBasis(const Args&, float*, int, int, int) {}
     template <int D>
@@ -183,6 +185,7 @@ struct LegendreBasis {   // (k+1) P_{k+1} = (2k+1) u P_k - k P_{k-1};  P'_{k+1} 
 
 struct HermiteBasis {    // physicists': H_{k+1} = 2 u H_k - 2k H_{k-1};  H'_k = 2k H_{k-1};  u = tanh x
     static constexpr bool kTable = false;
+    static constexpr int kTableRows = 0;
     struct Args {};
     __device__ HermiteBasis(const Args&, float*, int, int, int) {}
     template <int D>
@@ -216,6 +219,7 @@ struct HermiteBasis {    // physicists': H_{k+1} = 2 u H_k - 2k H_{k-1};  H'_k =
 
 struct FourierBasis {    // B_0 = 1, B_{2m-1} = cos(m x), B_{2m} = sin(m x) on the raw input; D = 2G
     static constexpr bool kTable = false;
+    static constexpr int kTableRows = 0;
     struct Args {};
     __device__ FourierBasis(const Args&, float*, int, int, int) {}
     // cos(m x), sin(m x) for m = 1..G from cos x, sin x by the angle-addition recurrence (Sec. 2.3)
@@ -257,6 +261,7 @@ struct FourierBasis {    // B_0 = 1, B_{2m-1} = cos(m x), B_{2m} = sin(m x) on t
 
 struct TableBasis {
     static constexpr bool kTable = true;
+    static constexpr int kTableRows = 1;
     struct Args {
         const float* lut;   // device, [K][n]
         int n;              // samples per row
@@ -319,6 +324,78 @@ struct TableBasis {
             const float lo = p[k], diff = p[D + 1 + k] - lo;
             t[k] = fmaf(f, diff, lo);
             if (k >= 1) dt[k - 1] = diff * inv_delta;
+        }
+    }
+};
+
+// DerivTableBasis: the table variant whose derivative comes from a second table (the auxiliary-table
+// option of Sec. 4.2.2, read as samples dLUT[k][i] = T_k'(-1 + i*Delta) interpolated like the
+// values: second order in Delta where the difference quotient of one cell is first order, and
+// continuous across knots).  Both tables are staged into LDS interleaved per sample,
+// [i][0..K) = T_k, [i][K..2K) = T_k', so that the 4K numbers of a cell are adjacent.
+struct DerivTableBasis {
+    static constexpr bool kTable = true;
+    static constexpr int kTableRows = 2;
+    struct Args {
+        const float* lut;    // device, [K][n] values
+        const float* dlut;   // device, [K][n] derivatives
+        int n;               // samples per row
+    };
+    const float* tab;        // LDS, [n][2K]
+    float half;              // (n-1)/2
+    int last;                // n-2
+
+    __device__ DerivTableBasis(const Args& a, float* dst, int K, int tid, int nthreads)
+    {
+        const int total = a.n * K;
+        for (int e = tid; e < total; e += nthreads) {
+            const int k = e / a.n, i = e - k * a.n;
+            dst[i * 2 * K + k] = a.lut[e];
+            dst[i * 2 * K + K + k] = a.dlut[e];
+        }
+        __syncthreads();
+        tab = dst;
+        half = 0.5f * (float)(a.n - 1);
+        last = a.n - 2;
+    }
+    template <int K>
+    __device__ __forceinline__ const float* cell(float u, float& frac) const
+    {
+        const float pos = fmaf(u, half, half);
+        int c = (int)pos;                       // pos >= 0: truncation is the floor
+        c = c < last ? c : last;
+        frac = pos - (float)c;
+        return tab + c * 2 * K;
+    }
+    template <int D>
+    __device__ __forceinline__ void T(float x, float (&out)[D + 1]) const
+    {
+        constexpr int K = D + 1;
+        float f;
+        const float* p = cell<K>(normalise(x), f);
+#pragma unroll
+        for (int k = 0; k < K; ++k) out[k] = fmaf(f, p[2 * K + k] - p[k], p[k]);
+    }
+    template <int D>
+    __device__ __forceinline__ void dT(float x, float (&out)[D > 0 ? D : 1], float& slope) const
+    {
+        constexpr int K = D + 1;
+        float f;
+        const float* p = cell<K>(normalise(x, slope), f);
+#pragma unroll
+        for (int k = 1; k < K; ++k) out[k - 1] = fmaf(f, p[3 * K + k] - p[K + k], p[K + k]);
+    }
+    template <int D>
+    __device__ __forceinline__ void T_dT(float x, float (&t)[D + 1], float (&dt)[D > 0 ? D : 1], float& slope,
+                                         bool) const
+    {
+        constexpr int K = D + 1;
+        float f;
+        const float* p = cell<K>(normalise(x, slope), f);
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            t[k] = fmaf(f, p[2 * K + k] - p[k], p[k]);
+            if (k >= 1) dt[k - 1] = fmaf(f, p[3 * K + k] - p[K + k], p[K + k]);
         }
     }
 };

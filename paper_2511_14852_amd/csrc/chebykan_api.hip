@@ -102,6 +102,14 @@ static void generic_dx_table(const float* x, const float* C, const float* dy, co
     launch<generic_dx_table_kernel>(grid, block, 0, s, x, C, dy, lut, n, dx, B, I, O, d);
 }
 
+static void generic_dx_table2(const float* x, const float* C, const float* dy, const float* dlut, int n, float* dx,
+                              int64_t B, int I, int O, int d, hipStream_t s)
+{
+    const ScopedOps ops(OP_DX);
+    dim3 block(64, 4), grid((unsigned)((B + 3) / 4), (unsigned)((I + 63) / 64));
+    launch<generic_dx_table2_kernel>(grid, block, 0, s, x, C, dy, dlut, n, dx, B, I, O, d);
+}
+
 static void generic_dC_table(const float* x, const float* dy, const float* lut, int n, float* dC, int64_t B, int I,
                              int O, int d, hipStream_t s)
 {
@@ -225,6 +233,56 @@ chebykan_status chebykan_lut_build(float* lut, int degree, int lut_size)
         }
     }
     return CHEBYKAN_OK;
+}
+
+chebykan_status chebykan_lut_build_derivative(float* dlut, int degree, int lut_size)
+{
+    if (!dlut) return CHEBYKAN_ERR_NULL;
+    if (degree < 0 || degree > CHEBYKAN_MAX_DEGREE || lut_size < 2 || lut_size > CHEBYKAN_MAX_LUT_SIZE)
+        return CHEBYKAN_ERR_SHAPE;
+    // Samples of T_k' = k U_{k-1} on the uniform grid: second-kind recurrence in double, rounded once to fp32.
+    const double step = 2.0 / (double)(lut_size - 1);
+    for (int i = 0; i < lut_size; ++i) {
+        const double xi = i == lut_size - 1 ? 1.0 : (double)i * step - 1.0;
+        double second_below = 0.0, second_here = 1.0;   // U_{k-2}, U_{k-1}
+        dlut[i] = 0.0f;
+        for (int k = 1; k <= degree; ++k) {
+            dlut[(size_t)k * lut_size + i] = (float)((double)k * second_here);
+            const double second_above = 2.0 * xi * second_here - second_below;
+            second_below = second_here;
+            second_here = second_above;
+        }
+    }
+    return CHEBYKAN_OK;
+}
+
+chebykan_status chebykan_backward_lut2(const float* x, const float* C, const float* dy, const float* lut,
+                                       const float* dlut, int lut_size, float* dx, float* dC, int64_t batch, int in,
+                                       int out, int degree, void* workspace, size_t workspace_bytes,
+                                       chebykan_stream_t stream)
+{
+    if (!C || !lut || !dlut || (batch != 0 && (!x || !dy))) return CHEBYKAN_ERR_NULL;
+    if (!dx && !dC && batch != 0) return CHEBYKAN_ERR_NULL;
+    if (!shape_ok(batch, in, out, degree) || lut_size < 2 || lut_size > CHEBYKAN_MAX_LUT_SIZE)
+        return CHEBYKAN_ERR_SHAPE;
+    const size_t need = backward_workspace_bytes(batch, in, out, degree);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return CHEBYKAN_ERR_WORKSPACE;
+    const chebykan_status dev = prepare_device();
+    if (dev != CHEBYKAN_OK) return dev;
+    hipStream_t s = (hipStream_t)stream;
+    (void)hipGetLastError();
+    if (kernel_family() != 1 && batch > 0 &&
+        fast_backward_table2(x, C, dy, lut, dlut, lut_size, dx, dC, batch, in, out, degree, workspace, s))
+        return launch_status();
+    // two tables too large for LDS, or a degree without table kernels: each gradient on its own path
+    if (dx && batch > 0) generic_dx_table2(x, C, dy, dlut, lut_size, dx, batch, in, out, degree, s);
+    if (dC) {
+        if (kernel_family() != 1 && batch > 0 &&
+            fast_backward_table(x, C, dy, lut, lut_size, nullptr, dC, batch, in, out, degree, workspace, s))
+            return launch_status();
+        generic_dC_table(x, dy, lut, lut_size, dC, batch, in, out, degree, s);
+    }
+    return launch_status();
 }
 
 chebykan_status chebykan_forward_lut(const float* x, const float* C, const float* lut, int lut_size, float* y,

@@ -11,5 +11,8 @@ template void degree_forward<2, TableBasis>(const float*, const float*, float*, 
                                             const TableBasis::Args&, hipStream_t);
 template void degree_backward<2, TableBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
                                              void*, const TableBasis::Args&, hipStream_t);
+// the same with the auxiliary derivative table (backward only: forward is that of the table variant)
+template void degree_backward<2, DerivTableBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
+                                                  void*, const DerivTableBasis::Args&, hipStream_t);
 template void degree_stack_combine<2>(CombineArgs&, hipStream_t);
 }  // namespace chebykan

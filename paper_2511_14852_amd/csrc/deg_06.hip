@@ -11,6 +11,9 @@ template void degree_forward<6, TableBasis>(const float*, const float*, float*, 
                                             const TableBasis::Args&, hipStream_t);
 template void degree_backward<6, TableBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
                                              void*, const TableBasis::Args&, hipStream_t);
+// the same with the auxiliary derivative table (backward only: forward is that of the table variant)
+template void degree_backward<6, DerivTableBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
+                                                  void*, const DerivTableBasis::Args&, hipStream_t);
 // other bases on the same kernels (paper Sec. 2.3)
 template void degree_forward<6, LegendreBasis>(const float*, const float*, float*, int, int, int, void*,
                                             const LegendreBasis::Args&, hipStream_t);

@@ -21,7 +21,7 @@ constexpr int MAX_LDS_BYTES = 160 * 1024;
 template <class Basis>
 inline size_t basis_lds_bytes(const typename Basis::Args& ba, int K)
 {
-    if constexpr (Basis::kTable) return (size_t)ba.n * K * sizeof(float);
+    if constexpr (Basis::kTable) return (size_t)Basis::kTableRows * ba.n * K * sizeof(float);
     else { (void)ba; (void)K; return 0; }
 }
 
@@ -348,7 +348,12 @@ void degree_backward(const float* x, const float* C, const float* dy, float* dx,
     }
     if (dC) {
         const ScopedOps ops(OP_DC);
-        pick_dC<D, Basis>(x, dy, dC, partial, B, I, O, plan_dC(B, I, O, D), ba, s);
+        if constexpr (std::is_same<Basis, DerivTableBasis>::value) {
+            // the coefficient gradient needs no derivative: the kernels of the plain table variant serve it
+            pick_dC<D, TableBasis>(x, dy, dC, partial, B, I, O, plan_dC(B, I, O, D), TableBasis::Args{ba.lut, ba.n}, s);
+        } else {
+            pick_dC<D, Basis>(x, dy, dC, partial, B, I, O, plan_dC(B, I, O, D), ba, s);
+        }
     }
 }
 

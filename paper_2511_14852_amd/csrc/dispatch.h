@@ -26,6 +26,10 @@ bool fast_forward_table(const float* x, const float* C, const float* lut, int n,
 bool fast_backward_table(const float* x, const float* C, const float* dy, const float* lut, int n, float* dx,
                          float* dC, int64_t B, int I, int O, int d, void* ws, hipStream_t s);
 
+// The same with the auxiliary derivative table dlut ([d+1][n], device): both tables must fit in LDS together.
+bool fast_backward_table2(const float* x, const float* C, const float* dy, const float* lut, const float* dlut, int n,
+                          float* dx, float* dC, int64_t B, int I, int O, int d, void* ws, hipStream_t s);
+
 // Forward of a whole narrow stack in one launch (act[0] input, act[l+1] output of layer l).  False when
 // the stack is not eligible (then nothing is enqueued and the caller runs the layers one by one).
 bool fast_chain_forward(int n_layers, const int* widths, int d, int64_t B, const float* const* C, float* const* act,

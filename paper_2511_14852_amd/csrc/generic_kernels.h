@@ -176,6 +176,34 @@ generic_dx_table_kernel(const float* __restrict__ x, const float* __restrict__ C
     dx[b * I + i] = slope * (total + part);
 }
 
+// dx with the derivative read from the auxiliary table dlut[k][i] = T_k'(-1 + i*Delta), interpolated
+// like the values (the second option of Sec. 4.2.2).
+__global__ void __launch_bounds__(256)
+generic_dx_table2_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
+                         const float* __restrict__ dlut, int n, float* __restrict__ dx, int64_t B, int I, int O,
+                         int degree)
+{
+    const int i = blockIdx.y * 64 + threadIdx.x;
+    const int64_t b = (int64_t)blockIdx.x * 4 + threadIdx.y;
+    if (i >= I || b >= B) return;
+    const int K = degree + 1;
+    float slope, f;
+    const int c = table_cell(normalise(x[b * I + i], slope), n, f);
+    const float* g = dy + b * O;
+    float total = 0.0f, part = 0.0f;
+    for (int o = 0; o < O; ++o) {
+        const float* cf = C + ((int64_t)i * O + o) * K;
+        float inner = 0.0f;
+        for (int k = 1; k < K; ++k) {
+            const float lo = dlut[(int64_t)k * n + c];
+            inner = fmaf(cf[k], fmaf(f, dlut[(int64_t)k * n + c + 1] - lo, lo), inner);
+        }
+        part = fmaf(g[o], inner, part);
+        if ((o % GENERIC_FOLD) == GENERIC_FOLD - 1) { total += part; part = 0.0f; }
+    }
+    dx[b * I + i] = slope * (total + part);
+}
+
 __global__ void __launch_bounds__(256)
 generic_dC_table_kernel(const float* __restrict__ x, const float* __restrict__ dy, const float* __restrict__ lut,
                         int n, float* __restrict__ dC, int64_t B, int I, int O, int degree)

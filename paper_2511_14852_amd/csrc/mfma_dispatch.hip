@@ -34,6 +34,11 @@ CHEBYKAN_FOR_EACH_DEGREE(CHEBYKAN_DECLARE_DEGREE)
                                                         int, int, int, void*, const TableBasis::Args&, hipStream_t);
 CHEBYKAN_FOR_EACH_TABLE_DEGREE(CHEBYKAN_DECLARE_TABLE_DEGREE)
 #undef CHEBYKAN_DECLARE_TABLE_DEGREE
+#define CHEBYKAN_DECLARE_DERIV_TABLE_DEGREE(n)                                                                          \
+    extern template void degree_backward<n, DerivTableBasis>(const float*, const float*, const float*, float*, float*, \
+                                                             int, int, int, void*, const DerivTableBasis::Args&, hipStream_t);
+CHEBYKAN_FOR_EACH_TABLE_DEGREE(CHEBYKAN_DECLARE_DERIV_TABLE_DEGREE)
+#undef CHEBYKAN_DECLARE_DERIV_TABLE_DEGREE
 
 #define CHEBYKAN_DECLARE_FAMILY(n, Basis)                                                                      \
     extern template void degree_forward<n, Basis>(const float*, const float*, float*, int, int, int, void*,   \
@@ -138,6 +143,24 @@ bool fast_backward_table(const float* x, const float* C, const float* dy, const 
     switch (d) {
 #define CHEBYKAN_BACKWARD_CASE(k) \
     case k: degree_backward<k, TableBasis>(x, C, dy, dx, dC, (int)B, I, O, ws, ba, s); return true;
+        CHEBYKAN_FOR_EACH_TABLE_DEGREE(CHEBYKAN_BACKWARD_CASE)
+#undef CHEBYKAN_BACKWARD_CASE
+    }
+    return false;
+}
+
+bool fast_backward_table2(const float* x, const float* C, const float* dy, const float* lut, const float* dlut, int n,
+                          float* dx, float* dC, int64_t B, int I, int O, int d, void* ws, hipStream_t s)
+{
+    // both tables ride along in LDS: twice the bytes of the plain table variant
+    if (!shape_fits(B, I, O, d) || !table_degree_specialised(d) || n < 2 ||
+        2 * (int64_t)n * (d + 1) * (int64_t)sizeof(float) > TABLE_LDS_BYTES)
+        return false;
+    if (backward_workspace_bytes(B, I, O, d) > 0 && !ws) return false;
+    const DerivTableBasis::Args ba{lut, dlut, n};
+    switch (d) {
+#define CHEBYKAN_BACKWARD_CASE(k) \
+    case k: degree_backward<k, DerivTableBasis>(x, C, dy, dx, dC, (int)B, I, O, ws, ba, s); return true;
         CHEBYKAN_FOR_EACH_TABLE_DEGREE(CHEBYKAN_BACKWARD_CASE)
 #undef CHEBYKAN_BACKWARD_CASE
     }

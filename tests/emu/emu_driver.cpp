@@ -3,7 +3,8 @@
 //   emu_driver <dir> <B> <I> <O> <degree> <family> [lut_size [basis]]
 // <dir> holds x.bin, C.bin, dy.bin (and lut.bin when lut_size is given: the table-interpolated
 // entry points are called then; basis 1..3 with lut_size 0 calls the Legendre / Hermite / Fourier entry
-// points); y.bin, dx.bin, dC.bin are written there.
+// points; basis 9 with a lut_size also reads dlut.bin and takes dx from the auxiliary derivative table);
+// y.bin, dx.bin, dC.bin are written there.
 #include <stdio.h>
 #include <stdlib.h>
 #include <math.h>
@@ -56,11 +57,15 @@ int main(int argc, char** argv)
     for (size_t i = 0; i < wn / 4; ++i) ws[i] = NAN;
     std::vector<float> lut;
     if (lut_size > 0) lut = read_bin(dir + "/lut.bin", K * (size_t)lut_size);
+    std::vector<float> dlut;
+    if (lut_size > 0 && basis == 9) dlut = read_bin(dir + "/dlut.bin", K * (size_t)lut_size);
     int rc = lut_size > 0 ? chebykan_forward_lut(x.data(), C.data(), lut.data(), lut_size, y, B, I, O, d, ws, wn, nullptr)
                           : chebykan_forward_basis(basis, x.data(), C.data(), y, B, I, O, d, ws, wn, nullptr);
     if (rc != CHEBYKAN_OK) { fprintf(stderr, "forward: %s\n", chebykan_status_string((chebykan_status)rc)); return 1; }
-    rc = lut_size > 0 ? chebykan_backward_lut(x.data(), C.data(), dy.data(), lut.data(), lut_size, dx, dC, B, I, O, d, ws,
-                                              wn, nullptr)
+    rc = lut_size > 0 ? (basis == 9 ? chebykan_backward_lut2(x.data(), C.data(), dy.data(), lut.data(), dlut.data(), lut_size,
+                                                             dx, dC, B, I, O, d, ws, wn, nullptr)
+                                    : chebykan_backward_lut(x.data(), C.data(), dy.data(), lut.data(), lut_size, dx, dC, B, I,
+                                                            O, d, ws, wn, nullptr))
                       : chebykan_backward_basis(basis, x.data(), C.data(), dy.data(), dx, dC, B, I, O, d, ws, wn, nullptr);
     if (rc != CHEBYKAN_OK) { fprintf(stderr, "backward: %s\n", chebykan_status_string((chebykan_status)rc)); return 1; }
     write_bin(dir + "/y.bin", y, (size_t)B * O);

@@ -58,7 +58,7 @@ def emu_driver():
     return exe
 
 
-def _run(exe, B, I, O, d, family, seed=1, lut_size=0, basis=0, tune=None):
+def _run(exe, B, I, O, d, family, seed=1, lut_size=0, basis=0, tune=None, deriv_table=False):
     x = wl.make_x(B, I, seed)
     C = wl.make_coeff(I, O, d, seed + 1)
     dy = wl.make_dy(B, O, seed + 2)
@@ -72,6 +72,10 @@ def _run(exe, B, I, O, d, family, seed=1, lut_size=0, basis=0, tune=None):
             lut = oracle.lut_build(d, lut_size).astype(np.float32)
             lut.tofile(os.path.join(td, "lut.bin"))
             args.append(str(lut_size))
+            if deriv_table:
+                dlut = oracle.lut_build_derivative(d, lut_size).astype(np.float32)
+                dlut.tofile(os.path.join(td, "dlut.bin"))
+                args.append("9")
         elif basis:
             args += ["0", str(basis)]
         env = dict(os.environ, CHEBYKAN_TEST_HOOKS=str(tune)) if tune is not None else None
@@ -82,6 +86,10 @@ def _run(exe, B, I, O, d, family, seed=1, lut_size=0, basis=0, tune=None):
         dC = np.fromfile(os.path.join(td, "dC.bin"), dtype=np.float32).reshape(I, O, d + 1)
     finally:
         shutil.rmtree(td, ignore_errors=True)
+    if lut_size and deriv_table:
+        _, dC_ref = oracle.backward_lut(x, C, dy, lut, need_dx=False)
+        return (oracle.rel_err(y, oracle.forward_lut(x, C, lut)), oracle.rel_err(dx, oracle.dx_lut2(x, C, dy, dlut)),
+                oracle.rel_err(dC, dC_ref))
     if lut_size:
         _, dC_ref = oracle.backward_lut(x, C, dy, lut, need_dx=False)
         return (oracle.rel_err(y, oracle.forward_lut(x, C, lut)), dx_error(dx, x, C, dy, lut),
@@ -187,6 +195,24 @@ LUT_CASES = [
 def test_table_variant_on_cpu_emulation(emu_driver, case):
     B, I, O, d, n = case
     errs = _run(emu_driver, B, I, O, d, family=2, lut_size=n)
+    assert all(np.isfinite(e) and e <= 1e-5 for e in errs), errs
+
+
+# the same with dx from the auxiliary derivative table (both tables staged in LDS): one case per kernel that
+# evaluates a derivative - both matrix-core dx kernels, the streaming kernel, the few-inputs kernel
+LUT2_CASES = [
+    (140, 40, 72, 6, 129),
+    (129, 5, 257, 8, 33),
+    (300, 64, 1, 6, 65),
+    (200, 8, 64, 6, 65),
+]
+QUICK |= {(140, 40, 72, 6, 129, "d"), (200, 8, 64, 6, 65, "d")}
+
+
+@pytest.mark.parametrize("case", _select([c + ("d",) for c in LUT2_CASES]), ids=lambda c: "B%d_I%d_O%d_d%d_n%d_%s" % c)
+def test_derivative_table_variant_on_cpu_emulation(emu_driver, case):
+    B, I, O, d, n, _ = case
+    errs = _run(emu_driver, B, I, O, d, family=2, lut_size=n, deriv_table=True)
     assert all(np.isfinite(e) and e <= 1e-5 for e in errs), errs
 
 
