@@ -15,7 +15,10 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRCS = [os.path.join(_HERE, "chebykan_oracle.c"), os.path.join(_HERE, "chebykan_lut_oracle.c"),
          os.path.join(_HERE, "kan_bases_oracle.c")]
-_LIB = os.path.join(_HERE, "liboracle.so")
+# CHEBYKAN_ORACLE_SANITIZE=1 builds and loads an AddressSanitizer + UndefinedBehaviorSanitizer build instead
+# (the interpreter must then run with the sanitizer runtime preloaded; tests/test_sanitizers_host.py does that).
+_SANITIZE = os.environ.get("CHEBYKAN_ORACLE_SANITIZE", "0") == "1"
+_LIB = os.path.join(_HERE, "liboracle_san.so" if _SANITIZE else "liboracle.so")
 _lib: Optional[ctypes.CDLL] = None
 
 MAX_DEGREE = 64
@@ -25,7 +28,9 @@ def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (-O2, OpenMP, no fast-math)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(s) for s in _SRCS):
         tmp = _LIB + ".tmp.%d" % os.getpid()
-        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+               "-fno-omit-frame-pointer"] if _SANITIZE else ["-O2"]
+        cmd = ["gcc", *opt, "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
                "-ffp-contract=off", "-o", tmp, *_SRCS, "-lm"]
         subprocess.run(cmd, check=True)
         os.replace(tmp, _LIB)
