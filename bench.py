@@ -9,7 +9,8 @@ Prints ONE JSON line.  The headline workload is the largest configuration
 (c5, one 1024 -> 1024 layer of degree 8 on 16384 rows: the compute-bound case the
 fp32-MFMA target is stated on); `value` is its rows per second, inputs resident
 in HBM.  The tabular stack (c2: the memory-bound target) runs in the same process
-and its full result is nested under `tabular_c2`.
+and its full result is nested under `tabular_c2`; the speech- and audio-shaped stacks
+follow under `speech_c3` and `audio_c4` (without the cold pass and the CPU baseline).
 
 `roofline` describes the dominant kernel OF THE TIMED STEPS: the library brackets
 every kernel it launches with two event records on the launch stream
@@ -49,8 +50,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default=HEADLINE, choices=["c1", "c2", "c3", "c4", "c5", "p1", "p2", "p3"])
     ap.add_argument("--no-tabular", action="store_true",
-                    help="do not run the tabular stack (c2) beside the headline workload")
+                    help="do not run the tabular stack (c2) and the two wide stacks (c3, c4) beside the headline workload")
     ap.add_argument("--tabular-steps", type=int, default=300, help="timed steps of the nested tabular run")
+    ap.add_argument("--stack-steps", type=int, default=40, help="timed steps of the nested speech- and audio-shaped runs")
     ap.add_argument("--rotate", type=int, default=4,
                     help="number of distinct (x, dy) input sets cycled through, so inputs are not cache-resident")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -243,8 +245,10 @@ def summarise_kernels(recs, steps, w, traffic):
     """Per (kernel, grid): launches per step, average duration over the traced steps, algorithmic work, rates."""
     agg = {}
     order = []
-    for name, grid, block, layer, ops, us in recs:
+    shares = {}
+    for name, grid, block, layer, ops, share, us in recs:
         key = (name, "%dx%d" % (grid[0], grid[1]), layer, ops)
+        shares[key] = share
         if key not in agg:
             agg[key] = []
             order.append(key)
@@ -255,6 +259,7 @@ def summarise_kernels(recs, steps, w, traffic):
         name, grid, layer, ops = key
         v = np.array(agg[key])
         fl, by = kernel_work(w, layer, ops)
+        fl, by = int(fl * shares[key]), int(by * shares[key])      # two launches tiling one output range
         avg = float(v.mean())
         row = {"kernel": name, "grid": grid, "layer": layer, "ops": ops, "launches_per_step": len(v) / steps,
                "avg_us": round(avg, 2), "min_us": round(float(v.min()), 2), "share": round(float(v.sum()) / total_us, 4),
@@ -381,8 +386,8 @@ def cpu_baseline(w, wl, target_seconds, lut_size=0, kind=0):
                       "(median of %d passes)" % (rows, w.batch, w.name, dt, threads, len(times))}
 
 
-def run_workload(name, steps, warmup, args, torch, binding, wl):
-    """Everything bench.py measures on one workload, as a dict."""
+def run_workload(name, steps, warmup, args, torch, binding, wl, brief=False):
+    """Everything bench.py measures on one workload, as a dict (brief: no cold pass, no CPU baseline)."""
     w = wl.WORKLOADS[name]
     lut = dlut = None
     if args.basis in ("lut", "lut2"):
@@ -533,9 +538,9 @@ def run_workload(name, steps, warmup, args, torch, binding, wl):
         "event_timed": step_stats,
         "calls": per_call,
     }
-    if not args.no_cold:
+    if not args.no_cold and not brief:
         res["cold"] = cold_pass(st, lambda: Stack(w, 1, torch, binding, wl, lut, kind, dlut), torch)
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not brief:
         res["cpu_baseline"] = cpu_baseline(w, wl, args.cpu_seconds, args.lut_size if lut is not None else 0, kind)
     stream = st.stream
     del st
@@ -576,6 +581,9 @@ def main():
     if args.workload == HEADLINE and not args.no_tabular and args.basis == "exact" and not args.graph:
         sub, _ = run_workload(TABULAR, args.tabular_steps, max(args.warmup, 20), args, torch, binding, wl)
         line["tabular_%s" % TABULAR] = sub
+        for key, name in (("speech_c3", "c3"), ("audio_c4", "c4")):
+            sub, _ = run_workload(name, args.stack_steps, args.warmup, args, torch, binding, wl, brief=True)
+            line[key] = sub
     print(json.dumps(line), flush=True)
 
 

@@ -31,11 +31,14 @@ extern thread_local CombineJob* g_deferred_combine;
 
 // Many slices of a small tensor (coefficient gradients of narrow layers): 32 slice groups.
 // Few slices of a large tensor (split forward): 4 groups, 64 consecutive elements per block.
-inline void launch_sum_slices(const float* partial, float* out, int64_t n, int slices, hipStream_t s)
+// `run` / `stride`: the output as a window of a larger tensor (see sum_slices_kernel); run = 0 means out[e].
+inline void launch_sum_slices(const float* partial, float* out, int64_t n, int slices, hipStream_t s, int64_t run = 0,
+                              int64_t stride = 0)
 {
+    if (run <= 0) { run = n; stride = 0; }
     // few large planes: plain streaming with 16-byte accesses; small sums are latency-bound and keep the
     // many-block form (c4's 16000 x 257 x 2 planes 22 -> 12 us; 16K elements x 4 planes measured 0.4 us slower)
-    if (slices <= 8 && n >= ((int64_t)1 << 20)) {
+    if (slices <= 8 && n >= ((int64_t)1 << 20) && run == n) {
         const dim3 grid((unsigned)((n + 1023) / 1024));
         if (n % 4 == 0 && aligned16(partial) && aligned16(out))
             launch<sum_few_slices_kernel<4>, 0, Tags<Int<4>>>(grid, dim3(256), 0, s, partial, out, n, slices);
@@ -43,10 +46,69 @@ inline void launch_sum_slices(const float* partial, float* out, int64_t n, int s
             launch<sum_few_slices_kernel<1>, 0, Tags<Int<1>>>(grid, dim3(256), 0, s, partial, out, n, slices);
     } else if (slices > 16)
         launch<sum_slices_kernel<32>, 0, Tags<Int<32>>>(dim3((unsigned)((n + 7) / 8)), dim3(256), 32 * 9 * sizeof(float), s, partial, out, n,
-                                      slices);
+                                      slices, run, stride);
     else
         launch<sum_slices_kernel<4>, 0, Tags<Int<4>>>(dim3((unsigned)((n + 63) / 64)), dim3(256), 4 * 65 * sizeof(float), s, partial, out, n,
-                                     slices);
+                                     slices, run, stride);
+}
+
+// ------------------------------------------------------------ narrow layers
+template <int D, int O, class Basis>
+void launch_narrow_fwd(const float* x, const float* C, float* y, int B, int I, const typename Basis::Args& ba, hipStream_t s,
+                       int o_stride, int o_begin)
+{
+    const NarrowPlan p = plan_narrow(B, I, NARROW_FWD_WGS);
+    launch<narrow_fwd_kernel<D, O, Basis>, MAX_LDS_BYTES, Tags<Int<D>, Int<O>, Basis>>(
+        dim3((unsigned)p.slices), dim3(NARROW_THREADS),
+        narrow_fwd_lds_floats(I, O, D + 1) * sizeof(float) + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, y, B, I, p.G,
+        p.rows_per_wg, ba, o_stride, o_begin);
+}
+
+template <int D, int O, class Basis>
+void launch_narrow_bwd(const float* x, const float* C, const float* dy, float* dx, float* dC, float* partial,
+                       int B, int I, const typename Basis::Args& ba, hipStream_t s, int o_stride, int o_begin)
+{
+    const NarrowPlan p = plan_narrow(B, I, NARROW_BWD_WGS);
+    const int blocks_i = (I + p.G - 1) / p.G;
+    launch<narrow_bwd_kernel<D, O, Basis>, MAX_LDS_BYTES, Tags<Int<D>, Int<O>, Basis>>(
+        dim3((unsigned)p.slices, (unsigned)blocks_i), dim3(NARROW_THREADS),
+        narrow_bwd_lds_floats(O, D + 1) * sizeof(float) + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy, dx,
+        dC ? partial : nullptr, B, I, p.G, p.rows_per_wg, ba, o_stride, o_begin);
+    if (dC) {
+        if (g_deferred_combine && o_stride == O)
+            *g_deferred_combine = CombineJob{partial, dC, I, O, p.slices, 1, (int64_t)I * O * (D + 1), 0};
+        else {
+            // the partials are compact [slice][i][o][k]; in a window, dC's runs of O*K values lie o_stride*K apart
+            const ScopedOps ops(OP_DC | OP_SUM);
+            launch_sum_slices(partial, dC + (int64_t)o_begin * (D + 1), (int64_t)I * O * (D + 1), p.slices, s,
+                              (int64_t)O * (D + 1), (int64_t)o_stride * (D + 1));
+        }
+    }
+}
+
+// O columns starting at o_begin of a layer with o_stride outputs (a narrow layer: o_stride = O, o_begin = 0)
+template <int D, class Basis>
+void narrow_fwd_by_out(const float* x, const float* C, float* y, int B, int I, int O, const typename Basis::Args& ba, hipStream_t s,
+                       int o_stride, int o_begin)
+{
+    switch (O) {
+        case 1: launch_narrow_fwd<D, 1, Basis>(x, C, y, B, I, ba, s, o_stride, o_begin); break;
+        case 2: launch_narrow_fwd<D, 2, Basis>(x, C, y, B, I, ba, s, o_stride, o_begin); break;
+        case 3: launch_narrow_fwd<D, 3, Basis>(x, C, y, B, I, ba, s, o_stride, o_begin); break;
+        default: launch_narrow_fwd<D, 4, Basis>(x, C, y, B, I, ba, s, o_stride, o_begin); break;
+    }
+}
+
+template <int D, class Basis>
+void narrow_bwd_by_out(const float* x, const float* C, const float* dy, float* dx, float* dC, float* partial, int B,
+                       int I, int O, const typename Basis::Args& ba, hipStream_t s, int o_stride, int o_begin)
+{
+    switch (O) {
+        case 1: launch_narrow_bwd<D, 1, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s, o_stride, o_begin); break;
+        case 2: launch_narrow_bwd<D, 2, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s, o_stride, o_begin); break;
+        case 3: launch_narrow_bwd<D, 3, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s, o_stride, o_begin); break;
+        default: launch_narrow_bwd<D, 4, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s, o_stride, o_begin); break;
+    }
 }
 
 // ------------------------------------------------------------------ forward
@@ -71,7 +133,7 @@ void pick_fwd(const float* x, const float* C, float* y, float* partial, int B, i
     if (O <= 64) {
         launch_fwd<D, 64, 4, Basis>(x, C, out, B, I, O, 1, 0, p, ba, s);
     } else {
-        const OutTiling t = out_tiling(O);
+        const OutTiling t = out_tiling(I, O, D);
         // batches of at most 64 rows (the paper's operator shapes): waves side by side, no MFMAs on
         // row blocks that are all padding; built for the exact basis at the degrees those shapes use
         constexpr bool small_batch_built = D >= 7 && std::is_same<Basis, ExactBasis>::value;
@@ -80,31 +142,48 @@ void pick_fwd(const float* x, const float* C, float* y, float* partial, int B, i
             if (B <= 32) { launch_fwd<D, 128, 4, Basis, 1>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s); done = true; }
             else if (B <= 64) { launch_fwd<D, 128, 4, Basis, 2>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s); done = true; }
         }
-        if (!done) launch_fwd<D, 128, 4, Basis>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s);
-        if (t.tail_begin >= 0) launch_fwd<D, 64, 4, Basis>(x, C, out, B, I, O, 1, t.tail_begin, p, ba, s);
+        const float wide_share = t.tail_begin >= 0 ? (float)t.tail_begin / (float)O : 1.0f;
+        if (!done) {
+            const ScopedShare share(wide_share);
+            launch_fwd<D, 128, 4, Basis>(x, C, out, B, I, O, t.wide_tiles, 0, p, ba, s);
+        }
+        if (t.tail_kind == 1) {
+            const ScopedShare share(1.0f - wide_share);
+            launch_fwd<D, 64, 4, Basis>(x, C, out, B, I, O, 1, t.tail_begin, p, ba, s);
+        }
     }
     if (p.splits > 1) {
         const ScopedOps ops(OP_FWD | OP_SUM);
         launch_sum_slices(partial, y, (int64_t)B * O, p.splits, s);
     }
+    if (O > 64) {
+        // 1..4 columns beyond the 128-wide tiles: streamed, straight into y (after the plane sum, which
+        // passes over those columns with whatever the planes held there)
+        const OutTiling t = out_tiling(I, O, D);
+        if (t.tail_kind == 2) {
+            const ScopedShare share(1.0f - (float)t.tail_begin / (float)O);
+            narrow_fwd_by_out<D, Basis>(x, C, y, B, I, O - t.tail_begin, ba, s, O, t.tail_begin);
+        }
+    }
 }
 
 // --------------------------------------------------------------------- dC
 template <int D>
-void launch_dC_combine(const float* partial, float* dC, int I, int O, int slices, hipStream_t s)
+void launch_dC_combine(const float* partial, float* dC, int I, int O, int slices, hipStream_t s, int o_count = -1)
 {
     const ScopedOps ops(OP_DC | OP_SUM);
+    if (o_count < 0) o_count = O;      // columns the partials hold (fewer when a streamed tail makes the rest)
     // small sums are latency-bound and gain from sharing one launch; large ones run at once
-    if (g_deferred_combine && (int64_t)((O + 31) / 32) * I <= 512) {
+    if (g_deferred_combine && o_count == O && (int64_t)((O + 31) / 32) * I <= 512) {
         *g_deferred_combine = CombineJob{partial, dC, I, O, slices, 0, 0, 0};
         return;
     }
-    const dim3 grid((unsigned)((O + 31) / 32), (unsigned)I);
+    const dim3 grid((unsigned)((o_count + 31) / 32), (unsigned)I);
     constexpr int lds32 = 1024 * ((D + 1) | 1) * (int)sizeof(float), lds8 = 256 * ((D + 1) | 1) * (int)sizeof(float);
     if (slices > 32)
-        launch<dC_combine_kernel<D, 32>, lds32, Tags<Int<D>, Int<32>>>(grid, dim3(1024), lds32, s, partial, dC, I, O, slices);
+        launch<dC_combine_kernel<D, 32>, lds32, Tags<Int<D>, Int<32>>>(grid, dim3(1024), lds32, s, partial, dC, I, O, o_count, slices);
     else
-        launch<dC_combine_kernel<D, 8>, lds8, Tags<Int<D>, Int<8>>>(grid, dim3(256), lds8, s, partial, dC, I, O, slices);
+        launch<dC_combine_kernel<D, 8>, lds8, Tags<Int<D>, Int<8>>>(grid, dim3(256), lds8, s, partial, dC, I, O, o_count, slices);
 }
 
 template <int D, int BN, int VEC, int BIC, class Basis>
@@ -130,9 +209,16 @@ void pick_dC_tile(const float* x, const float* dy, float* partial, float* direct
     if (p.bn == 64) {
         launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, direct, B, I, O, 1, 0, p, ba, s);
     } else {
-        const OutTiling t = out_tiling(O);
-        launch_dC<D, 128, 4, BIC, Basis>(x, dy, partial, direct, B, I, O, t.wide_tiles, 0, p, ba, s);
-        if (t.tail_begin >= 0) launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, direct, B, I, O, 1, t.tail_begin, p, ba, s);
+        const OutTiling t = out_tiling(I, O, D);
+        const float wide_share = t.tail_begin >= 0 ? (float)t.tail_begin / (float)O : 1.0f;
+        {
+            const ScopedShare share(wide_share);
+            launch_dC<D, 128, 4, BIC, Basis>(x, dy, partial, direct, B, I, O, t.wide_tiles, 0, p, ba, s);
+        }
+        if (t.tail_kind == 1) {
+            const ScopedShare share(1.0f - wide_share);
+            launch_dC<D, 64, 4, BIC, Basis>(x, dy, partial, direct, B, I, O, 1, t.tail_begin, p, ba, s);
+        }
     }
 }
 
@@ -156,7 +242,16 @@ void pick_dC(const float* x, const float* dy, float* dC, float* partial, int B, 
     } else {
         pick_dC_tile<D, dc_tile_features(D), Basis>(x, dy, partial, direct, B, I, O, p, ba, s);
     }
-    if (!direct) launch_dC_combine<D>(partial, dC, I, O, p.slices, s);
+    const OutTiling t = out_tiling(I, O, D);
+    const bool streamed_tail = p.bn == 128 && t.tail_kind == 2;
+    if (!direct) launch_dC_combine<D>(partial, dC, I, O, p.slices, s, streamed_tail ? t.tail_begin : O);
+    if (streamed_tail) {
+        // the 1..4 columns beyond the 128-wide tiles: per-workgroup partials behind those of the tiles, then a sum
+        // into the window of dC
+        const ScopedShare share(1.0f - (float)t.tail_begin / (float)O);
+        float* tail_partial = partial + (size_t)p.slices * I * (D + 1) * O;
+        narrow_bwd_by_out<D, Basis>(x, nullptr, dy, nullptr, dC, tail_partial, B, I, O - t.tail_begin, ba, s, O, t.tail_begin);
+    }
 }
 
 // --------------------------------------------------------------------- dx
@@ -187,19 +282,18 @@ template <int D, class Basis>
 void pick_dx(const float* x, const float* C, const float* dy, float* dx, float* partial, int B, int I, int O,
              const typename Basis::Args& ba, hipStream_t s)
 {
-    const bool vec = aligned16(C) && aligned16(dy) && O % 4 == 0;   // O%4==0 makes every slab run 16-byte aligned
+    // dy rows and coefficient runs are copied with 16-byte loads at any 4-byte aligned address (see pick_fwd)
     const DxPlan p = plan_dx(B, I, O, D);
     bool done = false;
     if constexpr (D <= 6) {   // the feature-per-lane kernel exists for these degrees only
         if (p.per_lane) {
-            if (vec) launch_dx2<D, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s);
-            else launch_dx2<D, 1, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s);
+            launch_dx2<D, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s);
             done = true;
         }
     }
     // batches of at most 64 rows: one column block per wave (see DxCfg); built like the forward variant
     if constexpr (D >= 7 && std::is_same<Basis, ExactBasis>::value) {
-        if (!done && vec && B <= 64) {
+        if (!done && B <= 64) {
             const bool one = B <= 32;
             switch (p.nb) {
                 case 1: one ? launch_dx<D, 1, 4, Basis, 1>(x, C, dy, dx, partial, B, I, O, p, ba, s)
@@ -215,73 +309,16 @@ void pick_dx(const float* x, const float* C, const float* dy, float* dx, float* 
         }
     }
     if (!done) {
-        switch (p.nb * 2 + (vec ? 1 : 0)) {
-            case 2: launch_dx<D, 1, 1, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
-            case 3: launch_dx<D, 1, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
-            case 4: launch_dx<D, 2, 1, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
-            case 5: launch_dx<D, 2, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
-            case 6: launch_dx<D, 3, 1, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
-            case 7: launch_dx<D, 3, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
-            case 8: launch_dx<D, 4, 1, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
+        switch (p.nb) {
+            case 1: launch_dx<D, 1, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
+            case 2: launch_dx<D, 2, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
+            case 3: launch_dx<D, 3, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
             default: launch_dx<D, 4, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s); break;
         }
     }
     if (p.split.splits > 1) {
         const ScopedOps ops(OP_DX | OP_SUM);
         launch_sum_slices(partial, dx, (int64_t)B * I, p.split.splits, s);
-    }
-}
-
-// ------------------------------------------------------------ narrow layers
-template <int D, int O, class Basis>
-void launch_narrow_fwd(const float* x, const float* C, float* y, int B, int I, const typename Basis::Args& ba, hipStream_t s)
-{
-    const NarrowPlan p = plan_narrow(B, I, NARROW_FWD_WGS);
-    launch<narrow_fwd_kernel<D, O, Basis>, MAX_LDS_BYTES, Tags<Int<D>, Int<O>, Basis>>(
-        dim3((unsigned)p.slices), dim3(NARROW_THREADS),
-        narrow_fwd_lds_floats(I, O, D + 1) * sizeof(float) + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, y, B, I, p.G,
-        p.rows_per_wg, ba);
-}
-
-template <int D, int O, class Basis>
-void launch_narrow_bwd(const float* x, const float* C, const float* dy, float* dx, float* dC, float* partial,
-                       int B, int I, const typename Basis::Args& ba, hipStream_t s)
-{
-    const NarrowPlan p = plan_narrow(B, I, NARROW_BWD_WGS);
-    const int blocks_i = (I + p.G - 1) / p.G;
-    launch<narrow_bwd_kernel<D, O, Basis>, MAX_LDS_BYTES, Tags<Int<D>, Int<O>, Basis>>(
-        dim3((unsigned)p.slices, (unsigned)blocks_i), dim3(NARROW_THREADS),
-        narrow_bwd_lds_floats(O, D + 1) * sizeof(float) + basis_lds_bytes<Basis>(ba, D + 1), s, x, C, dy, dx,
-        dC ? partial : nullptr, B, I, p.G, p.rows_per_wg, ba);
-    if (dC) {
-        if (g_deferred_combine) *g_deferred_combine = CombineJob{partial, dC, I, O, p.slices, 1, (int64_t)I * O * (D + 1), 0};
-        else {
-            const ScopedOps ops(OP_DC | OP_SUM);
-            launch_sum_slices(partial, dC, (int64_t)I * O * (D + 1), p.slices, s);
-        }
-    }
-}
-
-template <int D, class Basis>
-void narrow_fwd_by_out(const float* x, const float* C, float* y, int B, int I, int O, const typename Basis::Args& ba, hipStream_t s)
-{
-    switch (O) {
-        case 1: launch_narrow_fwd<D, 1, Basis>(x, C, y, B, I, ba, s); break;
-        case 2: launch_narrow_fwd<D, 2, Basis>(x, C, y, B, I, ba, s); break;
-        case 3: launch_narrow_fwd<D, 3, Basis>(x, C, y, B, I, ba, s); break;
-        default: launch_narrow_fwd<D, 4, Basis>(x, C, y, B, I, ba, s); break;
-    }
-}
-
-template <int D, class Basis>
-void narrow_bwd_by_out(const float* x, const float* C, const float* dy, float* dx, float* dC, float* partial, int B,
-                       int I, int O, const typename Basis::Args& ba, hipStream_t s)
-{
-    switch (O) {
-        case 1: launch_narrow_bwd<D, 1, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s); break;
-        case 2: launch_narrow_bwd<D, 2, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s); break;
-        case 3: launch_narrow_bwd<D, 3, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s); break;
-        default: launch_narrow_bwd<D, 4, Basis>(x, C, dy, dx, dC, partial, B, I, ba, s); break;
     }
 }
 
@@ -319,7 +356,7 @@ template <int D, class Basis>
 void degree_forward(const float* x, const float* C, float* y, int B, int I, int O, void* ws, const typename Basis::Args& ba, hipStream_t s)
 {
     const ScopedOps ops(OP_FWD);
-    if (use_narrow(B, I, O, D)) narrow_fwd_by_out<D, Basis>(x, C, y, B, I, O, ba, s);
+    if (use_narrow(B, I, O, D)) narrow_fwd_by_out<D, Basis>(x, C, y, B, I, O, ba, s, O, 0);
     else pick_fwd<D, Basis>(x, C, y, static_cast<float*>(ws), B, I, O, ba, s);
 }
 
@@ -330,7 +367,7 @@ void degree_backward(const float* x, const float* C, const float* dy, float* dx,
     float* partial = static_cast<float*>(ws);
     const ScopedOps both((dx ? OP_DX : 0) | (dC ? OP_DC : 0));
     if (use_narrow(B, I, O, D)) {
-        narrow_bwd_by_out<D, Basis>(x, C, dy, dx, dC, partial, B, I, O, ba, s);
+        narrow_bwd_by_out<D, Basis>(x, C, dy, dx, dC, partial, B, I, O, ba, s, O, 0);
         return;
     }
     if (dx && dC && use_narrow_in(B, I, O, D)) {   // few inputs, both gradients wanted: one kernel for both

@@ -38,12 +38,18 @@ enum : int { OP_FWD = 1, OP_DX = 2, OP_DC = 4, OP_SUM = 8 };
 struct LaunchContext {
     int layer;
     int ops;
+    float share;   // part of that work this launch does (an output range tiled by two launches), 1 by default
 };
 extern thread_local LaunchContext g_launch_context;
 struct ScopedOps {
     int saved;
     explicit ScopedOps(int ops) : saved(g_launch_context.ops) { g_launch_context.ops = ops; }
     ~ScopedOps() { g_launch_context.ops = saved; }
+};
+struct ScopedShare {
+    float saved;
+    explicit ScopedShare(float share) : saved(g_launch_context.share) { g_launch_context.share = share; }
+    ~ScopedShare() { g_launch_context.share = saved; }
 };
 struct ScopedLayer {
     int saved;

@@ -79,7 +79,10 @@ size_t backward_workspace_bytes(int64_t B, int I, int O, int d)
     if (B <= 0 || !shape_fits(B, I, O, d)) return 0;
     const size_t coeffs = (size_t)I * (size_t)(d + 1) * (size_t)O * sizeof(float);
     if (use_narrow(B, I, O, d)) return (size_t)plan_narrow(B, I, NARROW_BWD_WGS).slices * coeffs;
-    const size_t for_dC = (size_t)plan_dC(B, I, O, d).slices * coeffs;
+    size_t for_dC = (size_t)plan_dC(B, I, O, d).slices * coeffs;
+    const OutTiling ot = out_tiling(I, O, d);
+    if (O > 64 && ot.tail_kind == 2)   // partials of the streamed tail columns lie behind those of the tiles
+        for_dC += (size_t)plan_narrow(B, I, NARROW_BWD_WGS).slices * (size_t)I * (size_t)(O - ot.tail_begin) * (size_t)(d + 1) * sizeof(float);
     const DxPlan dxp = plan_dx(B, I, O, d);
     const size_t for_dx = dxp.split.splits > 1 ? (size_t)dxp.split.splits * (size_t)B * (size_t)I * sizeof(float) : 0;
     size_t need = for_dC > for_dx ? for_dC : for_dx;   // used one after the other on the same stream

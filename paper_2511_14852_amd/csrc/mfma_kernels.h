@@ -557,10 +557,11 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
 // rows of the partials into the caller's [i][o][k] layout through LDS, so that reads and
 // writes are both unit-stride.  block = G slice groups x 32 outputs; grid = (ceil(O/32), I).
 // G = 32 (1024 threads) shortens the serial chain per thread when there are many slices.
-// Dynamic LDS: G * 32 * ((D+1)|1) floats.
+// Only the first o_count columns are summed and written (the rest of a row may belong to a tail
+// that other kernels produce).  Dynamic LDS: G * 32 * ((D+1)|1) floats.
 template <int D, int G>
 __device__ __forceinline__ void dC_combine_body(const float* __restrict__ partial, float* __restrict__ dC, int I, int O,
-                                                int n_slices, int block_x, int block_y, float* lds)
+                                                int o_count, int n_slices, int block_x, int block_y, float* lds)
 {
     constexpr int K = D + 1, KP = K | 1;
     const int t = threadIdx.x;
@@ -573,7 +574,7 @@ __device__ __forceinline__ void dC_combine_body(const float* __restrict__ partia
     float v[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) v[k] = 0.0f;
-    if (o < O) {
+    if (o < o_count) {
         const float* p = partial + (int64_t)sg * slice_stride + (int64_t)i * K * O + o;
         int s = sg;
         // two slices per trip: both sets of loads are issued before either is added
@@ -592,7 +593,7 @@ __device__ __forceinline__ void dC_combine_body(const float* __restrict__ partia
 #pragma unroll
     for (int k = 0; k < K; ++k) lds[(sg * 32 + ol) * KP + k] = v[k];
     __syncthreads();
-    const int n_valid = (O - oc < 32 ? O - oc : 32) * K;
+    const int n_valid = (o_count - oc < 32 ? o_count - oc : 32) * K;
     float* dst = dC + ((int64_t)i * O + oc) * K;
     for (int e = t; e < n_valid; e += G * 32) {
         const int o2 = e / K, k = e % K;
@@ -605,10 +606,10 @@ __device__ __forceinline__ void dC_combine_body(const float* __restrict__ partia
 
 template <int D, int G>
 __global__ void __launch_bounds__(G * 32)
-dC_combine_kernel(const float* __restrict__ partial, float* __restrict__ dC, int I, int O, int n_slices)
+dC_combine_kernel(const float* __restrict__ partial, float* __restrict__ dC, int I, int O, int o_count, int n_slices)
 {
     extern __shared__ __align__(16) float lds[];
-    dC_combine_body<D, G>(partial, dC, I, O, n_slices, blockIdx.x, blockIdx.y, lds);
+    dC_combine_body<D, G>(partial, dC, I, O, o_count, n_slices, blockIdx.x, blockIdx.y, lds);
 }
 
 // Every slice sum of a stack's backward pass in ONE launch (the per-layer sums are tiny,
@@ -642,7 +643,7 @@ __global__ void __launch_bounds__(1024) stack_combine_kernel(CombineArgs a)
     const int b = blockIdx.x - j.first_block;
     if (j.kind == 0) {
         const int gx = (j.O + 31) / 32;
-        dC_combine_body<D, 32>(j.partial, j.out, j.I, j.O, j.slices, b % gx, b / gx, lds);
+        dC_combine_body<D, 32>(j.partial, j.out, j.I, j.O, j.O, j.slices, b % gx, b / gx, lds);
     } else {
         // 32 slice groups x 32 elements; groups add every 32nd slice, then the group sums in order
         const int el = threadIdx.x & 31, sg = threadIdx.x >> 5;
@@ -743,9 +744,10 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
             const bool ok = oc + kk < O;
             const uint32_t off = (uint32_t)m * (uint32_t)O + (uint32_t)(oc + kk);
             if constexpr (VEC == 4) {
+                // any 4-byte aligned position: a vector may run past the end of its row, element by element
                 const bufx4 v = load4(gv, off);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) areg[j * 4 + q] = ok ? v[q] : 0.0f;
+                for (int q = 0; q < 4; ++q) areg[j * 4 + q] = oc + kk + q < O ? v[q] : 0.0f;
             } else {
                 const float v = load1(gv, off);
                 areg[j] = ok ? v : 0.0f;
@@ -987,9 +989,10 @@ dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const 
             const bool ok = oc + kk < O;
             const uint32_t off = ga_off + (uint32_t)(oc + j * 2 * VEC);
             if constexpr (VEC == 4) {
+                // any 4-byte aligned position: a vector may run past the end of its row, element by element
                 const bufx4 v = load4(gv, off);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) areg[j * 4 + q] = ok ? v[q] : 0.0f;
+                for (int q = 0; q < 4; ++q) areg[j * 4 + q] = oc + kk + q < O ? v[q] : 0.0f;
             } else {
                 const float v = load1(gv, off);
                 areg[j] = ok ? v : 0.0f;

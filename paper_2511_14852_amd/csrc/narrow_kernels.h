@@ -67,12 +67,17 @@ __device__ __forceinline__ float group_sum(float v, int G)
 __host__ __device__ constexpr size_t narrow_fwd_lds_floats(int I, int O, int K) { return ((size_t)I * O * K + 3) & ~(size_t)3; }
 __host__ __device__ constexpr size_t narrow_bwd_lds_floats(int O, int K) { return (size_t)NARROW_THREADS * O * K; }
 
+// Both kernels work on a window of O columns of a wider layer: the layer has o_stride outputs
+// (row stride of y and dy, output stride of C) and the window starts at column o_begin.  A narrow
+// layer is its own window (o_stride = O, o_begin = 0); the 1..4 columns a wide layer has beyond a
+// multiple of 128 are a window at its right edge.
+
 // grid.x workgroups.  Dynamic LDS: I*O*(D+1) floats, coefficients as [k][o][i].
 // The x values of the next step are requested before the current step is computed.
 template <int D, int O, class Basis = ExactBasis>
 __global__ void __launch_bounds__(NARROW_THREADS)
 narrow_fwd_kernel(const float* __restrict__ x, const float* __restrict__ C, float* __restrict__ y,
-                  int B, int I, int G, int rows_per_wg, typename Basis::Args bargs)
+                  int B, int I, int G, int rows_per_wg, typename Basis::Args bargs, int o_stride, int o_begin)
 {
     constexpr int K = D + 1, RB = NARROW_RB;
     extern __shared__ __align__(16) float lds[];
@@ -97,9 +102,10 @@ narrow_fwd_kernel(const float* __restrict__ x, const float* __restrict__ C, floa
 
     float xnext[RB];
     load_item(0, xnext);
-    for (int e = t; e < I * O * K; e += NARROW_THREADS) {
-        const int k = e % K, o = (e / K) % O, i = e / (K * O);
-        lds[(k * O + o) * I + i] = C[e];
+    // consecutive threads fill consecutive LDS words (no bank conflicts); the strided gather from C is tiny
+    for (int f = t; f < I * O * K; f += NARROW_THREADS) {
+        const int i = f % I, ko = f / I;
+        lds[f] = C[((int64_t)i * o_stride + o_begin + ko % O) * K + ko / O];
     }
     __syncthreads();
 
@@ -143,7 +149,7 @@ narrow_fwd_kernel(const float* __restrict__ x, const float* __restrict__ C, floa
 #pragma unroll
                 for (int o = 0; o < O; ++o) {
                     const float s = group_sum(part[r][o], G);
-                    if (g == G - 1 && row0 + r < last) y[(row0 + r) * O + o] = s;
+                    if (g == G - 1 && row0 + r < last) y[(row0 + r) * o_stride + o_begin + o] = s;
                 }
         }
     }
@@ -155,7 +161,7 @@ template <int D, int O, class Basis = ExactBasis>
 __global__ void __launch_bounds__(NARROW_THREADS)
 narrow_bwd_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
                   float* __restrict__ dx, float* __restrict__ partial, int B, int I, int G, int rows_per_wg,
-                  typename Basis::Args bargs)
+                  typename Basis::Args bargs, int o_stride, int o_begin)
 {
     constexpr int K = D + 1, RB = NARROW_RB;
     extern __shared__ __align__(16) float lds[];
@@ -176,7 +182,7 @@ narrow_bwd_kernel(const float* __restrict__ x, const float* __restrict__ C, cons
             const bool ok = row0 + r < last;
             xv[r] = (ok && i_ok) ? x[(row0 + r) * I + i] : 0.0f;
 #pragma unroll
-            for (int o = 0; o < O; ++o) gv[r][o] = ok ? dy[(row0 + r) * O + o] : 0.0f;   // zero rows add nothing
+            for (int o = 0; o < O; ++o) gv[r][o] = ok ? dy[(row0 + r) * o_stride + o_begin + o] : 0.0f;   // zero rows add nothing
         }
     };
 
@@ -190,7 +196,7 @@ narrow_bwd_kernel(const float* __restrict__ x, const float* __restrict__ C, cons
 #pragma unroll
         for (int k = 0; k < K; ++k) acc[o][k] = 0.0f;
 #pragma unroll
-        for (int k = 1; k < K; ++k) creg[o][k - 1] = (i_ok && dx) ? C[((int64_t)i * O + o) * K + k] : 0.0f;
+        for (int k = 1; k < K; ++k) creg[o][k - 1] = (i_ok && dx) ? C[((int64_t)i * o_stride + o_begin + o) * K + k] : 0.0f;
     }
 
     for (int it = 0; it < n_iter; ++it) {
@@ -254,9 +260,12 @@ narrow_bwd_kernel(const float* __restrict__ x, const float* __restrict__ C, cons
 // every GROUPS-th slice each, then the group sums are added in group order.
 // block = 256 threads = GROUPS slice groups x 256/GROUPS elements; grid.x = ceil(n/(256/GROUPS)).
 // Dynamic LDS: GROUPS x (256/GROUPS + 1) floats.
+// The output may be a window of a larger tensor: element e goes to out[(e / run) * stride + e % run]
+// (runs of `run` consecutive elements, `stride` apart); run = n writes out[e].
 template <int GROUPS>
 __global__ void __launch_bounds__(256)
-sum_slices_kernel(const float* __restrict__ partial, float* __restrict__ out, int64_t n, int n_slices)
+sum_slices_kernel(const float* __restrict__ partial, float* __restrict__ out, int64_t n, int n_slices, int64_t run,
+                  int64_t stride)
 {
     constexpr int EL = 256 / GROUPS;
     extern __shared__ __align__(16) float lds[];
@@ -280,7 +289,7 @@ sum_slices_kernel(const float* __restrict__ partial, float* __restrict__ out, in
         float total = 0.0f;
 #pragma unroll
         for (int q = 0; q < GROUPS; ++q) total += lds[q * (EL + 1) + el];
-        out[e] = total;
+        out[(e / run) * stride + e % run] = total;
     }
 }
 

@@ -88,18 +88,23 @@ inline NarrowInPlan plan_narrow_in(int64_t B)
     return p;
 }
 
-// Output tiling: 128-wide tiles, except that a remainder of 1..64 columns beyond a multiple of 128
-// gets one 64-wide tile from a second launch (257 outputs: 2 x 128 + 64 computed columns
-// instead of 3 x 128).
+// Output tiling: 128-wide tiles, except that a remainder beyond a multiple of 128 is handled apart.
+// 1..4 left-over columns (257 outputs) go to the streaming kernels of narrow_kernels.h, which cost
+// about a tenth of a 64-wide matrix-core tile that would compute 60 unused columns; 5..64 columns
+// get one 64-wide tile from a second launch (2 x 128 + 64 computed columns instead of 3 x 128).
+constexpr int NARROW_MAX_OUT = 4;
 struct OutTiling {
     int wide_tiles;    // 128-wide tiles from column 0
-    int tail_begin;    // first column of the 64-wide tail tile, or -1
+    int tail_begin;    // first column of the tail, or -1
+    int tail_kind;     // 0 none, 1 one 64-wide matrix-core tile, 2 streaming kernels
 };
-inline OutTiling out_tiling(int O)
+inline OutTiling out_tiling(int I, int O, int d)
 {
     const int rem = O % 128;
-    if (O > 128 && rem >= 1 && rem <= 64) return OutTiling{O / 128, (O / 128) * 128};
-    return OutTiling{(O + 127) / 128, -1};
+    if (O > 128 && rem >= 1 && rem <= NARROW_MAX_OUT && (int64_t)I * rem * (d + 1) <= 16384)
+        return OutTiling{O / 128, (O / 128) * 128, 2};
+    if (O > 128 && rem >= 1 && rem <= 64) return OutTiling{O / 128, (O / 128) * 128, 1};
+    return OutTiling{(O + 127) / 128, -1, 0};
 }
 
 // Time of one launch of `wg` equal workgroups, in units of one workgroup's run time when two share
@@ -141,9 +146,10 @@ inline DcPlan plan_dC(int64_t B, int I, int O, int d)
     p.bn = O <= 64 ? 64 : 128;
     const int bic = dc_tile_features_for(I, d);
     const int64_t tiles_i = (I + bic - 1) / bic;
-    const int64_t tiles = tiles_i * ((O + p.bn - 1) / p.bn);
-    const OutTiling ot = out_tiling(O);
-    const bool mixed = p.bn == 128 && ot.tail_begin >= 0;
+    const OutTiling ot = out_tiling(I, O, d);
+    // a streamed tail is no tile of the matrix-core launch
+    const int64_t tiles = tiles_i * (p.bn == 128 && ot.tail_kind == 2 ? ot.wide_tiles : (O + p.bn - 1) / p.bn);
+    const bool mixed = p.bn == 128 && ot.tail_kind == 1;
     // at least 256 rows per slice; a small batch with few tiles may go down to one 32-row chunk per
     // workgroup, which shortens the serial chain of chunks when only a handful of workgroups exist
     const int64_t min_rows = (tiles < 64 && B < 4096 && !(test_hooks() & TEST_DC_MIN_256_ROWS)) ? 32 : 256;
@@ -228,7 +234,6 @@ inline bool shape_fits(int64_t B, int I, int O, int d)
 }
 
 // ------------------------------------------------------------ narrow layers
-constexpr int NARROW_MAX_OUT = 4;
 constexpr int NARROW_THREADS = 256;
 constexpr int NARROW_RB = 8;   // consecutive rows per lane group and step (memory-level parallelism)
 constexpr int NARROW_FWD_WGS = 2048, NARROW_BWD_WGS = 512;
@@ -281,15 +286,16 @@ inline FwdPlan plan_forward(int64_t B, int I, int O, int d)
         // Enough tiles, but with a tail tile they come as two launches that may each leave compute
         // units idle (257 outputs at 16000 rows: 250 + 125 workgroups).  Estimated time per range
         // count, in microseconds: both launches, plus writing and summing the partial planes.
-        const OutTiling ot = out_tiling(O);
+        const OutTiling ot = out_tiling(I, O, d);
         const int64_t row_tiles = (B + 127) / 128;
         if (O <= 128 || ot.tail_begin < 0 || row_tiles * ot.wide_tiles >= 384) return p;
+        const double tail_tile = ot.tail_kind == 1 ? 0.5 : 0.0;   // a streamed tail is one short launch of its own
         const double t_chunk = 0.1333 * bi * (d + 1);
         int best = 1;
         double best_us = 0.0;
         for (int sp = 1; sp <= 4 && sp <= n_chunks / 2; ++sp) {
             const int len = (n_chunks + sp - 1) / sp;
-            double us = t_chunk * len * (launch_rounds(row_tiles * ot.wide_tiles * sp) + 0.5 * launch_rounds(row_tiles * sp));
+            double us = t_chunk * len * (launch_rounds(row_tiles * ot.wide_tiles * sp) + tail_tile * launch_rounds(row_tiles * sp));
             if (sp > 1) us += 6.0 + (2.0 * sp + 1.0) * (double)B * O * 4.0 / 3.0e6;
             if (sp == 1 || us < best_us * 0.97) { best_us = us; best = sp; }
         }

@@ -34,10 +34,12 @@ static int64_t pick(int64_t lo, int64_t hi) { return lo + (int64_t)(next_u64() %
 static void check_shape(int64_t B, int I, int O, int d)
 {
     const int K = d + 1;
-    const OutTiling ot = out_tiling(O);
+    const OutTiling ot = out_tiling(I, O, d);
     CHECK(ot.wide_tiles >= 0 && (ot.tail_begin < 0 || (ot.tail_begin % 128 == 0 && O - ot.tail_begin >= 1 && O - ot.tail_begin <= 64)),
           "O=%d", O);
-    CHECK((int64_t)ot.wide_tiles * 128 + (ot.tail_begin >= 0 ? 64 : 0) >= O, "O=%d", O);
+    CHECK((ot.tail_kind == 0) == (ot.tail_begin < 0), "O=%d kind=%d", O, ot.tail_kind);
+    CHECK(ot.tail_kind != 2 || (O - ot.tail_begin <= NARROW_MAX_OUT && (int64_t)I * (O - ot.tail_begin) * K <= 16384), "O=%d I=%d", O, I);
+    CHECK((int64_t)ot.wide_tiles * 128 + (ot.tail_kind == 1 ? 64 : ot.tail_kind == 2 ? O - ot.tail_begin : 0) >= O, "O=%d", O);
 
     const DcPlan dc = plan_dC(B, I, O, d);
     CHECK(dc.bn == 64 || dc.bn == 128, "bn=%d", dc.bn);

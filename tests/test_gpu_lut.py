@@ -107,6 +107,7 @@ SHAPES = [
     (1200, 70, 40, 8, 1025),
     (129, 7, 520, 8, 1025),
     (140, 21, 64, 3, 2),
+    (700, 40, 130, 5, 513),     # two columns beyond the 128-wide tile: the streamed tail, table staged there too
 ]
 
 
@@ -203,6 +204,7 @@ SHAPES2 = [
     (100, 20, 2, 3, 129),
     (129, 7, 520, 8, 1025),
     (140, 21, 64, 3, 2),
+    (700, 40, 130, 5, 513),
 ]
 
 

@@ -95,6 +95,13 @@ SMALL_SHAPES = [
     (260, 12, 48, 5),
     (129, 7, 520, 8),      # contraction over more than 512 outputs (accumulator fold in dx)
     (1200, 70, 40, 8),     # more than 512 rows per batch slice and more than 14 feature chunks (folds in dC, forward)
+    # 1..4 columns beyond a multiple of 128: the streamed tail (forward into y, coefficient gradient through its own
+    # partials into a window of dC), with one and with several batch slices, beside the 64-wide tail tile (5 columns)
+    (700, 40, 130, 5),
+    (300, 24, 259, 4),
+    (2200, 64, 132, 8),
+    (900, 70, 257, 3),
+    (520, 48, 133, 6),
     # narrow outputs with every lane-group width and several feature groups
     (333, 8, 1, 6),
     (100, 20, 2, 3),
