@@ -246,9 +246,9 @@ def summarise_kernels(recs, steps, w, traffic):
     agg = {}
     order = []
     shares = {}
-    for name, grid, block, layer, ops, share, us in recs:
+    for name, grid, block, layer, ops, share, layer2, ops2, us in recs:
         key = (name, "%dx%d" % (grid[0], grid[1]), layer, ops)
-        shares[key] = share
+        shares[key] = (share, layer2, ops2)
         if key not in agg:
             agg[key] = []
             order.append(key)
@@ -258,8 +258,12 @@ def summarise_kernels(recs, steps, w, traffic):
     for key in order:
         name, grid, layer, ops = key
         v = np.array(agg[key])
+        share, layer2, ops2 = shares[key]
         fl, by = kernel_work(w, layer, ops)
-        fl, by = int(fl * shares[key]), int(by * shares[key])      # two launches tiling one output range
+        fl, by = int(fl * share), int(by * share)                  # two launches tiling one output range
+        if ops2:                                                   # a launch that holds two operations
+            fl2, by2 = kernel_work(w, layer2, ops2)
+            fl, by = fl + fl2, by + by2
         avg = float(v.mean())
         row = {"kernel": name, "grid": grid, "layer": layer, "ops": ops, "launches_per_step": len(v) / steps,
                "avg_us": round(avg, 2), "min_us": round(float(v.min()), 2), "share": round(float(v.sum()) / total_us, 4),

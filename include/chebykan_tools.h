@@ -48,7 +48,8 @@ chebykan_status chebykan_calibrate_copy(float *dst, const float *src, int64_t n,
  * thread), its grid and block size, what it computes - `layer`: the layer of a stack call it
  * belongs to (0 for single-layer calls, -1 for a kernel that covers every layer of the stack),
  * `ops`: CHEBYKAN_OP_* bits, `share`: the part of that work this launch does (below 1 when two
- * launches tile one output range) - and the time between its two events in microseconds.
+ * launches tile one output range), `layer2` / `ops2`: the same for a second operation when the
+ * launch holds two (ops2 = 0 otherwise) - and the time between its two events in microseconds.
  *
  * chebykan_trace_begin creates 2*max_kernels events (the only calls here that allocate); launches
  * beyond max_kernels are not timed and are counted in *dropped by chebykan_trace_end, which
@@ -65,7 +66,8 @@ chebykan_status chebykan_calibrate_copy(float *dst, const float *src, int64_t n,
 chebykan_status chebykan_trace_begin(int max_kernels);
 int chebykan_trace_end(int *dropped);
 chebykan_status chebykan_trace_get(int index, const char **name, unsigned grid[3], unsigned *block,
-                                   int *layer, int *ops, float *share, float *microseconds);
+                                   int *layer, int *ops, float *share, int *layer2, int *ops2,
+                                   float *microseconds);
 void chebykan_trace_free(void);
 
 #ifdef __cplusplus

@@ -103,7 +103,8 @@ def load() -> ctypes.CDLL:
         lib.chebykan_trace_end.restype = ci
         lib.chebykan_trace_get.argtypes = [ci, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_uint * 3),
                                            ctypes.POINTER(ctypes.c_uint), ctypes.POINTER(ci), ctypes.POINTER(ci),
-                                           ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
+                                           ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ci), ctypes.POINTER(ci),
+                                           ctypes.POINTER(ctypes.c_float)]
         lib.chebykan_trace_get.restype = ci
         lib.chebykan_trace_free.argtypes = []
         lib.chebykan_trace_free.restype = None
@@ -162,19 +163,23 @@ def chebykan_trace_end():
 
 
 def chebykan_trace_records(count: int):
-    """(kernel name, grid (x, y, z), block threads, layer, OP_* bits, share of that work, microseconds) per
-    timed launch, in launch order.  The streams the launches went to must have been synchronised."""
+    """(kernel name, grid (x, y, z), block threads, layer, OP_* bits, share of that work, second layer, second
+    OP_* bits, microseconds) per timed launch, in launch order.  The streams the launches went to must have been
+    synchronised."""
     lib = load()
     out = []
     name, grid, block, us = ctypes.c_char_p(), (ctypes.c_uint * 3)(), ctypes.c_uint(0), ctypes.c_float(0.0)
     layer, ops, share = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_float(1.0)
+    layer2, ops2 = ctypes.c_int(0), ctypes.c_int(0)
     for i in range(count):
         st = int(lib.chebykan_trace_get(i, ctypes.byref(name), ctypes.byref(grid), ctypes.byref(block),
-                                        ctypes.byref(layer), ctypes.byref(ops), ctypes.byref(share), ctypes.byref(us)))
+                                        ctypes.byref(layer), ctypes.byref(ops), ctypes.byref(share), ctypes.byref(layer2),
+                                        ctypes.byref(ops2), ctypes.byref(us)))
         if st != CHEBYKAN_OK:
             raise ChebykanError(st, "chebykan_trace_get")
         out.append((name.value.decode(), (int(grid[0]), int(grid[1]), int(grid[2])), int(block.value),
-                    int(layer.value), int(ops.value), float(share.value), float(us.value)))
+                    int(layer.value), int(ops.value), float(share.value), int(layer2.value), int(ops2.value),
+                    float(us.value)))
     return out
 
 

@@ -15,4 +15,5 @@ template void degree_backward<2, TableBasis>(const float*, const float*, const f
 template void degree_backward<2, DerivTableBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
                                                   void*, const DerivTableBasis::Args&, hipStream_t);
 template void degree_stack_combine<2>(CombineArgs&, hipStream_t);
+template void degree_pair_backward<2>(const PairArgs&, CombineJob*, hipStream_t);
 }  // namespace chebykan

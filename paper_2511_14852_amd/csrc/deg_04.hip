@@ -30,4 +30,5 @@ template void degree_backward<4, FourierBasis>(const float*, const float*, const
 // forward of a narrow stack in one launch
 template void degree_chain_forward<4>(const ChainArgs&, int, hipStream_t);
 template void degree_stack_combine<4>(CombineArgs&, hipStream_t);
+template void degree_pair_backward<4>(const PairArgs&, CombineJob*, hipStream_t);
 }  // namespace chebykan

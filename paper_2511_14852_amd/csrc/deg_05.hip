@@ -26,4 +26,5 @@ template void degree_backward<5, HermiteBasis>(const float*, const float*, const
 // forward of a narrow stack in one launch
 template void degree_chain_forward<5>(const ChainArgs&, int, hipStream_t);
 template void degree_stack_combine<5>(CombineArgs&, hipStream_t);
+template void degree_pair_backward<5>(const PairArgs&, CombineJob*, hipStream_t);
 }  // namespace chebykan

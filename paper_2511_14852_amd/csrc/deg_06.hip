@@ -30,4 +30,5 @@ template void degree_backward<6, FourierBasis>(const float*, const float*, const
 // forward of a narrow stack in one launch
 template void degree_chain_forward<6>(const ChainArgs&, int, hipStream_t);
 template void degree_stack_combine<6>(CombineArgs&, hipStream_t);
+template void degree_pair_backward<6>(const PairArgs&, CombineJob*, hipStream_t);
 }  // namespace chebykan

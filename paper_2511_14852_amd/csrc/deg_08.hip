@@ -28,4 +28,5 @@ template void degree_forward<8, FourierBasis>(const float*, const float*, float*
 template void degree_backward<8, FourierBasis>(const float*, const float*, const float*, float*, float*, int, int, int,
                                              void*, const FourierBasis::Args&, hipStream_t);
 template void degree_stack_combine<8>(CombineArgs&, hipStream_t);
+template void degree_pair_backward<8>(const PairArgs&, CombineJob*, hipStream_t);
 }  // namespace chebykan

@@ -322,6 +322,41 @@ void pick_dx(const float* x, const float* C, const float* dy, float* dx, float* 
     }
 }
 
+// ------------------------------------------------------------ two operations in one launch
+// Stack backward: the coefficient gradient of layer `up` (out <= 64, several batch slices) together with the
+// whole backward pass of the few-inputs layer below it (see dC_with_few_inputs_kernel).  The caller has
+// checked pair_eligible() and has already launched dx of the upper layer.  Both slice sums are recorded in
+// `jobs` (two entries) for the stack's single combine launch.
+template <int D, int BIC>
+void launch_pair(const PairArgs& a, const DcPlan& p, const NarrowInPlan& q, hipStream_t s)
+{
+    using Cfg = DcCfg<D, 64, 4, BIC>;
+    constexpr int lds = Cfg::LDS_BYTES > NIN_LDS_BYTES ? Cfg::LDS_BYTES : NIN_LDS_BYTES;
+    const int tiles_i = (a.I_up + BIC - 1) / BIC;
+    const DcSliceArgs up{a.x_up, a.dy_up, a.ws_up, a.B, a.I_up, a.O_up, 1, 0, tiles_i, p.slices, p.rows_per_slice};
+    const FewInputsArgs lo{a.x_lo, a.C_lo, a.dy_lo, a.dx_lo, a.ws_lo, a.B, a.I_lo, a.O_lo, q.rows_per_slice};
+    const ScopedLayer layer(a.layer_up);
+    const ScopedOps ops(OP_DC);
+    const ScopedSecond second(a.layer_up - 1, OP_DX | OP_DC);
+    launch<dC_with_few_inputs_kernel<Cfg, D>, lds, Tags<Cfg, Int<D>>>(dim3((unsigned)(q.slices + tiles_i * p.slices)), dim3(MFMA_THREADS),
+                                                                      (size_t)lds, s, up, lo, q.slices);
+}
+
+template <int D>
+void degree_pair_backward(const PairArgs& a, CombineJob* jobs, hipStream_t s)
+{
+    const DcPlan p = plan_dC(a.B, a.I_up, a.O_up, D);
+    const NarrowInPlan q = plan_narrow_in(a.B);
+    if constexpr (D == 6) {
+        if (dc_tile_features_for(a.I_up, D) == 16) launch_pair<D, 16>(a, p, q, s);
+        else launch_pair<D, dc_tile_features(D)>(a, p, q, s);
+    } else {
+        launch_pair<D, dc_tile_features(D)>(a, p, q, s);
+    }
+    jobs[0] = CombineJob{a.ws_up, a.dC_up, a.I_up, a.O_up, p.slices, 0, 0, 0};
+    jobs[1] = CombineJob{a.ws_lo, a.dC_lo, a.I_lo, a.O_lo, q.slices, 0, 0, 0};
+}
+
 // All deferred slice sums of a stack in one launch.
 template <int D>
 void degree_stack_combine(CombineArgs& a, hipStream_t s)

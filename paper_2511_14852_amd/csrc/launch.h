@@ -39,6 +39,8 @@ struct LaunchContext {
     int layer;
     int ops;
     float share;   // part of that work this launch does (an output range tiled by two launches), 1 by default
+    int layer2;    // a launch that holds two operations: the second one's layer and outputs (ops2 = 0: none)
+    int ops2;
 };
 extern thread_local LaunchContext g_launch_context;
 struct ScopedOps {
@@ -50,6 +52,19 @@ struct ScopedShare {
     float saved;
     explicit ScopedShare(float share) : saved(g_launch_context.share) { g_launch_context.share = share; }
     ~ScopedShare() { g_launch_context.share = saved; }
+};
+struct ScopedSecond {
+    int saved_layer, saved_ops;
+    ScopedSecond(int layer, int ops) : saved_layer(g_launch_context.layer2), saved_ops(g_launch_context.ops2)
+    {
+        g_launch_context.layer2 = layer;
+        g_launch_context.ops2 = ops;
+    }
+    ~ScopedSecond()
+    {
+        g_launch_context.layer2 = saved_layer;
+        g_launch_context.ops2 = saved_ops;
+    }
 };
 struct ScopedLayer {
     int saved;

@@ -62,6 +62,12 @@ CHEBYKAN_FOR_EACH_CHAIN_DEGREE(CHEBYKAN_DECLARE_CHAIN)
 thread_local CombineJob* g_deferred_combine = nullptr;
 
 template <int D>
+void degree_pair_backward(const PairArgs& a, CombineJob* jobs, hipStream_t s);
+#define CHEBYKAN_DECLARE_PAIR(n) extern template void degree_pair_backward<n>(const PairArgs&, CombineJob*, hipStream_t);
+CHEBYKAN_FOR_EACH_DEGREE(CHEBYKAN_DECLARE_PAIR)
+#undef CHEBYKAN_DECLARE_PAIR
+
+template <int D>
 void degree_stack_combine(CombineArgs& a, hipStream_t s);
 #define CHEBYKAN_DECLARE_COMBINE(n) extern template void degree_stack_combine<n>(CombineArgs&, hipStream_t);
 CHEBYKAN_FOR_EACH_DEGREE(CHEBYKAN_DECLARE_COMBINE)
@@ -227,6 +233,29 @@ bool fast_stack_backward(int n_layers, const int* widths, int d, int64_t B, cons
     jobs.n_jobs = 0;
     char* region = static_cast<char*>(ws);
     for (int l = n_layers - 1; l >= 0; --l) {
+        // dC of this layer and the whole backward of a few-inputs layer below it: one launch for both
+        if (l >= 1 && dC[l] && dC[l - 1] && grad[l - 1] && jobs.n_jobs + 2 <= COMBINE_MAX_JOBS &&
+            pair_eligible(B, widths[l], widths[l + 1], widths[l - 1], d)) {
+            const ScopedLayer layer(l);
+            if (!fast_backward(act[l], C[l], grad[l + 1], grad[l], nullptr, B, widths[l], widths[l + 1], d, region, s))
+                return false;   // cannot happen after the checks above
+            PairArgs a;
+            a.x_up = act[l]; a.dy_up = grad[l + 1]; a.dC_up = dC[l]; a.ws_up = reinterpret_cast<float*>(region);
+            a.I_up = widths[l]; a.O_up = widths[l + 1]; a.layer_up = l;
+            region += align256(backward_workspace_bytes(B, widths[l], widths[l + 1], d));
+            a.x_lo = act[l - 1]; a.C_lo = C[l - 1]; a.dy_lo = grad[l]; a.dx_lo = grad[l - 1]; a.dC_lo = dC[l - 1];
+            a.ws_lo = reinterpret_cast<float*>(region);
+            a.I_lo = widths[l - 1]; a.O_lo = widths[l]; a.B = (int)B;
+            region += align256(backward_workspace_bytes(B, widths[l - 1], widths[l], d));
+            switch (d) {
+#define CHEBYKAN_PAIR_CASE(k) case k: degree_pair_backward<k>(a, &jobs.job[jobs.n_jobs], s); break;
+                CHEBYKAN_FOR_EACH_DEGREE(CHEBYKAN_PAIR_CASE)
+#undef CHEBYKAN_PAIR_CASE
+            }
+            jobs.n_jobs += 2;
+            --l;                // the lower layer is done as well
+            continue;
+        }
         CombineJob job{nullptr, nullptr, 0, 0, 0, 0, 0, 0};
         g_deferred_combine = &job;
         const ScopedLayer layer(l);

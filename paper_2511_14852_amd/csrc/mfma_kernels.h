@@ -318,11 +318,11 @@ struct DcCfg {
 // of atomics).  grid.x = tiles_ik * tiles_o * n_slices.  Same chunk pipeline as the
 // forward kernel: loads through buffer views based at the slice (rows past the slice
 // read as zero dy, so they add nothing), producer work between MFMA issues.
+// `block` is the workgroup's linear id inside this operation (blockIdx.x when the kernel runs alone).
 template <class Cfg, class Basis = ExactBasis>
-__global__ void __launch_bounds__(MFMA_THREADS, 2)
-dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ partial,
-               int B, int I, int O, int n_tiles_o, int o_begin, int n_tiles_i, int n_slices, int rows_per_slice,
-               typename Basis::Args bargs, float* __restrict__ direct)
+__device__ __forceinline__ void dC_mfma_body(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ partial,
+                                             int B, int I, int O, int n_tiles_o, int o_begin, int n_tiles_i, int n_slices,
+                                             int rows_per_slice, typename Basis::Args bargs, float* __restrict__ direct, int block)
 {
     constexpr int D = Cfg::D, K = Cfg::K, BN = Cfg::BN, VEC = Cfg::VEC, BB = Cfg::BB, BIC = Cfg::BIC;
     constexpr int SMA = Cfg::SMA, SNB = Cfg::SNB, TM = Cfg::TM, TN = Cfg::TN, WN = Cfg::WN;
@@ -337,7 +337,7 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
     const int n_tiles = n_tiles_o * n_tiles_i;
     int tile, slice;
     {
-        const int L = blockIdx.x;
+        const int L = block;
         const int full = (n_slices / 8) * 8;               // slices in complete groups of 8
         if (L < full * n_tiles) {
             const int group = L / (8 * n_tiles), rem = L % (8 * n_tiles);
@@ -550,6 +550,16 @@ dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float*
             }
         }
     CHEBYKAN_PROBE(3);
+}
+
+template <class Cfg, class Basis = ExactBasis>
+__global__ void __launch_bounds__(MFMA_THREADS, 2)
+dC_mfma_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ partial,
+               int B, int I, int O, int n_tiles_o, int o_begin, int n_tiles_i, int n_slices, int rows_per_slice,
+               typename Basis::Args bargs, float* __restrict__ direct)
+{
+    dC_mfma_body<Cfg, Basis>(x, dy, partial, B, I, O, n_tiles_o, o_begin, n_tiles_i, n_slices, rows_per_slice, bargs, direct,
+                             (int)blockIdx.x);
 }
 
 // dC[i,o,k] = sum_s partial[s][(i,k)][o] in a fixed order: G slice groups take every G-th

@@ -26,12 +26,12 @@ constexpr int NIN_STAGE_FLOATS = 2 * NIN_ROWS * NIN_S;     // Phi^T tile + dy ti
 constexpr int NIN_G_FLOATS = 2 * NIN_ROWS * NIN_S;         // two partial G tiles (one per half of the outputs)
 constexpr int NIN_LDS_BYTES = (NIN_W_FLOATS + 2 * NIN_STAGE_FLOATS + NIN_G_FLOATS) * 4;
 
-// grid.x = n_slices.  dx or partial may be null (that gradient is skipped).
+// One workgroup = one batch slice.  dx or partial may be null (that gradient is skipped).
 template <int D, class Basis = ExactBasis>
-__global__ void __launch_bounds__(MFMA_THREADS, 2)
-bwd_narrow_in_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
-                     float* __restrict__ dx, float* __restrict__ partial, int B, int I, int O, int rows_per_slice,
-                     typename Basis::Args bargs)
+__device__ __forceinline__ void bwd_narrow_in_body(const float* __restrict__ x, const float* __restrict__ C,
+                                                   const float* __restrict__ dy, float* __restrict__ dx,
+                                                   float* __restrict__ partial, int B, int I, int O, int rows_per_slice,
+                                                   typename Basis::Args bargs, int slice)
 {
     constexpr int K = D + 1, S = NIN_S;
     constexpr int EPT = 2;   // (row, feature) elements per thread and chunk: 32 * I <= 32 * 16
@@ -45,7 +45,6 @@ bwd_narrow_in_kernel(const float* __restrict__ x, const float* __restrict__ C, c
     const int lane = t & 63, wave = t >> 6;
     const int l32 = lane & 31, h = lane >> 5;
     const int IK = I * K;
-    const int slice = blockIdx.x;
     const int64_t r_begin = (int64_t)slice * rows_per_slice;
     int64_t r_end = r_begin + rows_per_slice;
     if (r_end > B) r_end = B;
@@ -183,6 +182,48 @@ bwd_narrow_in_kernel(const float* __restrict__ x, const float* __restrict__ C, c
             if (m < IK && col < O) out[(int64_t)m * O + col] = v[r];
         }
     }
+}
+
+// grid.x = n_slices.
+template <int D, class Basis = ExactBasis>
+__global__ void __launch_bounds__(MFMA_THREADS, 2)
+bwd_narrow_in_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
+                     float* __restrict__ dx, float* __restrict__ partial, int B, int I, int O, int rows_per_slice,
+                     typename Basis::Args bargs)
+{
+    bwd_narrow_in_body<D, Basis>(x, C, dy, dx, partial, B, I, O, rows_per_slice, bargs, (int)blockIdx.x);
+}
+
+// Two independent operations of a stack's backward pass in ONE launch: the coefficient gradient of
+// layer l (matrix-core slices, see dC_mfma_kernel) and the whole backward pass of the few-inputs
+// layer l-1 below it.  Both only need dx of layer l, which an earlier kernel wrote; neither reads what
+// the other writes.  Sharing a launch lets their start-up and wind-down phases overlap and puts
+// workgroups of the vector-ALU-heavy and of the MFMA-heavy operation on the same compute units.
+// The first n_first workgroups take the few-inputs layer (the longer-running ones first).
+struct DcSliceArgs {
+    const float* x;
+    const float* dy;
+    float* partial;
+    int B, I, O, n_tiles_o, o_begin, n_tiles_i, n_slices, rows_per_slice;
+};
+struct FewInputsArgs {
+    const float* x;
+    const float* C;
+    const float* dy;
+    float* dx;
+    float* partial;
+    int B, I, O, rows_per_slice;
+};
+template <class DcCfgT, int D>
+__global__ void __launch_bounds__(MFMA_THREADS, 2)
+dC_with_few_inputs_kernel(DcSliceArgs a, FewInputsArgs b, int n_first)
+{
+    if ((int)blockIdx.x < n_first)
+        bwd_narrow_in_body<D, ExactBasis>(b.x, b.C, b.dy, b.dx, b.partial, b.B, b.I, b.O, b.rows_per_slice, ExactBasis::Args{},
+                                          (int)blockIdx.x);
+    else
+        dC_mfma_body<DcCfgT, ExactBasis>(a.x, a.dy, a.partial, a.B, a.I, a.O, a.n_tiles_o, a.o_begin, a.n_tiles_i, a.n_slices,
+                                         a.rows_per_slice, ExactBasis::Args{}, nullptr, (int)blockIdx.x - n_first);
 }
 
 }  // namespace chebykan

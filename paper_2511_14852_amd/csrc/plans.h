@@ -88,6 +88,29 @@ inline NarrowInPlan plan_narrow_in(int64_t B)
     return p;
 }
 
+// Stack backward: the coefficient gradient of a layer with at most 64 outputs and the backward pass of a
+// few-inputs layer directly below it can share one launch (both only need dx of the upper layer).  The upper
+// layer must go through the matrix-core slice kernel with partials (several slices) and small slice sums.
+inline bool pair_eligible(int64_t B, int I_up, int O_up, int I_lo, int d);
+struct PairArgs {
+    // upper layer: dC only
+    const float* x_up;
+    const float* dy_up;
+    float* dC_up;
+    float* ws_up;
+    int I_up, O_up, layer_up;
+    // lower layer: dx and dC
+    const float* x_lo;
+    const float* C_lo;
+    const float* dy_lo;
+    float* dx_lo;
+    float* dC_lo;
+    float* ws_lo;
+    int I_lo, O_lo;
+    int B;
+};
+
+
 // Output tiling: 128-wide tiles, except that a remainder beyond a multiple of 128 is handled apart.
 // 1..4 left-over columns (257 outputs) go to the streaming kernels of narrow_kernels.h, which cost
 // about a tenth of a 64-wide matrix-core tile that would compute 60 unused columns; 5..64 columns
@@ -187,6 +210,14 @@ inline DcPlan plan_dC(int64_t B, int I, int O, int d)
     p.slices = (int)((B + rows - 1) / rows);
     if (p.slices < 1) p.slices = 1;
     return p;
+}
+
+inline bool pair_eligible(int64_t B, int I_up, int O_up, int I_lo, int d)
+{
+    if (!degree_specialised(d) || O_up > 64 || O_up <= NARROW_MAX_OUT) return false;
+    if (use_narrow_in(B, I_up, O_up, d) || !use_narrow_in(B, I_lo, I_up, d)) return false;
+    if (plan_dC(B, I_up, O_up, d).slices < 2) return false;                     // a single slice writes dC itself
+    return (int64_t)((O_up + 31) / 32) * I_up <= 512 && (int64_t)((I_up + 31) / 32) * I_lo <= 512;   // sums small enough to share the combine launch
 }
 
 // Column blocks per tile: the count (1..4) that covers the I*D columns of G with the

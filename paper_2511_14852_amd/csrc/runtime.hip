@@ -120,7 +120,7 @@ struct TraceSink {
     std::string name;                   // scratch for chebykan_trace_get
 };
 thread_local TraceSink* g_trace = nullptr;
-thread_local LaunchContext g_launch_context = {0, 0, 1.0f};
+thread_local LaunchContext g_launch_context = {0, 0, 1.0f, 0, 0};
 static thread_local TraceSink* g_sink = nullptr;   // this thread's sink, collecting or not
 
 void trace_before(TraceSink* sink, const char* signature, dim3 grid, dim3 block, hipStream_t s)
@@ -195,7 +195,7 @@ int chebykan_trace_end(int* dropped)
 }
 
 chebykan_status chebykan_trace_get(int index, const char** name, unsigned grid[3], unsigned* block, int* layer, int* ops,
-                                   float* share, float* microseconds)
+                                   float* share, int* layer2, int* ops2, float* microseconds)
 {
     TraceSink* sink = g_sink;
     if (!sink || g_trace) return CHEBYKAN_ERR_NULL;               // nothing collected, or still collecting
@@ -230,6 +230,8 @@ chebykan_status chebykan_trace_get(int index, const char** name, unsigned grid[3
     if (layer) *layer = r.context.layer;
     if (ops) *ops = r.context.ops;
     if (share) *share = r.context.share;
+    if (layer2) *layer2 = r.context.layer2;
+    if (ops2) *ops2 = r.context.ops2;
     if (microseconds) {
         float ms = 0.0f;
         if (hipEventElapsedTime(&ms, sink->events[2 * (size_t)index], sink->events[2 * (size_t)index + 1]) != hipSuccess) {

@@ -46,9 +46,9 @@ def test_kernel_timing_names_and_durations():
     assert names[0].startswith("fwd_mfma_kernel<FwdCfg<6, 64")
     assert any(nm.startswith("dx2_mfma_kernel<") or nm.startswith("dx_mfma_kernel<") for nm in names)
     assert any(nm.startswith("dC_mfma_kernel<") for nm in names)
-    for name, grid, block, layer, ops, share, us in recs:
+    for name, grid, block, layer, ops, share, layer2, ops2, us in recs:
         assert grid[0] >= 1 and block in (256, 1024) and 0.5 < us < 5000.0, (name, grid, block, us)
-        assert layer == 0 and share == 1.0
+        assert layer == 0 and share == 1.0 and ops2 == 0
         if name.startswith("fwd_mfma_kernel"):
             assert ops == binding.OP_FORWARD
         if name.startswith("dx2_mfma_kernel") or name.startswith("dx_mfma_kernel"):
