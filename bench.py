@@ -76,6 +76,9 @@ def parse_args():
                     help="counter-collection mode for rocprofv3 --pmc: one plain 256 MiB device copy (the "
                          "calibration kernel of known size), then this many steps exactly as the timed region "
                          "issues them, then exit")
+    ap.add_argument("--probe-calls", action="store_true",
+                    help="with --probe: issue every layer's forward, dx-only and dC-only call on its own (the calls of "
+                         "the `calls` list) instead of the stack step, so the single-layer kernels show up too")
     return ap.parse_args()
 
 
@@ -575,7 +578,11 @@ def main():
         with torch.cuda.stream(st.stream):
             dst.copy_(src)                      # reads 256 MiB, writes 256 MiB
         for k in range(args.probe):
-            st.step(k)
+            if args.probe_calls:
+                for (_tag, _l, thunk) in st.calls(k):
+                    thunk()
+            else:
+                st.step(k)
         torch.cuda.synchronize()
         print(json.dumps({"probe_steps": args.probe, "copy_bytes_each_way": src.numel() * 4}), flush=True)
         return
