@@ -61,8 +61,8 @@ def parse_args():
                     help="skip the cold pass (whole buffer sets rotated through at least 512 MB)")
     ap.add_argument("--trace-timed", default="auto", choices=["auto", "on", "off"],
                     help="per-kernel event records inside the timed steps: on, off (a second pass over the same "
-                         "steps is traced instead), or auto = on when a step takes at least a millisecond "
-                         "(two records per kernel cost a few microseconds per step)")
+                         "steps is traced instead), or auto = on when a step takes at least five milliseconds "
+                         "(two records per kernel cost a few microseconds each: under 0.5 % of such a step)")
     ap.add_argument("--family", type=int, default=0, help="kernel family override (0 auto)")
     ap.add_argument("--basis", default="exact", choices=["exact", "lut", "lut2", "legendre", "hermite", "fourier"],
                     help="exact = Chebyshev recurrences (default); lut = the paper's table-interpolated variant "
@@ -444,7 +444,7 @@ def run_workload(name, steps, warmup, args, torch, binding, wl, brief=False):
             st.step(k)
         e1.record(st.stream)
         torch.cuda.synchronize()
-        trace_timed = args.trace_timed == "on" or (args.trace_timed == "auto" and e0.elapsed_time(e1) / 3 >= 1.0)
+        trace_timed = args.trace_timed == "on" or (args.trace_timed == "auto" and e0.elapsed_time(e1) / 3 >= 5.0)
         if trace_timed:
             binding.chebykan_trace_begin(steps * kernels_per_step_cap)
         torch.cuda.synchronize()
