@@ -26,8 +26,16 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "basis.h"
 #include "buffer_io.h"
+
+// Hides a value from the optimiser at one point of the program (emits no instruction); a host-side
+// build of the kernels may define it away.
+#ifndef CHEBYKAN_OPAQUE
+#define CHEBYKAN_OPAQUE(v) asm volatile("" : "+v"(v))
+#endif
 
 // Optional in-kernel time stamps for profiling builds (slot 0 kernel entry, 1 before the
 // chunk loop, 2 after it, 3 kernel exit); compiled out unless the includer defines it.
@@ -921,29 +929,41 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
 // accumulators it is also what folds long contractions: every 512 outputs the accumulators
 // are folded into 16 running dx values per lane.  Used whenever the feature count fills the
 // 32-feature tiles reasonably; very narrow inputs stay with dx_mfma_kernel.
+//
+// The contraction index of this product (the output o) is the fast index of both operands as
+// they lie in HBM: of a dy row, and - together with k - of a feature's coefficient run
+// C[i][o][0..K).  Both tiles are therefore copied verbatim, 16 bytes at a time, into LDS rows
+//     sA[row][BO (+4)]      sB[feature][BO*K (+4)]
+// and a lane fetches the operands of four contraction steps with 16-byte LDS reads at immediate
+// offsets from one base: one read of its dy row and K reads of its feature's run, for 4*D MFMAs.
+// Row strides are 16-byte aligned with stride/4 odd, so that consecutive lanes' 16-byte accesses
+// fall on distinct banks.  The k = 0 coefficients travel with the rest and are not used.
 template <int D_, int VEC_>
 struct Dx2Cfg {
     static constexpr int D = D_, K = D_ + 1, VEC = VEC_;
     static constexpr int BM = 128, BF = 32;
     static constexpr int BO = D <= 4 ? 32 : 16;         // outputs per contraction chunk
-    static constexpr int SAX = BO + 1;                  // odd row stride of the dy tile
-    static constexpr int SSX = BO * K + 1;              // odd slab stride: lane i reads bank i + const
-    static constexpr int A_FLOATS = (BM * SAX + 3) & ~3;
-    static constexpr int B_FLOATS = (BF * SSX + 3) & ~3;
+    static constexpr int SAX = BO + 4;                  // row stride of the dy tile
+    static constexpr int SSX = BO * K + 4;              // stride of a feature's coefficient run
+    static constexpr int A_FLOATS = BM * SAX;
+    static constexpr int B_FLOATS = BF * SSX;
     static constexpr int STAGE = A_FLOATS + B_FLOATS;
     static constexpr int LDS_BYTES = 2 * STAGE * 4;
-    static constexpr int NSTEP = BO / 2;
+    static constexpr int NSTEP = BO / 2;                // MFMA steps per chunk: a step takes one output from each lane half
+    static constexpr int NGROUP = NSTEP / 4;            // operand fetches per chunk: four steps each
     static constexpr int FOLD = FOLD_TERMS / BO;
-    // producers: two threads per dy row, eight threads per feature slab; every address is a
+    // producers: two threads per dy row, eight threads per feature run; every address is a
     // per-thread base plus a compile-time offset
     static constexpr int A_PER = BO / 2;                // dy floats per thread and chunk
-    static constexpr int A_NV = A_PER / VEC;
+    static constexpr int A_NV = A_PER / 4;
     static constexpr int RUN = BO * K;                  // floats of one feature's coefficient run
     static constexpr int C_PER = RUN / 8;               // per thread
-    static constexpr int C_NV = VEC == 4 ? C_PER / 4 : 0;        // full vectors per thread
-    static constexpr int C_NS = C_PER - C_NV * 4;                // single floats per thread
+    static constexpr int C_NV = C_PER / 4;              // full vectors per thread
+    static constexpr int C_NS = C_PER - C_NV * 4;       // single floats per thread
     static_assert(D >= 1, "degree 0 has no input gradient");
-    static_assert(A_PER % VEC == 0 && RUN % 8 == 0, "split");
+    static_assert(VEC == 4, "tiles are copied 16 bytes at a time");
+    static_assert(A_PER % 4 == 0 && RUN % 8 == 0 && NSTEP % 4 == 0, "split");
+    static_assert((SAX / 4) % 2 == 1 && (SSX / 4) % 2 == 1 && SAX % 4 == 0 && SSX % 4 == 0, "bank spread of 16-byte rows");
 };
 
 // grid.x = ceil(B/128) * ceil(I/32), feature tile fastest.
@@ -952,8 +972,8 @@ __global__ void __launch_bounds__(MFMA_THREADS, 2)
 dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
                 float* __restrict__ dx, int B, int I, int O, int n_tiles_i, int chunks_per_split, typename Basis::Args bargs)
 {
-    constexpr int D = Cfg::D, K = Cfg::K, VEC = Cfg::VEC, BF = Cfg::BF, BO = Cfg::BO;
-    constexpr int SAX = Cfg::SAX, SSX = Cfg::SSX;
+    constexpr int D = Cfg::D, K = Cfg::K, BF = Cfg::BF, BO = Cfg::BO;
+    constexpr int SAX = Cfg::SAX, SSX = Cfg::SSX, NSTEP = Cfg::NSTEP, NGROUP = Cfg::NGROUP;
     extern __shared__ __align__(16) float lds[];
     CHEBYKAN_PROBE(0);
     const Basis basis(bargs, lds + Cfg::LDS_BYTES / 4, Cfg::K, (int)threadIdx.x, MFMA_THREADS);
@@ -983,57 +1003,20 @@ dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const 
         xval[r] = f_ok ? v : 0.0f;
     }
 
-    float areg[Cfg::A_PER];
-    float creg[Cfg::C_PER];
+    bufx4 areg[Cfg::A_NV];
+    bufx4 creg[Cfg::C_NV > 0 ? Cfg::C_NV : 1];
+    float cone[Cfg::C_NS > 0 ? Cfg::C_NS : 1];
     const int pa_row = t >> 1, pa_part = t & 1;        // dy tile: row and half-row of this thread
-    const int pc_f = t >> 3, pc_part = t & 7;          // coefficient slab: feature and eighth
-    const uint32_t ga_off = (uint32_t)pa_row * (uint32_t)O + (uint32_t)(pa_part * VEC);
+    const int pc_f = t >> 3, pc_part = t & 7;          // coefficient run: feature and eighth
+    const uint32_t ga_off = (uint32_t)pa_row * (uint32_t)O + (uint32_t)(pa_part * 4);
     const uint32_t gc_off = (uint32_t)pc_f * OK_;
-    const int la_off = pa_row * SAX + pa_part * VEC;
+    const int la_off = pa_row * SAX + pa_part * 4;
     const int lc_off = pc_f * SSX;
 
-    auto load_chunk = [&](int oc) {
-#pragma unroll
-        for (int j = 0; j < Cfg::A_NV; ++j) {
-            const int kk = pa_part * VEC + j * 2 * VEC;             // column inside the chunk
-            const bool ok = oc + kk < O;
-            const uint32_t off = ga_off + (uint32_t)(oc + j * 2 * VEC);
-            if constexpr (VEC == 4) {
-                // any 4-byte aligned position: a vector may run past the end of its row, element by element
-                const bufx4 v = load4(gv, off);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) areg[j * 4 + q] = oc + kk + q < O ? v[q] : 0.0f;
-            } else {
-                const float v = load1(gv, off);
-                areg[j] = ok ? v : 0.0f;
-            }
-        }
-        const uint32_t base = gc_off + (uint32_t)oc * (uint32_t)K;
-#pragma unroll
-        for (int j = 0; j < Cfg::C_NV; ++j) {
-            const bufx4 v = load4(cv, base + (uint32_t)(pc_part * 4 + j * 32));
-            creg[j * 4 + 0] = v[0]; creg[j * 4 + 1] = v[1]; creg[j * 4 + 2] = v[2]; creg[j * 4 + 3] = v[3];
-        }
-#pragma unroll
-        for (int j = 0; j < Cfg::C_NS; ++j)
-            creg[Cfg::C_NV * 4 + j] = load1(cv, base + (uint32_t)(Cfg::C_NV * 32 + pc_part + j * 8));
-    };
-
-    auto store_chunk = [&](float* sA, float* sB) {
-#pragma unroll
-        for (int j = 0; j < Cfg::A_NV; ++j)
-#pragma unroll
-            for (int q = 0; q < VEC; ++q) sA[la_off + j * 2 * VEC + q] = areg[j * VEC + q];
-#pragma unroll
-        for (int j = 0; j < Cfg::C_NV; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) sB[lc_off + pc_part * 4 + j * 32 + q] = creg[j * 4 + q];
-#pragma unroll
-        for (int j = 0; j < Cfg::C_NS; ++j) sB[lc_off + Cfg::C_NV * 32 + pc_part + j * 8] = creg[Cfg::C_NV * 4 + j];
-    };
-
-    const int aBase = (wave * 32 + l32) * SAX + h * (BO / 2);
-    const int bBase = l32 * SSX + h * (BO / 2) * K + 1;
+    // ragged = true (below) only for the chunk that holds the end of the dy rows: a vector may run
+    // past the end of its row there, element by element
+    const int aBase = (wave * 32 + l32) * SAX + h * NSTEP;
+    const int bBase = l32 * SSX + h * NSTEP * K;
 
     floatx16 acc[D];
 #pragma unroll
@@ -1042,13 +1025,17 @@ dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const 
 #pragma unroll
     for (int r = 0; r < 16; ++r) dxacc[r] = 0.0f;
 
-    // dxacc += (1-u^2) sum_k acc_k T_k'(u), then acc = 0
+    // dxacc += (1-u^2) sum_k acc_k T_k'(u), then acc = 0.  The empty asm makes x opaque here: the
+    // derivative values of the 16 rows are recomputed at every fold instead of living in 16 x (D+1)
+    // registers across the chunk loop, where the compiler would otherwise keep them.
     auto fold = [&]() {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
+            float xr = xval[r];
+            CHEBYKAN_OPAQUE(xr);
             float slope;
             float dT[D];
-            basis.template dT<D>(xval[r], dT, slope);
+            basis.template dT<D>(xr, dT, slope);
             float sum = 0.0f;
 #pragma unroll
             for (int j = 0; j < D; ++j) sum = fmaf(acc[j][r], dT[j], sum);
@@ -1058,20 +1045,54 @@ dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const 
         for (int j = 0; j < D; ++j) acc[j] = zero16();
     };
 
-    constexpr int LA = D >= 6 ? 1 : 2;   // operand lookahead in steps; a step is already D MFMAs long
-    float aop[Cfg::NSTEP], bop[Cfg::NSTEP][D];
-    auto read_step = [&](const float* sA, const float* sB, int s) {
-        aop[s] = sA[aBase + s];
-#pragma unroll
-        for (int j = 0; j < D; ++j) bop[s][j] = sB[bBase + s * K + j];
+    // Operands of four steps (a group): 4 dy values and the 4 x K coefficients of this lane's feature,
+    // K + 1 reads of 16 bytes.  Item i of a group is its i-th read (0: dy, 1..K: coefficients).
+    floatx4 aop[2], bop[2][K];
+    auto read_item = [&](const float* sA, const float* sB, int g, int i) {
+        if (i == 0) aop[g & 1] = *reinterpret_cast<const floatx4*>(sA + aBase + 4 * g);
+        else bop[g & 1][i - 1] = *reinterpret_cast<const floatx4*>(sB + bBase + 4 * g * K + 4 * (i - 1));
     };
-    auto mfma_steps = [&](const float* sA, const float* sB, int s0, int s1) {
-#pragma unroll
-        for (int s = s0; s < s1; ++s) {
-            if (s + LA < Cfg::NSTEP) read_step(sA, sB, s + LA);
-#pragma unroll
-            for (int j = 0; j < D; ++j) acc[j] = mfma32(aop[s], bop[s][j], acc[j]);
+    // Producer work of a chunk as a list of items: first the LDS writes of chunk c+1 (held in registers
+    // since the previous iteration), then the global loads of chunk c+2 into the same registers.
+    constexpr int NW = Cfg::A_NV + Cfg::C_NV + Cfg::C_NS;
+    auto store_item = [&](float* sA, float* sB, int i) {
+        if (i < Cfg::A_NV) {
+            const floatx4 v = {areg[i][0], areg[i][1], areg[i][2], areg[i][3]};
+            *reinterpret_cast<floatx4*>(sA + la_off + i * 8) = v;
+        } else if (i < Cfg::A_NV + Cfg::C_NV) {
+            const int j = i - Cfg::A_NV;
+            const floatx4 v = {creg[j][0], creg[j][1], creg[j][2], creg[j][3]};
+            *reinterpret_cast<floatx4*>(sB + lc_off + pc_part * 4 + j * 32) = v;
+        } else {
+            const int j = i - Cfg::A_NV - Cfg::C_NV;
+            sB[lc_off + Cfg::C_NV * 32 + pc_part + j * 8] = cone[j];
         }
+    };
+    auto load_item = [&](int oc, int i, auto ragged) {
+        if (i < Cfg::A_NV) {
+            const bufx4 v = load4(gv, ga_off + (uint32_t)(oc + i * 8));   // any 4-byte aligned position
+            if constexpr (decltype(ragged)::value) {
+                const int kk = oc + pa_part * 4 + i * 8;                  // first output of this vector
+#pragma unroll
+                for (int q = 0; q < 4; ++q) areg[i][q] = kk + q < O ? v[q] : 0.0f;
+            } else {
+                areg[i] = v;
+            }
+        } else if (i < Cfg::A_NV + Cfg::C_NV) {
+            const int j = i - Cfg::A_NV;
+            creg[j] = load4(cv, gc_off + (uint32_t)oc * (uint32_t)K + (uint32_t)(pc_part * 4 + j * 32));
+        } else {
+            const int j = i - Cfg::A_NV - Cfg::C_NV;
+            cone[j] = load1(cv, gc_off + (uint32_t)oc * (uint32_t)K + (uint32_t)(Cfg::C_NV * 32 + pc_part + j * 8));
+        }
+    };
+    auto load_chunk = [&](int oc, auto ragged) {
+#pragma unroll
+        for (int i = 0; i < NW; ++i) load_item(oc, i, ragged);
+    };
+    auto store_chunk = [&](float* sA, float* sB) {
+#pragma unroll
+        for (int i = 0; i < NW; ++i) store_item(sA, sB, i);
     };
 
     // chunks past the last one are loaded and stored too (all-zero dy, stage never read).
@@ -1081,33 +1102,63 @@ dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const 
     const int c_begin = blockIdx.y * chunks_per_split;
     const int n_chunks = n_chunks_all - c_begin < chunks_per_split ? n_chunks_all - c_begin : chunks_per_split;
     dx += (int64_t)blockIdx.y * B * I;
-    load_chunk(c_begin * BO);
-    store_chunk(lds, lds + Cfg::A_FLOATS);
-    load_chunk((c_begin + 1) * BO);
-    CHEBYKAN_PROBE(1);
-    for (int c = 0; c < n_chunks; ++c) {
+
+    using Plain = std::false_type;
+    using Ragged = std::true_type;
+    // One chunk.  The instruction order is laid down by hand, one step (D independent MFMAs) at a
+    // time with a scheduling fence after each: next to a step's MFMAs sit its share of the reads of
+    // the next group, and its share of the producer items - none of them vector-ALU work, so
+    // the matrix pipe is only ever interrupted by issue slots.
+    auto chunk_body = [&](int c, auto ragged) {
         __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
-        float* sA = lds + (c & 1) * Cfg::STAGE;
+        const float* sA = lds + (c & 1) * Cfg::STAGE;
+        const float* sB = sA + Cfg::A_FLOATS;
         float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
+        float* nB = nA + Cfg::A_FLOATS;
+        const int oc_next = (c_begin + c + 2) * BO;
 #pragma unroll
-        for (int q = 0; q < LA; ++q) read_step(sA, sA + Cfg::A_FLOATS, q);
-        mfma_steps(sA, sA + Cfg::A_FLOATS, 0, Cfg::NSTEP / 2);
-        store_chunk(nA, nA + Cfg::A_FLOATS);
-        load_chunk((c_begin + c + 2) * BO);
-        mfma_steps(sA, sA + Cfg::A_FLOATS, Cfg::NSTEP / 2, Cfg::NSTEP);
-        __builtin_amdgcn_sched_group_barrier(0x100, LA * (1 + D), 0);
+        for (int i = 0; i <= K; ++i) read_item(sA, sB, 0, i);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int q = 0; q < Cfg::NSTEP * D; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // up to two LDS reads
-            __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);   // one vector-ALU
-            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+        for (int s = 0; s < NSTEP; ++s) {
+            const int g = s / 4, m = s % 4;
+            if (g + 1 < NGROUP) {
+#pragma unroll
+                for (int i = 0; i <= K; ++i)
+                    if (i * 4 / (K + 1) == m) read_item(sA, sB, g + 1, i);
+            }
+#pragma unroll
+            for (int i = 0; i < 2 * NW; ++i)
+                if (i * NSTEP / (2 * NW) == s) {
+                    if (i < NW) store_item(nA, nB, i);
+                    else load_item(oc_next, i - NW, ragged);
+                }
+#pragma unroll
+            for (int j = 0; j < D; ++j) {
+                const int e = m * K + 1 + j;           // position in the group's run: step m, degree j+1
+                acc[j] = mfma32(aop[g & 1][m], bop[g & 1][e / 4][e % 4], acc[j]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if ((c + 1) % Cfg::FOLD == 0) fold();
+    };
+
+    // the first two chunks of the range are loaded ahead of the loop; either may hold the row end
+    if ((c_begin + 1) * BO <= O) load_chunk(c_begin * BO, Plain{}); else load_chunk(c_begin * BO, Ragged{});
+    store_chunk(lds, lds + Cfg::A_FLOATS);
+    if ((c_begin + 2) * BO <= O) load_chunk((c_begin + 1) * BO, Plain{}); else load_chunk((c_begin + 1) * BO, Ragged{});
+    CHEBYKAN_PROBE(1);
+    // blocks of FOLD chunks, each closed by a fold (the last one by the final fold)
+    for (int cf = 0; cf < n_chunks; cf += Cfg::FOLD) {
+        const int c_end = cf + Cfg::FOLD < n_chunks ? cf + Cfg::FOLD : n_chunks;
+        // chunk c+2 is loaded in iteration c: plain while that chunk ends inside the rows (chunks that
+        // begin past the row end hold nothing that is read)
+        const int c_plain = O / BO - 2 - c_begin < c_end ? O / BO - 2 - c_begin : c_end;
+        int c = cf;
+        for (; c < c_plain; ++c) chunk_body(c, Plain{});
+        for (; c < c_end; ++c) chunk_body(c, Ragged{});
+        fold();
     }
     CHEBYKAN_PROBE(2);
-    fold();
 
     if (f_ok) {
 #pragma unroll
