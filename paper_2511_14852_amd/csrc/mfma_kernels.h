@@ -65,6 +65,16 @@ __device__ __forceinline__ floatx16 zero16()
     return z;
 }
 
+// One MFMA operand from LDS.  The access is volatile so that it stays a single 4-byte read whose
+// constant offset goes into the instruction's 16-bit offset field: left to itself the compiler pairs
+// operand reads into two-address reads, whose offsets reach only 1 KB, and pays for the pairing with
+// a vector add per new base - and every vector-ALU instruction in a chunk loop takes time from the
+// matrix pipe, while an LDS instruction only takes an issue slot.
+#ifndef CHEBYKAN_LDS_OPERAND
+#define CHEBYKAN_LDS_OPERAND(p) (*(const volatile __attribute__((address_space(3))) float*)(p))
+#endif
+__device__ __forceinline__ float lds_operand(const float* p) { return CHEBYKAN_LDS_OPERAND(p); }
+
 // row inside a 32x32 MFMA output block held by register r of a lane in half h
 __device__ __forceinline__ int mfma_row(int r, int h) { return 8 * (r >> 2) + 4 * h + (r & 3); }
 
@@ -94,6 +104,10 @@ struct FwdCfg {
     // (a last partial round repeats the final element in the idle threads: same value, same place)
     static constexpr int NREM = (NE - NFULL * VEC * MFMA_THREADS + MFMA_THREADS - 1) / MFMA_THREADS;
     static constexpr int NMFMA = NSTEP * TM * TN;              // MFMA instructions per chunk and wave
+    // producer work spread over the chunk's steps, or all of it ahead of the MFMAs (see DcCfg; for this
+    // kernel no difference was measured at either width)
+    static constexpr bool CLUSTER = false;
+    static_assert(VEC == 4, "coefficient runs are copied 16 bytes at a time");
     static_assert(BI % 2 == 0 && BN % 64 == 0, "tile shape");
     static_assert((BN * K) % VEC == 0, "vector width");
 };
@@ -211,25 +225,60 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
 #pragma unroll
         for (int j = 0; j < TN; ++j) { acc[i][j] = zero16(); total[i][j] = zero16(); }
 
-    // MFMA operands are read from LDS LOOKAHEAD steps before the step that uses them, so that
-    // the LDS latency is covered by earlier MFMAs of the same wave.
-    constexpr int LA = LOOKAHEAD < Cfg::NSTEP / 2 ? LOOKAHEAD : Cfg::NSTEP / 2;
-    float aop[Cfg::NSTEP][TM], bop[Cfg::NSTEP][TN];
+    // The instruction order of a chunk is laid down by hand, one step (TM x TN independent MFMAs) at a
+    // time with a scheduling fence after each.  Operands of a step are read LA steps ahead of the
+    // MFMAs that use them, as single 4-byte reads at immediate offsets (see lds_operand).
+    constexpr int NSTEP = Cfg::NSTEP;
+    constexpr int LA = LOOKAHEAD < NSTEP / 2 ? LOOKAHEAD : NSTEP / 2;
+    float aop[NSTEP][TM], bop[NSTEP][TN];
     auto read_step = [&](const float* pA, const float* pB, int s) {
         const int ih = s / K, k = s % K;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) aop[s][i] = pA[i * 32 * SA + s];
+        for (int i = 0; i < TM; ++i) aop[s][i] = lds_operand(pA + i * 32 * SA + s);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bop[s][j] = pB[ih * SS + j * 32 * KP + k];
+        for (int j = 0; j < TN; ++j) bop[s][j] = lds_operand(pB + ih * SS + j * 32 * KP + k);
     };
-    auto mfma_steps = [&](const float* pA, const float* pB, int s0, int s1) {
+    // Producer work of a chunk as a list of items: the basis of this thread's XPT elements of chunk c+1,
+    // the coefficient vectors and single floats of chunk c+1, then the loads of chunk c+2 into the same
+    // registers.
+    constexpr int XPT = Cfg::XPT, NCO = Cfg::NFULL + Cfg::NREM, NITEM = 2 * (XPT + NCO);
+    auto item = [&](float* sA, float* sB, int i0, int q) {
+        if (q < XPT) {
+            float T[D + 1];
+            basis.template T<D>(xreg[q], T);
+            float* dst = sA + xr_row * SA + (xr_f0 + q) * K;
 #pragma unroll
-        for (int s = s0; s < s1; ++s) {
-            if (s + LA < Cfg::NSTEP) read_step(pA, pB, s + LA);
+            for (int k = 0; k < K; ++k) dst[k] = T[k];
+        } else if (q < XPT + Cfg::NFULL) {
+            const int j = q - XPT;
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            if constexpr (KP == K) {
+                floatx4 v = {creg[j * 4 + 0], creg[j * 4 + 1], creg[j * 4 + 2], creg[j * 4 + 3]};
+                *reinterpret_cast<floatx4*>(sB + (e / (BN * K)) * SS + e % (BN * K)) = v;
+            } else {
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(aop[s][i], bop[s][j], acc[i][j]);
+                for (int v = 0; v < VEC; ++v) store_coeff(sB, e + v, creg[j * VEC + v]);
+            }
+        } else if (q < XPT + NCO) {
+            const int j = q - XPT - Cfg::NFULL;
+            int e = Cfg::NFULL * VEC * MFMA_THREADS + t + j * MFMA_THREADS;
+            if (e > Cfg::NE - 1) e = Cfg::NE - 1;
+            store_coeff(sB, e, creg[Cfg::NFULL * VEC + j]);
+        } else if (q < 2 * XPT + NCO) {
+            const int j = q - XPT - NCO;
+            // a feature index past I would read the next row: keep that out of the basis
+            const float v = load1(xv, x_off + (uint32_t)(i0 + j));
+            xreg[j] = (i0 + xr_f0 + j < I) ? v : 0.0f;
+        } else if (q < 2 * XPT + NCO + Cfg::NFULL) {
+            const int j = q - 2 * XPT - NCO;
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            const bufx4 v = load4(cv, (uint32_t)(i0 + e / (BN * K)) * OK_ + (uint32_t)(e % (BN * K)));
+            creg[j * 4 + 0] = v[0]; creg[j * 4 + 1] = v[1]; creg[j * 4 + 2] = v[2]; creg[j * 4 + 3] = v[3];
+        } else {
+            const int j = q - 2 * XPT - NCO - Cfg::NFULL;
+            int e = Cfg::NFULL * VEC * MFMA_THREADS + t + j * MFMA_THREADS;
+            if (e > Cfg::NE - 1) e = Cfg::NE - 1;
+            creg[Cfg::NFULL * VEC + j] = load1(cv, (uint32_t)(i0 + e / (BN * K)) * OK_ + (uint32_t)(e % (BN * K)));
         }
     };
 
@@ -248,24 +297,30 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
     for (int c = 0; c < n_chunks; ++c) {
         __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
         float* sA = lds + (c & 1) * Cfg::STAGE;
-        float* sB = sA + Cfg::A_FLOATS;
         float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
+        const float* pA = sA + aBase;
+        const float* pB = sA + Cfg::A_FLOATS + bBase;
+        const int i_next = (c_begin + c + 2) * BI;
 #pragma unroll
-        for (int q = 0; q < LA; ++q) read_step(sA + aBase, sB + bBase, q);
-        mfma_steps(sA + aBase, sB + bBase, 0, Cfg::NSTEP / 2);
-        store_chunk(nA, nA + Cfg::A_FLOATS);
-        load_chunk((c_begin + c + 2) * BI);
-        mfma_steps(sA + aBase, sB + bBase, Cfg::NSTEP / 2, Cfg::NSTEP);
-        // ask the scheduler to keep the operand reads ahead and to spread the producer
-        // instructions between the MFMA issues
-        __builtin_amdgcn_sched_group_barrier(0x100, LA * (TM + TN), 0);
+        for (int s = 0; s < LA; ++s) read_step(pA, pB, s);
+        if constexpr (Cfg::CLUSTER) {
 #pragma unroll
-        for (int q = 0; q < Cfg::NMFMA; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // up to two LDS reads
-            __builtin_amdgcn_sched_group_barrier(0x402, 2, 0);   // two vector-ALU / transcendental
-            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+            for (int q = 0; q < NITEM; ++q) item(nA, nA + Cfg::A_FLOATS, i_next, q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int s = 0; s < NSTEP; ++s) {
+            if (s + LA < NSTEP) read_step(pA, pB, s + LA);
+            if constexpr (!Cfg::CLUSTER) {
+#pragma unroll
+                for (int q = 0; q < NITEM; ++q)
+                    if (q * NSTEP / NITEM == s) item(nA, nA + Cfg::A_FLOATS, i_next, q);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(aop[s][i], bop[s][j], acc[i][j]);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if ((c + 1) % Cfg::FOLD == 0) {
 #pragma unroll
@@ -307,11 +362,15 @@ struct DcCfg {
     static constexpr int LDS_BYTES = 2 * STAGE * 4;
     static constexpr int NSTEP = BB / 2;
     static constexpr int FOLD = FOLD_TERMS / BB;
+    // Where the producer work of a chunk goes: spread over the chunk's steps, or (64-wide tiles: two
+    // accumulators per wave, where every interruption of the MFMA stream costs more) all of it ahead
+    // of one uninterrupted run of MFMAs.  Measured both ways at both widths.
+    static constexpr bool CLUSTER = BN == 64;
     static constexpr int NEA = BB * BIC;
     static constexpr int XPT = (NEA + MFMA_THREADS - 1) / MFMA_THREADS;
     static constexpr int NEB = BB * BN;
     static constexpr int GPT = NEB / VEC / MFMA_THREADS;
-    static_assert(NEB % (VEC * MFMA_THREADS) == 0, "dy tile must split evenly");
+    static_assert(VEC == 4 && NEB % (VEC * MFMA_THREADS) == 0, "dy tile must split evenly into 16-byte vectors");
     static_assert(A_FLOATS % 4 == 0, "dy tile must stay 16-byte aligned");
     static_assert(BIC >= 1 && BMR <= 128, "tile rows");
     // single-slice launches turn their tile to the caller's [i][o][k] layout in LDS: [feature][output][K|1]
@@ -437,18 +496,45 @@ __device__ __forceinline__ void dC_mfma_body(const float* __restrict__ x, const 
 #pragma unroll
         for (int j = 0; j < TN; ++j) { acc[i][j] = zero16(); total[i][j] = zero16(); }
 
-    auto mfma_steps = [&](const float* pA, const float* pB, int s0, int s1) {
+    // The instruction order of a chunk is laid down by hand, one step (TM x TN independent MFMAs) at a
+    // time with a scheduling fence after each.  Operands of a step are read LA steps ahead of the
+    // MFMAs that use them, as single 4-byte reads at immediate offsets (see lds_operand).
+    constexpr int NSTEP = Cfg::NSTEP;
+    constexpr int LA = 2;
+    float aop[NSTEP][TM], bop[NSTEP][TN];
+    auto read_step = [&](const float* pA, const float* pB, int s) {
 #pragma unroll
-        for (int s = s0; s < s1; ++s) {
-            float a[TM], b[TN];
+        for (int i = 0; i < TM; ++i) aop[s][i] = lds_operand(pA + s * SMA + i * 32);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = pA[s * SMA + i * 32];
+        for (int j = 0; j < TN; ++j) bop[s][j] = lds_operand(pB + s * SNB + j * 32);
+    };
+    // Producer work of a chunk as a list of items: item j < XPT evaluates the basis of this thread's
+    // j-th element of chunk c+1 and writes it; the next GPT items write the dy vectors of chunk c+1;
+    // then come the loads of chunk c+2 into the same registers.
+    constexpr int XPT = Cfg::XPT, GPT = Cfg::GPT, NITEM = 2 * (XPT + GPT);
+    auto item = [&](float* sA, float* sB, int c, int q) {
+        const uint32_t row0 = (uint32_t)(c + 2) * BB;
+        if (q < XPT) {
+            const int bl = xe[q] / BIC, il = xe[q] % BIC;
+            float T[D + 1];
+            basis.template T<D>(xreg[q], T);
+            float* dst = sA + bl * SMA + il * K;
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = pB[s * SNB + j * 32];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
+            for (int k = 0; k < K; ++k) dst[k] = T[k];
+        } else if (q < XPT + GPT) {
+            const int j = q - XPT;
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            floatx4 v = {greg[j * 4 + 0], greg[j * 4 + 1], greg[j * 4 + 2], greg[j * 4 + 3]};
+            *reinterpret_cast<floatx4*>(sB + (e / BN) * SNB + e % BN) = v;
+        } else if (q < 2 * XPT + GPT) {
+            const int j = q - XPT - GPT;
+            const int bl = xe[j] / BIC, il = xe[j] % BIC;
+            xreg[j] = load1(xv, (row0 + (uint32_t)bl) * (uint32_t)I + (uint32_t)il);
+        } else {
+            const int j = q - 2 * XPT - GPT;
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            const bufx4 v = load4(gv, (row0 + (uint32_t)(e / BN)) * (uint32_t)O + (uint32_t)(e % BN));
+            greg[j * 4 + 0] = v[0]; greg[j * 4 + 1] = v[1]; greg[j * 4 + 2] = v[2]; greg[j * 4 + 3] = v[3];
         }
     };
 
@@ -461,17 +547,28 @@ __device__ __forceinline__ void dC_mfma_body(const float* __restrict__ x, const 
         __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
         float* sA = lds + (c & 1) * Cfg::STAGE;
         float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
-        mfma_steps(sA + aBase, sA + Cfg::A_FLOATS + bBase, 0, Cfg::NSTEP / 2);
-        store_chunk(nA, nA + Cfg::A_FLOATS);
-        load_chunk(c + 2);
-        mfma_steps(sA + aBase, sA + Cfg::A_FLOATS + bBase, Cfg::NSTEP / 2, Cfg::NSTEP);
+        const float* pA = sA + aBase;
+        const float* pB = sA + Cfg::A_FLOATS + bBase;
 #pragma unroll
-        for (int q = 0; q < Cfg::NSTEP * TM * TN; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-            __builtin_amdgcn_sched_group_barrier(0x402, 2, 0);   // two vector-ALU / transcendental
-            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+        for (int s = 0; s < LA; ++s) read_step(pA, pB, s);
+        if constexpr (Cfg::CLUSTER) {
+#pragma unroll
+            for (int q = 0; q < NITEM; ++q) item(nA, nA + Cfg::A_FLOATS, c, q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int s = 0; s < NSTEP; ++s) {
+            if (s + LA < NSTEP) read_step(pA, pB, s + LA);
+            if constexpr (!Cfg::CLUSTER) {
+#pragma unroll
+                for (int q = 0; q < NITEM; ++q)
+                    if (q * NSTEP / NITEM == s) item(nA, nA + Cfg::A_FLOATS, c, q);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(aop[s][i], bop[s][j], acc[i][j]);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if ((c + 1) % Cfg::FOLD == 0) {
 #pragma unroll
@@ -694,7 +791,7 @@ struct DxCfg {
     static constexpr int BIX = BNC / D;                 // input features per tile
     static constexpr int BNR = BIX * D;                 // real columns (i, k=1..D)
     static constexpr int BO = 32;                       // outputs per contraction chunk
-    static constexpr int SAX = BO + 1;                  // odd row stride of the dy tile
+    static constexpr int SAX = BO + 4;                  // row stride of the dy tile: 16-byte aligned rows, stride/4 odd
     static constexpr int SSX = BO * K + (D % 32);       // slab stride = D (mod 32): column n hits bank n
     static constexpr int A_FLOATS = (BM * SAX + 3) & ~3;
     static constexpr int B_FLOATS = (BIX * SSX + 3) & ~3;
@@ -710,7 +807,8 @@ struct DxCfg {
     static constexpr int CPT = (NEB / VEC + MFMA_THREADS - 1) / MFMA_THREADS;
     static constexpr int EPT = (BM * BIX + MFMA_THREADS - 1) / MFMA_THREADS;
     static_assert(D >= 1 && BIX >= 1, "degree 0 has no input gradient");
-    static_assert((BO * K) % VEC == 0 && NEA % (VEC * MFMA_THREADS) == 0, "vector width");
+    static_assert(VEC == 4, "tiles are copied 16 bytes at a time");
+    static_assert((BO * K) % VEC == 0 && NEA % (VEC * MFMA_THREADS) == 0 && NSTEP % 4 == 0, "vector width");
 };
 
 // dx[b,i] = (1-u^2) sum_o dy[b,o] sum_{k>=1} C[i,o,k] T_k'(u),  u = tanh x[b,i]
@@ -744,8 +842,8 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
     const BufferView cv = make_view(C + (int64_t)i0 * O * K, (int64_t)(I - i0) * O * K);
     const uint32_t OK_ = (uint32_t)O * (uint32_t)K;
 
-    float areg[Cfg::APT * VEC];
-    float creg[Cfg::CPT * VEC];
+    bufx4 areg[Cfg::APT];
+    bufx4 creg[Cfg::CPT];
     // coefficient element handled in round j; past-the-end threads repeat the last vector
     int ce[Cfg::CPT];
 #pragma unroll
@@ -754,55 +852,53 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
         ce[j] = e < Cfg::NEB ? e : Cfg::NEB - VEC;
     }
 
-    auto load_chunk = [&](int oc) {
-#pragma unroll
-        for (int j = 0; j < Cfg::APT; ++j) {
-            const int e = (t + j * MFMA_THREADS) * VEC;
-            const int m = e / BO, kk = e % BO;
-            const bool ok = oc + kk < O;
-            const uint32_t off = (uint32_t)m * (uint32_t)O + (uint32_t)(oc + kk);
-            if constexpr (VEC == 4) {
-                // any 4-byte aligned position: a vector may run past the end of its row, element by element
-                const bufx4 v = load4(gv, off);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) areg[j * 4 + q] = oc + kk + q < O ? v[q] : 0.0f;
-            } else {
-                const float v = load1(gv, off);
-                areg[j] = ok ? v : 0.0f;
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < Cfg::CPT; ++j) {
+    // Producer work of a chunk as a list of items: the LDS writes of chunk c+1 (dy vectors, then
+    // coefficient vectors; held in registers since the previous iteration), then the global loads of
+    // chunk c+2 into the same registers.  ragged = true only for the chunk that holds the end of the
+    // dy rows: a vector may run past the end of its row there, element by element.
+    constexpr int APT = Cfg::APT, CPT = Cfg::CPT, NITEM = 2 * (APT + CPT);
+    auto item = [&](float* sA, float* sB, int oc, int q, auto ragged) {
+        if (q < APT) {
+            const int e = (t + q * MFMA_THREADS) * VEC;
+            const floatx4 v = {areg[q][0], areg[q][1], areg[q][2], areg[q][3]};
+            *reinterpret_cast<floatx4*>(sA + (e / BO) * SAX + e % BO) = v;
+        } else if (q < APT + CPT) {
+            const int j = q - APT;
             const int il = ce[j] / (BO * K), rem = ce[j] % (BO * K);
-            const uint32_t off = (uint32_t)il * OK_ + (uint32_t)oc * (uint32_t)K + (uint32_t)rem;
-            if constexpr (VEC == 4) {
-                const bufx4 v = load4(cv, off);
-                creg[j * 4 + 0] = v[0]; creg[j * 4 + 1] = v[1]; creg[j * 4 + 2] = v[2]; creg[j * 4 + 3] = v[3];
-            } else {
-                creg[j] = load1(cv, off);
-            }
-        }
-    };
-
-    auto store_chunk = [&](float* sA, float* sB) {
-#pragma unroll
-        for (int j = 0; j < Cfg::APT; ++j) {
-            const int e = (t + j * MFMA_THREADS) * VEC;
-            const int m = e / BO, kk = e % BO;
-#pragma unroll
-            for (int q = 0; q < VEC; ++q) sA[m * SAX + kk + q] = areg[j * VEC + q];
-        }
-#pragma unroll
-        for (int j = 0; j < Cfg::CPT; ++j) {
-            const int il = ce[j] / (BO * K), rem = ce[j] % (BO * K);
-            if constexpr (VEC == 4 && SSX % 4 == 0) {
-                floatx4 v = {creg[j * 4 + 0], creg[j * 4 + 1], creg[j * 4 + 2], creg[j * 4 + 3]};
+            if constexpr (SSX % 4 == 0) {
+                const floatx4 v = {creg[j][0], creg[j][1], creg[j][2], creg[j][3]};
                 *reinterpret_cast<floatx4*>(sB + il * SSX + rem) = v;
             } else {
 #pragma unroll
-                for (int q = 0; q < VEC; ++q) sB[il * SSX + rem + q] = creg[j * VEC + q];
+                for (int v = 0; v < VEC; ++v) sB[il * SSX + rem + v] = creg[j][v];
             }
+        } else if (q < 2 * APT + CPT) {
+            const int j = q - APT - CPT;
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            const int m = e / BO, kk = e % BO;
+            // any 4-byte aligned position
+            const bufx4 v = load4(gv, (uint32_t)m * (uint32_t)O + (uint32_t)(oc + kk));
+            if constexpr (decltype(ragged)::value) {
+#pragma unroll
+                for (int w = 0; w < 4; ++w) areg[j][w] = oc + kk + w < O ? v[w] : 0.0f;
+            } else {
+                areg[j] = v;
+            }
+        } else {
+            const int j = q - 2 * APT - CPT;
+            const int il = ce[j] / (BO * K), rem = ce[j] % (BO * K);
+            creg[j] = load4(cv, (uint32_t)il * OK_ + (uint32_t)oc * (uint32_t)K + (uint32_t)rem);
         }
+    };
+    using Plain = std::false_type;
+    using Ragged = std::true_type;
+    auto load_chunk = [&](int oc) {
+#pragma unroll
+        for (int q = APT + CPT; q < NITEM; ++q) item(nullptr, nullptr, oc, q, Ragged{});
+    };
+    auto store_chunk = [&](float* sA, float* sB) {
+#pragma unroll
+        for (int q = 0; q < APT + CPT; ++q) item(sA, sB, 0, q, Plain{});
     };
 
     const int lane = t & 63, wave = t >> 6;
@@ -829,25 +925,22 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
     for (int j = 1; j < NB; ++j) bBaseSmall = my_block == j ? bBase[j] : bBaseSmall;
     const int aBaseSmall = l32 * SAX + h * (BO / 2);
 
-    auto mfma_steps = [&](const float* sA, const float* sB, int s0, int s1) {
+    // Operands.  A lane's dy values of consecutive steps are consecutive in its tile row: four steps
+    // (a group) per 16-byte read, the next group fetched while this one is used.  Its coefficients lie
+    // K words apart: single reads at immediate offsets (see lds_operand), LA steps ahead.
+    constexpr int NSTEP = Cfg::NSTEP, NGROUP = NSTEP / 4, LA = 2;
+    constexpr int NAQ = Cfg::RB == 4 ? 1 : NACC;        // dy rows per lane
+    constexpr int NBQ = Cfg::RB == 4 ? NB : 1;          // coefficient columns per lane
+    floatx4 aq[NAQ][2];
+    float bq[NSTEP][NBQ];
+    auto read_a = [&](const float* sA, int g) {
 #pragma unroll
-        for (int s = s0; s < s1; ++s) {
-            if constexpr (Cfg::RB == 4) {
-                const float a = sA[aBase + s];
-                float b[NB];
+        for (int i = 0; i < NAQ; ++i)
+            aq[i][g & 1] = *reinterpret_cast<const floatx4*>(sA + (Cfg::RB == 4 ? aBase : aBaseSmall + i * 32 * SAX) + 4 * g);
+    };
+    auto read_b = [&](const float* sB, int s) {
 #pragma unroll
-                for (int j = 0; j < NB; ++j) b[j] = sB[bBase[j] + s * K];
-#pragma unroll
-                for (int j = 0; j < NB; ++j) acc[j] = mfma32(a, b[j], acc[j]);
-            } else {
-                const float b = sB[bBaseSmall + s * K];
-                float a[NACC];
-#pragma unroll
-                for (int i = 0; i < NACC; ++i) a[i] = sA[aBaseSmall + i * 32 * SAX + s];
-#pragma unroll
-                for (int i = 0; i < NACC; ++i) acc[i] = mfma32(a[i], b, acc[i]);
-            }
-        }
+        for (int j = 0; j < NBQ; ++j) bq[s][j] = lds_operand(sB + (Cfg::RB == 4 ? bBase[j] : bBaseSmall) + s * K);
     };
 
     // chunks past the last one are loaded and stored too (all-zero dy, stage never read).
@@ -857,29 +950,53 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
     const int c_begin = blockIdx.y * chunks_per_split;
     const int n_chunks = n_chunks_all - c_begin < chunks_per_split ? n_chunks_all - c_begin : chunks_per_split;
     dx += (int64_t)blockIdx.y * B * I;
+
+    // One chunk; the instruction order is laid down by hand, one step (NACC independent MFMAs) at a
+    // time with a scheduling fence after each.
+    auto chunk_body = [&](int c, auto ragged) {
+        __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
+        const float* sA = lds + (c & 1) * Cfg::STAGE;
+        const float* sB = sA + Cfg::A_FLOATS;
+        float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
+        float* nB = nA + Cfg::A_FLOATS;
+        const int oc_next = (c_begin + c + 2) * BO;
+        read_a(sA, 0);
+#pragma unroll
+        for (int s = 0; s < LA; ++s) read_b(sB, s);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s = 0; s < NSTEP; ++s) {
+            const int g = s / 4, m = s % 4;
+            if (m == 1 && g + 1 < NGROUP) read_a(sA, g + 1);
+            if (s + LA < NSTEP) read_b(sB, s + LA);
+#pragma unroll
+            for (int q = 0; q < NITEM; ++q)
+                if (q * NSTEP / NITEM == s) item(nA, nB, oc_next, q, ragged);
+            if constexpr (Cfg::RB == 4) {
+#pragma unroll
+                for (int j = 0; j < NB; ++j) acc[j] = mfma32(aq[0][g & 1][m], bq[s][j], acc[j]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < NACC; ++i) acc[i] = mfma32(aq[i][g & 1][m], bq[s][0], acc[i]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
     load_chunk(c_begin * BO);
     store_chunk(lds, lds + Cfg::A_FLOATS);
     load_chunk((c_begin + 1) * BO);
-    for (int c = 0; c < n_chunks; ++c) {
-        __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
-        float* sA = lds + (c & 1) * Cfg::STAGE;
-        float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
-        mfma_steps(sA, sA + Cfg::A_FLOATS, 0, Cfg::NSTEP / 2);
-        store_chunk(nA, nA + Cfg::A_FLOATS);
-        load_chunk((c_begin + c + 2) * BO);
-        mfma_steps(sA, sA + Cfg::A_FLOATS, Cfg::NSTEP / 2, Cfg::NSTEP);
+    // blocks of FOLD chunks, each closed by a fold of the accumulators
+    for (int cf = 0; cf < n_chunks; cf += Cfg::FOLD) {
+        const int c_end = cf + Cfg::FOLD < n_chunks ? cf + Cfg::FOLD : n_chunks;
+        // chunk c+2 is loaded in iteration c: plain while that chunk ends inside the rows (chunks that
+        // begin past the row end hold nothing that is read)
+        const int c_plain = O / BO - 2 - c_begin < c_end ? O / BO - 2 - c_begin : c_end;
+        int c = cf;
+        for (; c < c_plain; ++c) chunk_body(c, Plain{});
+        for (; c < c_end; ++c) chunk_body(c, Ragged{});
 #pragma unroll
-        for (int q = 0; q < Cfg::NSTEP * NACC; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-            __builtin_amdgcn_sched_group_barrier(0x402, Cfg::RB == 4 ? 2 : 4, 0);   // vector-ALU
-            __builtin_amdgcn_sched_group_barrier(0x200, Cfg::RB == 4 ? 1 : 2, 0);   // LDS writes
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
-        }
-        if ((c + 1) % Cfg::FOLD == 0) {
-#pragma unroll
-            for (int j = 0; j < NACC; ++j) { total[j] += acc[j]; acc[j] = zero16(); }
-        }
+        for (int j = 0; j < NACC; ++j) { total[j] += acc[j]; acc[j] = zero16(); }
     }
 
     // --- epilogue: G tile to LDS, then each thread finishes (row, feature) pairs

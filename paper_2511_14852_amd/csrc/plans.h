@@ -237,15 +237,16 @@ inline int dx_column_blocks(int I, int D)
 
 // The feature-per-lane kernel works on 32-feature tiles; it is taken for degrees up to 6
 // (measured slower at degree 8, where its eight accumulator blocks leave too few registers)
-// unless it needs over 5 % more MFMA blocks than the packed-column kernel (ragged or very
-// narrow feature counts).
+// unless it needs over 30 % more MFMA blocks than the packed-column kernel (very narrow feature
+// counts): per block it is the faster of the two by about a fifth (257 and 80 features at degrees 5
+// and 3 were measured both ways).
 inline bool dx_feature_per_lane(int I, int D)
 {
     if (D > 6) return false;
     const int nb = dx_column_blocks(I, D);
     const int64_t packed = (int64_t)((I + 32 * nb / D - 1) / (32 * nb / D)) * nb;
     const int64_t per_lane = (int64_t)((I + 31) / 32) * D;
-    return per_lane * 100 <= packed * 105;
+    return per_lane * 100 <= packed * 130;
 }
 
 inline bool shape_fits(int64_t B, int I, int O, int d)
