@@ -128,24 +128,61 @@ __device__ __forceinline__ void chain_mfma_layer(const float* __restrict__ x, co
 #pragma unroll
         for (int j = 0; j < TN; ++j) { acc[i][j] = zero16(); total[i][j] = zero16(); }
 
-    // operands are read from LDS LOOKAHEAD steps ahead of their MFMA, as in fwd_mfma_kernel
-    constexpr int LA = LOOKAHEAD < Cfg::NSTEP / 2 ? LOOKAHEAD : Cfg::NSTEP / 2;
-    float aop[Cfg::NSTEP][TM], bop[Cfg::NSTEP][TN];
+    // Chunk loop as in fwd_mfma_kernel: the instruction order is laid down per step, operands are read
+    // LA steps ahead as single LDS reads at immediate offsets, and the producer work of a chunk is a list
+    // of items (LDS writes of chunk c+1, each followed by the load of chunk c+2 that refills its register).
+    constexpr int NSTEP = Cfg::NSTEP;
+    constexpr int LA = LOOKAHEAD < NSTEP / 2 ? LOOKAHEAD : NSTEP / 2;
+    float aop[NSTEP][TM], bop[NSTEP][TN];
     auto read_step = [&](const float* pA, const float* pB, int s) {
         const int ih = s / K, k = s % K;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) aop[s][i] = pA[i * 32 * SA + s];
+        for (int i = 0; i < TM; ++i) aop[s][i] = lds_operand(pA + i * 32 * SA + s);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bop[s][j] = pB[ih * SS + j * 32 * KP + k];
+        for (int j = 0; j < TN; ++j) bop[s][j] = lds_operand(pB + ih * SS + j * 32 * KP + k);
     };
-    auto mfma_steps = [&](const float* pA, const float* pB, int s0, int s1) {
+    constexpr int XPT = Cfg::XPT, NCO = Cfg::NFULL + Cfg::NREM, NITEM = 2 * (XPT + NCO);
+    auto item = [&](float* sA, float* sB, int i0, int q) {
+        if (q < XPT) {
+            float T[D + 1];
+            basis.template T<D>(xreg[q], T);
+            float* dst = sA + xr_row * SA + (xr_f0 + q) * K;
 #pragma unroll
-        for (int s = s0; s < s1; ++s) {
-            if (s + LA < Cfg::NSTEP) read_step(pA, pB, s + LA);
+            for (int k = 0; k < K; ++k) dst[k] = T[k];
+        } else if (q < XPT + Cfg::NFULL) {
+            const int j = q - XPT;
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            if constexpr (KP == K) {
+                floatx4 v = {creg[j * 4 + 0], creg[j * 4 + 1], creg[j * 4 + 2], creg[j * 4 + 3]};
+                *reinterpret_cast<floatx4*>(sB + (e / (BN * K)) * SS + e % (BN * K)) = v;
+            } else {
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(aop[s][i], bop[s][j], acc[i][j]);
+                for (int v = 0; v < VEC; ++v) store_coeff(sB, e + v, creg[j * VEC + v]);
+            }
+        } else if (q < XPT + NCO) {
+            const int j = q - XPT - Cfg::NFULL;
+            int e = Cfg::NFULL * VEC * MFMA_THREADS + t + j * MFMA_THREADS;
+            if (e > Cfg::NE - 1) e = Cfg::NE - 1;
+            store_coeff(sB, e, creg[Cfg::NFULL * VEC + j]);
+        } else if (q < 2 * XPT + NCO) {
+            const int j = q - XPT - NCO;
+            const int i = i0 + xr_f0 + j;
+            if constexpr (FROM_LDS) {
+                xreg[j] = i < I ? act[xr_row * CHAIN_ACT_STRIDE + i] : 0.0f;
+            } else {
+                const float v = load1(xv, x_off + (uint32_t)(i0 + j));
+                xreg[j] = i < I ? v : 0.0f;
+            }
+        } else if (q < 2 * XPT + NCO + Cfg::NFULL) {
+            const int j = q - 2 * XPT - NCO;
+            const int e = (t + j * MFMA_THREADS) * VEC;
+            const bufx4 v = load4(cv, (uint32_t)(i0 + e / (BN * K)) * OK_ + (uint32_t)(e % (BN * K)));
+            creg[j * 4 + 0] = v[0]; creg[j * 4 + 1] = v[1]; creg[j * 4 + 2] = v[2]; creg[j * 4 + 3] = v[3];
+        } else {
+            const int j = q - 2 * XPT - NCO - Cfg::NFULL;
+            int e = Cfg::NFULL * VEC * MFMA_THREADS + t + j * MFMA_THREADS;
+            if (e > Cfg::NE - 1) e = Cfg::NE - 1;
+            creg[Cfg::NFULL * VEC + j] = load1(cv, (uint32_t)(i0 + e / (BN * K)) * OK_ + (uint32_t)(e % (BN * K)));
         }
     };
 
@@ -156,22 +193,23 @@ __device__ __forceinline__ void chain_mfma_layer(const float* __restrict__ x, co
     for (int c = 0; c < n_chunks; ++c) {
         __syncthreads();   // stage c is complete; every wave has finished reading stage c+1
         float* sA = lds + (c & 1) * Cfg::STAGE;
-        float* sB = sA + Cfg::A_FLOATS;
         float* nA = lds + ((c + 1) & 1) * Cfg::STAGE;
+        const float* pA = sA + aBase;
+        const float* pB = sA + Cfg::A_FLOATS + bBase;
+        const int i_next = (c + 2) * BI;
 #pragma unroll
-        for (int q = 0; q < LA; ++q) read_step(sA + aBase, sB + bBase, q);
-        mfma_steps(sA + aBase, sB + bBase, 0, Cfg::NSTEP / 2);
-        store_chunk(nA, nA + Cfg::A_FLOATS);
-        load_chunk((c + 2) * BI);
-        mfma_steps(sA + aBase, sB + bBase, Cfg::NSTEP / 2, Cfg::NSTEP);
-        __builtin_amdgcn_sched_group_barrier(0x100, LA * (TM + TN), 0);
+        for (int s = 0; s < LA; ++s) read_step(pA, pB, s);
 #pragma unroll
-        for (int q = 0; q < Cfg::NMFMA; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // up to two LDS reads
-            __builtin_amdgcn_sched_group_barrier(0x402, 2, 0);   // two vector-ALU / transcendental
-            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+        for (int s = 0; s < NSTEP; ++s) {
+            if (s + LA < NSTEP) read_step(pA, pB, s + LA);
+#pragma unroll
+            for (int q = 0; q < NITEM; ++q)
+                if (q * NSTEP / NITEM == s) item(nA, nA + Cfg::A_FLOATS, i_next, item_at(q, NITEM));
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(aop[s][i], bop[s][j], acc[i][j]);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if ((c + 1) % Cfg::FOLD == 0) {
 #pragma unroll

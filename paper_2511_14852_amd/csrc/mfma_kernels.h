@@ -75,6 +75,12 @@ __device__ __forceinline__ floatx16 zero16()
 #endif
 __device__ __forceinline__ float lds_operand(const float* p) { return CHEBYKAN_LDS_OPERAND(p); }
 
+// The producer work of a chunk is a list of n items: n/2 LDS writes of the next chunk's data, held in
+// registers, then the n/2 global loads that refill those registers with the chunk after.  item_at gives
+// the p-th item to issue: write 0, load 0, write 1, load 1, ... - each load follows the write that
+// frees its register, and is consumed a whole chunk later.
+__host__ __device__ constexpr int item_at(int p, int n) { return p % 2 == 0 ? p / 2 : n / 2 + p / 2; }
+
 // row inside a 32x32 MFMA output block held by register r of a lane in half h
 __device__ __forceinline__ int mfma_row(int r, int h) { return 8 * (r >> 2) + 4 * h + (r & 3); }
 
@@ -305,7 +311,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
         for (int s = 0; s < LA; ++s) read_step(pA, pB, s);
         if constexpr (Cfg::CLUSTER) {
 #pragma unroll
-            for (int q = 0; q < NITEM; ++q) item(nA, nA + Cfg::A_FLOATS, i_next, q);
+            for (int q = 0; q < NITEM; ++q) item(nA, nA + Cfg::A_FLOATS, i_next, item_at(q, NITEM));
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
@@ -314,7 +320,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
             if constexpr (!Cfg::CLUSTER) {
 #pragma unroll
                 for (int q = 0; q < NITEM; ++q)
-                    if (q * NSTEP / NITEM == s) item(nA, nA + Cfg::A_FLOATS, i_next, q);
+                    if (q * NSTEP / NITEM == s) item(nA, nA + Cfg::A_FLOATS, i_next, item_at(q, NITEM));
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -553,7 +559,7 @@ __device__ __forceinline__ void dC_mfma_body(const float* __restrict__ x, const 
         for (int s = 0; s < LA; ++s) read_step(pA, pB, s);
         if constexpr (Cfg::CLUSTER) {
 #pragma unroll
-            for (int q = 0; q < NITEM; ++q) item(nA, nA + Cfg::A_FLOATS, c, q);
+            for (int q = 0; q < NITEM; ++q) item(nA, nA + Cfg::A_FLOATS, c, item_at(q, NITEM));
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
@@ -562,7 +568,7 @@ __device__ __forceinline__ void dC_mfma_body(const float* __restrict__ x, const 
             if constexpr (!Cfg::CLUSTER) {
 #pragma unroll
                 for (int q = 0; q < NITEM; ++q)
-                    if (q * NSTEP / NITEM == s) item(nA, nA + Cfg::A_FLOATS, c, q);
+                    if (q * NSTEP / NITEM == s) item(nA, nA + Cfg::A_FLOATS, c, item_at(q, NITEM));
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -971,7 +977,7 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
             if (s + LA < NSTEP) read_b(sB, s + LA);
 #pragma unroll
             for (int q = 0; q < NITEM; ++q)
-                if (q * NSTEP / NITEM == s) item(nA, nB, oc_next, q, ragged);
+                if (q * NSTEP / NITEM == s) item(nA, nB, oc_next, item_at(q, NITEM), ragged);
             if constexpr (Cfg::RB == 4) {
 #pragma unroll
                 for (int j = 0; j < NB; ++j) acc[j] = mfma32(aq[0][g & 1][m], bq[s][j], acc[j]);
