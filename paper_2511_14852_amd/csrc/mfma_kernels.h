@@ -50,7 +50,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int MFMA_THREADS = 256;
 constexpr int FOLD_TERMS = 512;  // contraction terms between accumulator folds
-constexpr int LOOKAHEAD = 3;     // MFMA steps between an LDS operand read and its use
+constexpr int LOOKAHEAD = 2;     // MFMA steps between an LDS operand read and its use
 
 __device__ __forceinline__ floatx16 mfma32(float a, float b, floatx16 c)
 {
@@ -506,7 +506,7 @@ __device__ __forceinline__ void dC_mfma_body(const float* __restrict__ x, const 
     // time with a scheduling fence after each.  Operands of a step are read LA steps ahead of the
     // MFMAs that use them, as single 4-byte reads at immediate offsets (see lds_operand).
     constexpr int NSTEP = Cfg::NSTEP;
-    constexpr int LA = 2;
+    constexpr int LA = LOOKAHEAD;
     float aop[NSTEP][TM], bop[NSTEP][TN];
     auto read_step = [&](const float* pA, const float* pB, int s) {
 #pragma unroll
@@ -934,7 +934,7 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
     // Operands.  A lane's dy values of consecutive steps are consecutive in its tile row: four steps
     // (a group) per 16-byte read, the next group fetched while this one is used.  Its coefficients lie
     // K words apart: single reads at immediate offsets (see lds_operand), LA steps ahead.
-    constexpr int NSTEP = Cfg::NSTEP, NGROUP = NSTEP / 4, LA = 2;
+    constexpr int NSTEP = Cfg::NSTEP, NGROUP = NSTEP / 4, LA = LOOKAHEAD;
     constexpr int NAQ = Cfg::RB == 4 ? 1 : NACC;        // dy rows per lane
     constexpr int NBQ = Cfg::RB == 4 ? NB : 1;          // coefficient columns per lane
     floatx4 aq[NAQ][2];
