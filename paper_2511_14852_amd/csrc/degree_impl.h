@@ -263,7 +263,19 @@ void launch_dx(const float* x, const float* C, const float* dy, float* dx, float
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * p.feature_tiles;
     launch<dx_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES, Tags<Cfg, Basis>>(
         dim3((unsigned)tiles, (unsigned)p.split.splits), dim3(MFMA_THREADS), Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1),
-        s, x, C, dy, p.split.splits > 1 ? partial : dx, B, I, O, p.feature_tiles, p.split.chunks_per_split, ba);
+        s, x, C, dy, p.split.splits > 1 ? partial : dx, B, I, O, p.feature_tiles, p.split.chunks_per_split, 0, ba);
+}
+
+// The few features from p.tail_begin on, beside a feature-per-lane launch over the full tiles (see DxPlan).
+template <int D, int NB, class Basis>
+void launch_dx_tail(const float* x, const float* C, const float* dy, float* dx, int B, int I, int O,
+                    const DxPlan& p, const typename Basis::Args& ba, hipStream_t s)
+{
+    using Cfg = DxCfg<D, NB, 4, 4>;
+    const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * p.tail_tiles;
+    launch<dx_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES, Tags<Cfg, Basis>>(
+        dim3((unsigned)tiles, 1u), dim3(MFMA_THREADS), Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1),
+        s, x, C, dy, dx, B, I, O, p.tail_tiles, (O + Cfg::BO - 1) / Cfg::BO, p.tail_begin, ba);
 }
 
 template <int D, int VEC, class Basis>
@@ -275,7 +287,7 @@ void launch_dx2(const float* x, const float* C, const float* dy, float* dx, floa
     const int64_t tiles = (int64_t)((B + Cfg::BM - 1) / Cfg::BM) * p.feature_tiles;
     launch<dx2_mfma_kernel<Cfg, Basis>, Basis::kTable ? MAX_LDS_BYTES : Cfg::LDS_BYTES, Tags<Cfg, Basis>>(
         dim3((unsigned)tiles, (unsigned)p.split.splits), dim3(MFMA_THREADS), Cfg::LDS_BYTES + basis_lds_bytes<Basis>(ba, D + 1),
-        s, x, C, dy, p.split.splits > 1 ? partial : dx, B, I, O, p.feature_tiles, p.split.chunks_per_split, ba);
+        s, x, C, dy, p.split.splits > 1 ? partial : dx, B, I, O, p.feature_tiles, p.split.chunks_per_split, p.tail_begin, ba);
 }
 
 template <int D, class Basis>
@@ -287,7 +299,19 @@ void pick_dx(const float* x, const float* C, const float* dy, float* dx, float* 
     bool done = false;
     if constexpr (D <= 6) {   // the feature-per-lane kernel exists for these degrees only
         if (p.per_lane) {
-            launch_dx2<D, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s);
+            if (p.tail_begin < I) {
+                // full tiles here, the remaining features from a packed-column launch; the work share of
+                // each goes into the timing report
+                {
+                    ScopedShare share((float)p.tail_begin / (float)I);
+                    launch_dx2<D, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s);
+                }
+                ScopedShare share((float)(I - p.tail_begin) / (float)I);
+                if (p.tail_nb == 1) launch_dx_tail<D, 1, Basis>(x, C, dy, dx, B, I, O, p, ba, s);
+                else launch_dx_tail<D, 2, Basis>(x, C, dy, dx, B, I, O, p, ba, s);
+            } else {
+                launch_dx2<D, 4, Basis>(x, C, dy, dx, partial, B, I, O, p, ba, s);
+            }
             done = true;
         }
     }

@@ -826,7 +826,8 @@ struct DxCfg {
 template <class Cfg, class Basis = ExactBasis>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
-               float* __restrict__ dx, int B, int I, int O, int n_tiles_i, int chunks_per_split, typename Basis::Args bargs)
+               float* __restrict__ dx, int B, int I, int O, int n_tiles_i, int chunks_per_split, int i_begin,
+               typename Basis::Args bargs)
 {
     constexpr int D = Cfg::D, K = Cfg::K, VEC = Cfg::VEC, BIX = Cfg::BIX, BO = Cfg::BO, NB = Cfg::NB;
     constexpr int SAX = Cfg::SAX, SSX = Cfg::SSX, SG = Cfg::SG;
@@ -838,7 +839,7 @@ dx_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const f
     const int tile_i = blockIdx.x % n_tiles_i;
     const int tile_b = blockIdx.x / n_tiles_i;
     const int b0 = tile_b * Cfg::BM;
-    const int i0 = tile_i * BIX;
+    const int i0 = i_begin + tile_i * BIX;   // the launch covers the features from i_begin on
 
     // Views based at this tile.  Rows past B and features past I read as zero.  Outputs past O
     // (last chunk only) would read the next dy row / the next feature's slab: the dy value is
@@ -1089,11 +1090,13 @@ struct Dx2Cfg {
     static_assert((SAX / 4) % 2 == 1 && (SSX / 4) % 2 == 1 && SAX % 4 == 0 && SSX % 4 == 0, "bank spread of 16-byte rows");
 };
 
-// grid.x = ceil(B/128) * ceil(I/32), feature tile fastest.
+// grid.x = ceil(B/128) * n_tiles_i, feature tile fastest.  The launch covers features [0, i_count)
+// (all I of them, or the full tiles when a second launch takes the remainder).
 template <class Cfg, class Basis = ExactBasis>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const float* __restrict__ dy,
-                float* __restrict__ dx, int B, int I, int O, int n_tiles_i, int chunks_per_split, typename Basis::Args bargs)
+                float* __restrict__ dx, int B, int I, int O, int n_tiles_i, int chunks_per_split, int i_count,
+                typename Basis::Args bargs)
 {
     constexpr int D = Cfg::D, K = Cfg::K, BF = Cfg::BF, BO = Cfg::BO;
     constexpr int SAX = Cfg::SAX, SSX = Cfg::SSX, NSTEP = Cfg::NSTEP, NGROUP = Cfg::NGROUP;
@@ -1118,7 +1121,7 @@ dx2_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, const 
     const uint32_t OK_ = (uint32_t)O * (uint32_t)K;
 
     // this lane's 16 (row, feature) pairs: requested now, used in the epilogue
-    const bool f_ok = i0 + l32 < I;
+    const bool f_ok = i0 + l32 < i_count;
     float xval[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {

@@ -37,12 +37,13 @@ constexpr bool fourier_degree_specialised(int d) { return d == 4 || d == 6 || d 
 #define CHEBYKAN_FOR_EACH_CHAIN_DEGREE(X) X(3) X(4) X(5) X(6)
 constexpr bool chain_degree(int d) { return d >= 3 && d <= 6; }
 
-// Test hooks.  Three plan decisions depend on sizes that only large inputs reach; the host-side
+// Test hooks.  Four plan decisions depend on sizes that only large inputs reach; the host-side
 // emulation tests need them on small inputs.  A build with -DCHEBYKAN_TEST_HOOKS reads a bit mask
 // from the environment variable CHEBYKAN_TEST_HOOKS once; the product build has no such switch.
 constexpr int TEST_CHAIN_ANY_BATCH = 1;   // fuse a narrow stack's forward at any batch size
 constexpr int TEST_DIRECT_DC = 2;         // a single-slice dC is written by the slice kernel at any tile count
 constexpr int TEST_DC_MIN_256_ROWS = 4;   // small batches keep at least 256 rows per coefficient-gradient slice
+constexpr int TEST_DX_TAIL_ANY_SIZE = 8;  // a second input-gradient launch for the last few features at any amount of work
 #ifdef CHEBYKAN_TEST_HOOKS
 inline int test_hooks()
 {
@@ -369,6 +370,13 @@ struct DxPlan {
     int nb;            // column blocks of the packed kernel
     int feature_tiles;
     FwdPlan split;
+    // A feature count just above a multiple of 32 (257): the feature-per-lane launch covers features
+    // [0, tail_begin) in full tiles and a second, packed-column launch with tail_nb column blocks the
+    // few features from tail_begin on, instead of one 32-feature tile that is nearly all padding.
+    // tail_begin = I: no second launch.
+    int tail_begin;
+    int tail_nb;
+    int tail_tiles;
 };
 
 inline DxPlan plan_dx(int64_t B, int I, int O, int d)
@@ -376,9 +384,25 @@ inline DxPlan plan_dx(int64_t B, int I, int O, int d)
     DxPlan p;
     p.per_lane = d >= 1 && dx_feature_per_lane(I, d);
     p.nb = d >= 1 ? dx_column_blocks(I, d) : 1;
+    p.tail_begin = I;
+    p.tail_nb = 1;
+    p.tail_tiles = 0;
     if (p.per_lane) {
         p.feature_tiles = (I + 31) / 32;
         p.split = plan_dx_split(B, p.feature_tiles, O, d <= 4 ? 32 : 16);
+        // second launch for the remainder: only unsplit contractions (both launches write dx itself),
+        // at least two full tiles, and a remainder that fits one packed tile of at most two column blocks
+        const int rem = I % 32;
+        const bool pays = B * (int64_t)O >= ((int64_t)1 << 21) || (test_hooks() & TEST_DX_TAIL_ANY_SIZE);   // enough work for a launch
+        if (rem > 0 && I >= 64 && p.split.splits == 1 && pays) {
+            const int nb = rem * d <= 32 ? 1 : (rem * d <= 64 ? 2 : 0);
+            if (nb > 0 && nb * 3 <= d) {   // the tail's column blocks (slower per block) against the d blocks of a padded tile
+                p.tail_begin = I - rem;
+                p.tail_nb = nb;
+                p.tail_tiles = 1;
+                p.feature_tiles = I / 32;
+            }
+        }
     } else {
         const int bix = 32 * p.nb / (d >= 1 ? d : 1);
         p.feature_tiles = (I + bix - 1) / bix;

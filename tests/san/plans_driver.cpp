@@ -64,7 +64,15 @@ static void check_shape(int64_t B, int I, int O, int d)
         const DxPlan dx = plan_dx(B, I, O, d);
         CHECK(dx.nb >= 1 && dx.nb <= 4 && dx.feature_tiles >= 1, "nb=%d tiles=%d", dx.nb, dx.feature_tiles);
         const int feats = dx.per_lane ? 32 : 32 * dx.nb / d;
-        CHECK(feats >= 1 && (int64_t)dx.feature_tiles * feats >= I, "dx tiles cover the features: I=%d d=%d", I, d);
+        CHECK(dx.tail_begin >= 0 && dx.tail_begin <= I, "tail_begin=%d I=%d", dx.tail_begin, I);
+        CHECK(feats >= 1 && (int64_t)dx.feature_tiles * feats >= dx.tail_begin, "dx tiles cover the features: I=%d d=%d", I, d);
+        if (dx.tail_begin < I) {
+            // second launch: packed columns over the features past the full 32-feature tiles, contraction unsplit
+            CHECK(dx.per_lane && dx.split.splits == 1 && dx.tail_begin % 32 == 0 && dx.tail_begin >= 32, "tail_begin=%d", dx.tail_begin);
+            CHECK((dx.tail_nb == 1 || dx.tail_nb == 2) && dx.tail_tiles >= 1, "tail_nb=%d tiles=%d", dx.tail_nb, dx.tail_tiles);
+            CHECK((int64_t)dx.tail_tiles * (32 * dx.tail_nb / d) >= I - dx.tail_begin, "tail tiles cover the rest: I=%d d=%d", I, d);
+            CHECK((int64_t)dx.feature_tiles * 32 == dx.tail_begin, "full tiles end where the tail begins (I=%d)", I);
+        }
         const int co = dx.per_lane ? (d <= 4 ? 32 : 16) : 32;
         const int nco = (O + co - 1) / co;
         CHECK((int64_t)dx.split.splits * dx.split.chunks_per_split >= nco &&

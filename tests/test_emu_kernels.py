@@ -173,6 +173,14 @@ def test_single_slice_dC_written_by_the_slice_kernel(emu_driver, case):
     assert all(np.isfinite(e) and e <= 1e-5 for e in errs), errs
 
 
+@pytest.mark.parametrize("case", [(140, 65, 40, 5), (130, 73, 36, 6)], ids=lambda c: "B%d_I%d_O%d_d%d" % c)
+def test_input_gradient_with_a_second_launch_for_the_last_features(emu_driver, case):
+    """Feature counts just above a multiple of 32: feature-per-lane tiles plus a packed-column launch over
+    the last 1 and 9 features (one and two column blocks), forced here at a small amount of work."""
+    errs = _run(emu_driver, *case, family=2, tune=8)
+    assert all(np.isfinite(e) and e <= 1e-5 for e in errs), errs
+
+
 def test_generic_family_on_cpu_emulation(emu_driver):
     errs = _run(emu_driver, 37, 11, 9, 7, family=1)
     assert all(np.isfinite(e) and e <= 1e-5 for e in errs), errs

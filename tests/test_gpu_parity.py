@@ -102,6 +102,13 @@ SMALL_SHAPES = [
     (2200, 64, 132, 8),
     (900, 70, 257, 3),
     (520, 48, 133, 6),
+    # feature counts just above a multiple of 32 with enough work for a second launch: the feature-per-lane
+    # input gradient over the full tiles plus a packed-column launch for the last 1, 6 and 9 features (one and
+    # two column blocks); 75 features at degree 6 do not fit two blocks and stay with one padded tile
+    (4096, 65, 512, 5),
+    (2048, 70, 1024, 3),
+    (4096, 73, 512, 6),
+    (4096, 75, 512, 6),
     # narrow outputs with every lane-group width and several feature groups
     (333, 8, 1, 6),
     (100, 20, 2, 3),
