@@ -222,8 +222,11 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
     const int lane = t & 63, wave = t >> 6;
     const int wm = Cfg::RB == 4 ? wave >> 1 : 0, wn = Cfg::RB == 4 ? wave & 1 : wave;
     const int l32 = lane & 31, h = lane >> 5;
-    const int aBase = (wm * 64 + l32) * SA + h * (BI / 2) * K;
-    const int bBase = h * (BI / 2) * SS + (wn * WN + l32) * KP;
+    int aBase = (wm * 64 + l32) * SA + h * (BI / 2) * K;
+    int bBase = h * (BI / 2) * SS + (wn * WN + l32) * KP;
+    // one register each for the whole loop (the compiler would otherwise rebuild them from their parts per chunk)
+    CHEBYKAN_OPAQUE(aBase);
+    CHEBYKAN_OPAQUE(bBase);
 
     floatx16 acc[TM][TN], total[TM][TN];
 #pragma unroll
@@ -493,8 +496,11 @@ __device__ __forceinline__ void dC_mfma_body(const float* __restrict__ x, const 
     const int lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, h = lane >> 5;
-    const int aBase = h * (BB / 2) * SMA + wm * 64 + l32;
-    const int bBase = h * (BB / 2) * SNB + wn * WN + l32;
+    int aBase = h * (BB / 2) * SMA + wm * 64 + l32;
+    int bBase = h * (BB / 2) * SNB + wn * WN + l32;
+    // one register each for the whole loop (the compiler would otherwise rebuild them from their parts per chunk)
+    CHEBYKAN_OPAQUE(aBase);
+    CHEBYKAN_OPAQUE(bBase);
 
     floatx16 acc[TM][TN], total[TM][TN];
 #pragma unroll
@@ -518,6 +524,9 @@ __device__ __forceinline__ void dC_mfma_body(const float* __restrict__ x, const 
     // j-th element of chunk c+1 and writes it; the next GPT items write the dy vectors of chunk c+1;
     // then come the loads of chunk c+2 into the same registers.
     constexpr int XPT = Cfg::XPT, GPT = Cfg::GPT, NITEM = 2 * (XPT + GPT);
+    static_assert((MFMA_THREADS * VEC) % BN == 0, "a thread's dy vectors lie whole rows apart");
+    const int g_lds = ((t * VEC) / BN) * SNB + (t * VEC) % BN;                          // in the LDS tile
+    const uint32_t g_off = (uint32_t)((t * VEC) / BN) * (uint32_t)O + (uint32_t)((t * VEC) % BN);   // in the dy rows of a chunk
     auto item = [&](float* sA, float* sB, int c, int q) {
         const uint32_t row0 = (uint32_t)(c + 2) * BB;
         if (q < XPT) {
@@ -528,18 +537,17 @@ __device__ __forceinline__ void dC_mfma_body(const float* __restrict__ x, const 
 #pragma unroll
             for (int k = 0; k < K; ++k) dst[k] = T[k];
         } else if (q < XPT + GPT) {
+            // vector j of this thread: row (4t)/BN + j*(1024/BN), column (4t)%BN - one base, constant offsets
             const int j = q - XPT;
-            const int e = (t + j * MFMA_THREADS) * VEC;
             floatx4 v = {greg[j * 4 + 0], greg[j * 4 + 1], greg[j * 4 + 2], greg[j * 4 + 3]};
-            *reinterpret_cast<floatx4*>(sB + (e / BN) * SNB + e % BN) = v;
+            *reinterpret_cast<floatx4*>(sB + g_lds + j * (MFMA_THREADS * VEC / BN) * SNB) = v;
         } else if (q < 2 * XPT + GPT) {
             const int j = q - XPT - GPT;
             const int bl = xe[j] / BIC, il = xe[j] % BIC;
             xreg[j] = load1(xv, (row0 + (uint32_t)bl) * (uint32_t)I + (uint32_t)il);
         } else {
             const int j = q - 2 * XPT - GPT;
-            const int e = (t + j * MFMA_THREADS) * VEC;
-            const bufx4 v = load4(gv, (row0 + (uint32_t)(e / BN)) * (uint32_t)O + (uint32_t)(e % BN));
+            const bufx4 v = load4(gv, (row0 + (uint32_t)(j * (MFMA_THREADS * VEC / BN))) * (uint32_t)O + g_off);
             greg[j * 4 + 0] = v[0]; greg[j * 4 + 1] = v[1]; greg[j * 4 + 2] = v[2]; greg[j * 4 + 3] = v[3];
         }
     };
