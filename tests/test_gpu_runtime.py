@@ -107,3 +107,49 @@ def test_calls_from_two_host_threads():
         dx_ref, dC_ref = oracle.backward(x, C, dy)
         errs = (oracle.rel_err(y, oracle.forward(x, C)), oracle.rel_err(dx, dx_ref), oracle.rel_err(dC, dC_ref))
         assert all(np.isfinite(e) and e <= 1e-5 for e in errs), (k, errs)
+
+
+def test_calls_captured_in_a_graph_replay_like_eager_calls():
+    """A forward, a workspace backward and a static-scratch backward recorded into one HIP graph after
+    chebykan_init(); three replays, with eager work of the library and synchronisations between them, each
+    give what the eager calls give (the library enqueues kernels only: no memsets, no allocation, no
+    function-attribute changes at launch time)."""
+    binding.chebykan_init()
+    B, I, O, d = 700, 40, 72, 6
+    x, C, dy = _layer(B, I, O, d, 71)
+    y = torch.empty((B, O), device="cuda")
+    dx = torch.empty((B, I), device="cuda")
+    dC = torch.empty_like(C)
+    dx2 = torch.empty((B, I), device="cuda")
+    dC2 = torch.empty_like(C)
+    ws = binding.alloc_workspace(B, I, O, d)
+    s = torch.cuda.Stream()
+
+    def issue(stream):
+        binding.chebykan_forward(x, C, y, ws, stream)
+        binding.chebykan_backward(x, C, dy, dx, dC, ws, stream)
+        st = binding.raw_backward_noalloc(x.data_ptr(), C.data_ptr(), dy.data_ptr(), dx2.data_ptr(), dC2.data_ptr(),
+                                          B, I, O, d, stream.cuda_stream)
+        assert st == binding.CHEBYKAN_OK
+
+    issue(s)
+    s.synchronize()
+    eager = [t.clone() for t in (y, dx, dC, dx2, dC2)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=s):
+        issue(s)
+    other = _layer(300, 16, 16, 4, 81)
+    y_o = torch.empty((300, 16), device="cuda")
+    ws_o = binding.alloc_workspace(300, 16, 16, 4)
+    for replay in range(3):
+        for t in (y, dx, dC, dx2, dC2):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, got, want in zip(("y", "dx", "dC", "dx static", "dC static"), (y, dx, dC, dx2, dC2), eager):
+            assert torch.equal(got, want), (replay, name)
+        binding.chebykan_forward(other[0], other[1], y_o, ws_o)      # eager work between the replays
+        torch.cuda.synchronize()
+    y_ref = oracle.forward(x.cpu().numpy(), C.cpu().numpy())
+    assert oracle.rel_err(y.cpu().numpy(), y_ref) <= 1e-5
