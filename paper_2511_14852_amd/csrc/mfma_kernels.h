@@ -19,6 +19,13 @@
 // Accuracy: accumulators are folded into a second set about every 512
 // contraction terms, so that long fp32 sums keep a relative error near 1e-6.
 //
+// Chunk loops: fp32 MFMA and vector-ALU instructions do not overlap on this chip, so beyond its
+// MFMAs a loop costs what vector-ALU instructions and stalls it holds.  The bodies are written one
+// step at a time - a step is the set of independent MFMAs that share operands, closed by a
+// scheduling fence - with each step's share of operand reads, LDS writes and global loads next to
+// it in the source, operand offsets as instruction immediates, and masking of ragged ends confined
+// to the last chunks.
+//
 // MFMA operand layout used throughout (32x32x2, lane l, half h = l/32):
 //   A: lane supplies A[row = l%32][k = h];  B: lane supplies B[k = h][col = l%32];
 //   D: register r holds D[row = 8*(r/4) + 4*h + r%4][col = l%32].
@@ -123,11 +130,9 @@ struct FwdCfg {
 // The launch covers the n_tiles_o BN-wide output tiles that start at column o_begin, so a width
 // just above a multiple of 128 can be tiled with 128-wide tiles plus one 64-wide tile.
 //
-// Per chunk c: barrier; first half of chunk c's MFMA steps; generate chunk c+1 into the
-// other LDS stage; request chunk c+2 from HBM; second half of the MFMA steps.  All loads go
-// through bounds-checked buffer views (zeros beyond the tensor), so this body has no
-// branches and the vector-ALU, LDS-write and load instructions can be scheduled between
-// MFMA issues of the same wave.
+// Per chunk c: barrier; the MFMA steps of chunk c, and between them chunk c+1 generated into the
+// other LDS stage and chunk c+2 requested from HBM.  All loads go through bounds-checked buffer
+// views (zeros beyond the tensor), so this body has no branches.
 template <class Cfg, class Basis = ExactBasis>
 __global__ void __launch_bounds__(MFMA_THREADS, 2)
 fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float* __restrict__ y,
