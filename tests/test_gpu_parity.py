@@ -94,6 +94,10 @@ SMALL_SHAPES = [
     (131, 10, 100, 3),
     (260, 12, 48, 5),
     (129, 7, 520, 8),      # contraction over more than 512 outputs (accumulator fold in dx)
+    # the feature-per-lane input gradient past one fold block (both chunk widths, ragged last chunk) and at degree 2
+    (200, 64, 530, 4),
+    (150, 64, 600, 5),
+    (300, 64, 40, 2),
     (1200, 70, 40, 8),     # more than 512 rows per batch slice and more than 14 feature chunks (folds in dC, forward)
     # 1..4 columns beyond a multiple of 128: the streamed tail (forward into y, coefficient gradient through its own
     # partials into a window of dC), with one and with several batch slices, beside the 64-wide tail tile (5 columns)
