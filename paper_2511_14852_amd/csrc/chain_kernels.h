@@ -93,9 +93,7 @@ __device__ __forceinline__ void chain_mfma_layer(const float* __restrict__ x, co
         for (int j = 0; j < Cfg::XPT; ++j) {
             float T[D + 1];
             basis.template T<D>(xreg[j], T);
-            float* dst = sA + xr_row * SA + (xr_f0 + j) * K;
-#pragma unroll
-            for (int k = 0; k < K; ++k) dst[k] = T[k];
+            store_run<K, true>(sA + xr_row * SA + (xr_f0 + j) * K, T);
         }
 #pragma unroll
         for (int j = 0; j < Cfg::NFULL; ++j) {
@@ -131,24 +129,19 @@ __device__ __forceinline__ void chain_mfma_layer(const float* __restrict__ x, co
     // Chunk loop as in fwd_mfma_kernel: the instruction order is laid down per step, operands are read
     // LA steps ahead as single LDS reads at immediate offsets, and the producer work of a chunk is a list
     // of items (LDS writes of chunk c+1, each followed by the load of chunk c+2 that refills its register).
-    constexpr int NSTEP = Cfg::NSTEP;
-    constexpr int LA = LOOKAHEAD < NSTEP / 2 ? LOOKAHEAD : NSTEP / 2;
+    constexpr int NSTEP = Cfg::NSTEP, W = Cfg::W;
+    constexpr int LA = W > 1 ? W : (LOOKAHEAD < NSTEP / 2 ? LOOKAHEAD : NSTEP / 2);
+    static_assert(NSTEP % W == 0, "whole groups");
     float aop[NSTEP][TM], bop[NSTEP][TN];
     auto read_step = [&](const float* pA, const float* pB, int s) {
-        const int ih = s / K, k = s % K;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) aop[s][i] = lds_operand(pA + i * 32 * SA + s);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) bop[s][j] = lds_operand(pB + ih * SS + j * 32 * KP + k);
+        if (s % W == 0) fwd_read_group<Cfg>(pA, pB, s / W, aop, bop);
     };
     constexpr int XPT = Cfg::XPT, NCO = Cfg::NFULL + Cfg::NREM, NITEM = 2 * (XPT + NCO);
     auto item = [&](float* sA, float* sB, int i0, int q) {
         if (q < XPT) {
             float T[D + 1];
             basis.template T<D>(xreg[q], T);
-            float* dst = sA + xr_row * SA + (xr_f0 + q) * K;
-#pragma unroll
-            for (int k = 0; k < K; ++k) dst[k] = T[k];
+            store_run<K, true>(sA + xr_row * SA + (xr_f0 + q) * K, T);
         } else if (q < XPT + Cfg::NFULL) {
             const int j = q - XPT;
             const int e = (t + j * MFMA_THREADS) * VEC;

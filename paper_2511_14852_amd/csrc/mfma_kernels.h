@@ -81,6 +81,9 @@ __device__ __forceinline__ floatx16 zero16()
 #define CHEBYKAN_LDS_OPERAND(p) (*(const volatile __attribute__((address_space(3))) float*)(p))
 #endif
 __device__ __forceinline__ float lds_operand(const float* p) { return CHEBYKAN_LDS_OPERAND(p); }
+#ifndef CHEBYKAN_LDS_STORE
+#define CHEBYKAN_LDS_STORE(p, v) (*(volatile __attribute__((address_space(3))) float*)(p) = (v))
+#endif
 
 // The producer work of a chunk is a list of n items: n/2 LDS writes of the next chunk's data, held in
 // registers, then the n/2 global loads that refill those registers with the chunk after.  item_at gives
@@ -92,17 +95,73 @@ __host__ __device__ constexpr int item_at(int p, int n) { return p % 2 == 0 ? p 
 __device__ __forceinline__ int mfma_row(int r, int h) { return 8 * (r >> 2) + 4 * h + (r & 3); }
 
 // ============================================================== forward
+template <int W> struct LdsVec;
+template <> struct LdsVec<2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct LdsVec<4> { typedef float type __attribute__((ext_vector_type(4))); };
+
+// K consecutive floats to LDS.  SINGLE: one 4-byte write each at an immediate offset, through volatile
+// accesses so that they stay that way - where rows are 8- or 16-byte aligned the compiler otherwise
+// merges them into wide writes, for which the values first have to be moved into consecutive
+// registers, and only vector-ALU instructions take time from the MFMAs.
+template <int K, bool SINGLE>
+__device__ __forceinline__ void store_run(float* dst, const float (&v)[K])
+{
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        if constexpr (SINGLE) CHEBYKAN_LDS_STORE(dst + k, v[k]);
+        else dst[k] = v[k];
+    }
+}
+
+// Operands of the W steps of group g of a forward chunk (see FwdCfg::W): pA / pB are the lane's bases
+// in the Phi tile and the coefficient tile.
+template <class Cfg>
+__device__ __forceinline__ void fwd_read_group(const float* pA, const float* pB, int g, float (&aop)[Cfg::NSTEP][Cfg::TM],
+                                               float (&bop)[Cfg::NSTEP][Cfg::TN])
+{
+    constexpr int W = Cfg::W, K = Cfg::K;
+    const int s0 = W * g, ih = s0 / K, k0 = s0 % K;      // a group never straddles two features: W divides K
+    if constexpr (W > 1) {
+        typedef typename LdsVec<W>::type vec;
+#pragma unroll
+        for (int i = 0; i < Cfg::TM; ++i) {
+            const vec a = *reinterpret_cast<const vec*>(pA + i * 32 * Cfg::SA + s0);
+#pragma unroll
+            for (int w = 0; w < W; ++w) aop[s0 + w][i] = a[w];
+        }
+#pragma unroll
+        for (int j = 0; j < Cfg::TN; ++j) {
+            const vec b = *reinterpret_cast<const vec*>(pB + ih * Cfg::SS + j * 32 * Cfg::KP + k0);
+#pragma unroll
+            for (int w = 0; w < W; ++w) bop[s0 + w][j] = b[w];
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < Cfg::TM; ++i) aop[s0][i] = lds_operand(pA + i * 32 * Cfg::SA + s0);
+#pragma unroll
+        for (int j = 0; j < Cfg::TN; ++j) bop[s0][j] = lds_operand(pB + ih * Cfg::SS + j * 32 * Cfg::KP + k0);
+    }
+}
+
 // RB_ = 32-row blocks of the tile that can hold real rows.  4: the waves form a 2 x 2 grid
 // (64 rows x BN/2 outputs each).  1 or 2 (a batch of at most 32 or 64 rows, BN = 128): the four
 // waves stand side by side, 32 outputs each, and issue no MFMA for row blocks that are all padding.
 template <int D_, int BN_, int BI_, int VEC_, int RB_ = 4>
 struct FwdCfg {
-    static constexpr int D = D_, K = D_ + 1, KP = K | 1;      // KP: odd per-output stride in LDS
+    static constexpr int D = D_, K = D_ + 1;
+    // W = contraction steps fetched by one LDS read of an operand.  A lane's operands of consecutive steps
+    // are consecutive in LDS on both sides (its Phi row; the K coefficients of one feature and output), so
+    // where K is 4 or 6 they are read 16 or 8 bytes at a time: rows and runs then start on such
+    // boundaries (KP = K: the coefficient runs are copied verbatim) and strides are odd multiples of W
+    // floats, which spreads a pass of 16-byte (8 lanes) or 8-byte (16 lanes) accesses over all banks.
+    // Otherwise single reads and odd strides.
+    static constexpr int W = K == 4 ? 4 : (K == 6 ? 2 : 1);
+    static constexpr int KP = W > 1 ? K : (K | 1);             // per-output stride in LDS
     static constexpr int BM = 128, BN = BN_, BI = BI_, VEC = VEC_, RB = RB_;
     static constexpr int WN = RB == 4 ? BN / 2 : BN / 4, TM = RB == 4 ? 2 : RB, TN = WN / 32;
     static_assert(RB == 4 || ((RB == 1 || RB == 2) && BN == 128), "small-batch tiles are 128 outputs wide");
     static constexpr int CH = BI * K;                          // contraction terms per chunk
-    static constexpr int SA = CH | 1;                          // odd row stride of the Phi tile
+    static constexpr int SA = W > 1 ? CH + ((CH / W) % 2 == 0 ? W : 2 * W) : (CH | 1);   // row stride of the Phi tile
     static constexpr int SS = BN * KP;                         // stride between feature slabs
     static constexpr int A_FLOATS = (BM * SA + 3) & ~3;
     static constexpr int B_FLOATS = (BI * SS + 3) & ~3;
@@ -122,6 +181,7 @@ struct FwdCfg {
     static constexpr bool CLUSTER = false;
     static_assert(VEC == 4, "coefficient runs are copied 16 bytes at a time");
     static_assert(BI % 2 == 0 && BN % 64 == 0, "tile shape");
+    static_assert(W == 1 || (CH % W == 0 && (SA / W) % 2 == 1 && ((BI / 2) * K) % W == 0 && K % W == 0), "wide operand reads");
     static_assert((BN * K) % VEC == 0, "vector width");
 };
 
@@ -200,9 +260,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
         for (int j = 0; j < Cfg::XPT; ++j) {
             float T[D + 1];
             basis.template T<D>(xreg[j], T);
-            float* dst = sA + xr_row * SA + (xr_f0 + j) * K;
-#pragma unroll
-            for (int k = 0; k < K; ++k) dst[k] = T[k];
+            store_run<K, (Cfg::W > 1)>(sA + xr_row * SA + (xr_f0 + j) * K, T);
         }
 #pragma unroll
         for (int j = 0; j < Cfg::NFULL; ++j) {
@@ -242,15 +300,14 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
     // The instruction order of a chunk is laid down by hand, one step (TM x TN independent MFMAs) at a
     // time with a scheduling fence after each.  Operands of a step are read LA steps ahead of the
     // MFMAs that use them, as single 4-byte reads at immediate offsets (see lds_operand).
-    constexpr int NSTEP = Cfg::NSTEP;
-    constexpr int LA = LOOKAHEAD < NSTEP / 2 ? LOOKAHEAD : NSTEP / 2;
+    // Where a lane's operands are read several steps at a time (FwdCfg::W), a group of W steps is read
+    // one group ahead.
+    constexpr int NSTEP = Cfg::NSTEP, W = Cfg::W;
+    constexpr int LA = W > 1 ? W : (LOOKAHEAD < NSTEP / 2 ? LOOKAHEAD : NSTEP / 2);
+    static_assert(NSTEP % W == 0, "whole groups");
     float aop[NSTEP][TM], bop[NSTEP][TN];
     auto read_step = [&](const float* pA, const float* pB, int s) {
-        const int ih = s / K, k = s % K;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) aop[s][i] = lds_operand(pA + i * 32 * SA + s);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) bop[s][j] = lds_operand(pB + ih * SS + j * 32 * KP + k);
+        if (s % W == 0) fwd_read_group<Cfg>(pA, pB, s / W, aop, bop);
     };
     // Producer work of a chunk as a list of items: the basis of this thread's XPT elements of chunk c+1,
     // the coefficient vectors and single floats of chunk c+1, then the loads of chunk c+2 into the same
@@ -260,9 +317,7 @@ fwd_mfma_kernel(const float* __restrict__ x, const float* __restrict__ C, float*
         if (q < XPT) {
             float T[D + 1];
             basis.template T<D>(xreg[q], T);
-            float* dst = sA + xr_row * SA + (xr_f0 + q) * K;
-#pragma unroll
-            for (int k = 0; k < K; ++k) dst[k] = T[k];
+            store_run<K, (Cfg::W > 1)>(sA + xr_row * SA + (xr_f0 + q) * K, T);
         } else if (q < XPT + Cfg::NFULL) {
             const int j = q - XPT;
             const int e = (t + j * MFMA_THREADS) * VEC;

@@ -167,6 +167,7 @@ inline float emu_rcpf(float x) { return 1.0f / x; }
 #define __builtin_amdgcn_sched_barrier(mask) ((void)0)
 #define CHEBYKAN_OPAQUE(v) ((void)0)
 #define CHEBYKAN_LDS_OPERAND(p) (*(p))
+#define CHEBYKAN_LDS_STORE(p, v) (*(p) = (v))
 #define __builtin_amdgcn_rcpf emu_rcpf
 
 // wave-level exchange: every lane of the wave must take part
