@@ -535,10 +535,9 @@ __device__ __forceinline__ void dC_mfma_body(const float* __restrict__ x, const 
             const int bl = xe[j] / BIC, il = xe[j] % BIC;
             float T[D + 1];
             basis.template T<D>(xreg[j], T);
-            // SMA = BMR (mod 32): consecutive elements land K words apart across row ends too
-            float* dst = sA + bl * SMA + il * K;
-#pragma unroll
-            for (int k = 0; k < K; ++k) dst[k] = T[k];
+            // SMA = BMR (mod 32): consecutive elements land K words apart across row ends too.  At even K the
+            // compiler would pair the writes into 8-byte ones (register moves): single writes there.
+            store_run<K, (K % 2 == 0)>(sA + bl * SMA + il * K, T);
         }
 #pragma unroll
         for (int j = 0; j < Cfg::GPT; ++j) {
@@ -593,9 +592,7 @@ __device__ __forceinline__ void dC_mfma_body(const float* __restrict__ x, const 
             const int bl = xe[q] / BIC, il = xe[q] % BIC;
             float T[D + 1];
             basis.template T<D>(xreg[q], T);
-            float* dst = sA + bl * SMA + il * K;
-#pragma unroll
-            for (int k = 0; k < K; ++k) dst[k] = T[k];
+            store_run<K, (K % 2 == 0)>(sA + bl * SMA + il * K, T);
         } else if (q < XPT + GPT) {
             // vector j of this thread: row (4t)/BN + j*(1024/BN), column (4t)%BN - one base, constant offsets
             const int j = q - XPT;
